@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the fp32 matrix product on one MI355X.
+
+A step is one gemm_f32 call through the C ABI on operands already resident in HBM.  Prints one
+JSON line: GFLOP/s at 4096^3 (the compute-bound point; 1024^3 and the other workloads ride
+along under "extra"), the fraction of the fp32 MFMA peak, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = 157.3      # MI355X fp32 matrix peak: 256 CUs x 2.4 GHz x 256 flop/clk/CU
+HBM_GBS = 8000.0
+
+
+def flops_of(w) -> float:
+    b = w["batch"] or 1
+    return 2.0 * b * w["M"] * w["N"] * w["K"]
+
+
+def bytes_of(w) -> float:
+    b = w["batch"] or 1
+    return 4.0 * b * (w["M"] * w["K"] + w["K"] * w["N"] + w["M"] * w["N"])
+
+
+class Runner:
+    """Holds device operands of one workload and launches it."""
+
+    def __init__(self, name, mode="plain"):
+        import torch
+        from paper_2002_02268_amd import binding, synth
+        self.torch, self.binding, self.name, self.mode = torch, binding, name, mode
+        self.w = synth.WORKLOADS[name]
+        A, B = synth.make_operands(name)
+        self.hA, self.hB = A, B
+        self.A = torch.from_numpy(A).cuda()
+        self.B = torch.from_numpy(B).cuda()
+        w = self.w
+        shape = (w["batch"], w["M"], w["N"]) if w["batch"] else (w["M"], w["N"])
+        self.C = torch.empty(shape, device="cuda")
+        if mode == "packed":
+            self.Bp = torch.empty(binding.pack_b_size(w["N"], w["K"]) // 4, device="cuda")
+            binding.pack_b(self.B, self.Bp, transB=w["transB"])
+
+    def step(self):
+        b, w = self.binding, self.w
+        if self.mode == "packed":
+            b.gemm_f32_packed(self.A, self.Bp, self.C)
+        elif self.mode == "pack_only":
+            b.pack_b(self.B, self.Bp, transB=w["transB"])
+        elif w["batch"]:
+            b.gemm_f32_batched(self.A, self.B, self.C, transB=w["transB"])
+        else:
+            b.gemm_f32(self.A, self.B, self.C, transB=w["transB"])
+
+    def time(self, steps, warmup):
+        """(wall ms per step, event ms per step) over exactly `steps` launches."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        start.record()          # same stream the library launches on (torch's current stream)
+        for _ in range(steps):
+            self.step()
+        stop.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, start.elapsed_time(stop) / steps
+
+
+def cpu_baseline(runner, target_s=12.0):
+    """The oracle as it stands, on the host cores, on the first R rows of the workload's A."""
+    import numpy as np
+    import oracle
+    w = runner.w
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+    used = oracle.threads_used(cores)
+    A, B = runner.hA, runner.hB
+
+    def run(rows):
+        t0 = time.perf_counter()
+        oracle.gemm_f32(np.ascontiguousarray(A[:rows]), B, transB=w["transB"], nthreads=used)
+        return time.perf_counter() - t0
+
+    probe_rows = min(w["M"], used * 2)
+    t_probe = run(probe_rows)
+    rows = int(min(w["M"], max(probe_rows, probe_rows * target_s / max(t_probe, 1e-3))))
+    rows = max(used, rows // used * used)
+    t = run(rows)
+    gflops = 2.0 * rows * w["N"] * w["K"] / t / 1e9
+    return {"value": round(gflops, 3), "unit": "GFLOP/s", "cores": used, "kind": "oracle",
+            "sample": f"first {rows} of {w['M']} rows of A against all of B ({runner.name}), "
+                      f"{t:.1f} s, fp64 triple loop"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="square4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="time only --workload")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    from paper_2002_02268_amd import binding, synth
+    binding.lib()
+    torch.cuda.set_device(0)
+
+    main_run = Runner(args.workload)
+    w = main_run.w
+    wall_ms, ev_ms = main_run.time(args.steps, args.warmup)
+    gflops = flops_of(w) / (wall_ms * 1e-3) / 1e9
+    achieved_tflops = flops_of(w) / (ev_ms * 1e-3) / 1e12
+
+    extra = {}
+    if not args.no_extra:
+        plan = [("square1024", "plain", 2000), ("ragged", "plain", 1000), ("transb2048", "plain", 300),
+                ("transb2048", "packed", 300), ("batched64", "plain", 1000)]
+        for name, mode, steps in plan:
+            if name == args.workload and mode == "plain":
+                continue
+            r = Runner(name, mode)
+            wl, ev = r.time(steps, 50)
+            key = name + ("_packed" if mode == "packed" else "")
+            extra[key] = {"gflops": round(flops_of(r.w) / (wl * 1e-3) / 1e9, 1), "ms": round(wl, 5),
+                          "frac_peak": round(flops_of(r.w) / (ev * 1e-3) / 1e12 / PEAK_TFLOPS, 4)}
+            if name == "batched64":
+                extra[key]["algorithmic_GBs"] = round(bytes_of(r.w) / (ev * 1e-3) / 1e9, 1)
+            if mode == "packed":
+                r.mode = "pack_only"
+                wl, ev = r.time(steps, 20)
+                extra["pack_b_2048"] = {"ms": round(wl, 5),
+                                        "algorithmic_GBs": round(8.0 * r.w["N"] * r.w["K"] / (ev * 1e-3) / 1e9, 1)}
+            del r
+            torch.cuda.empty_cache()
+
+    out = {
+        "metric": "fp32 GEMM GFLOP/s", "value": round(gflops, 1), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "M": w["M"], "N": w["N"], "K": w["K"], "batch": w["batch"],
+                   "transB": w["transB"], "dist": w["dist"], "seed": w["seed"],
+                   "variant": binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"])},
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": None},
+        "extra": extra,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(main_run)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

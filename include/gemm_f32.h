@@ -1,0 +1,128 @@
+/*
+ * gemm_f32 -- dense fp32 matrix product C = A * op(B) on one AMD MI355X (gfx950).
+ *
+ * The operation is the one the paper's deep-learning case study optimises:
+ * Section 6.1 states it as C[x,y] = sum_k A[x,k] * B[k,y] with C of shape
+ * (M,N); Section 6.3 states the same thing as the RISE program `mm`
+ * (a :: M.K.float, b :: K.N.float, each row of a reduced against each column
+ * of b by dot = zip, multiply, reduce(+, 0)).  The reduction starts from 0, so
+ * C is overwritten (alpha = 1, beta = 0) and its previous contents, NaN
+ * included, never influence the result.
+ *
+ * Conventions shared by every entry point
+ *   - All matrix pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or retains them.
+ *   - Row-major storage with element strides (BLAS style):
+ *       A   M x K, element (i,k) at A[i*lda + k],              lda >= max(K,1)
+ *       B   transB == 0: K x N, element (k,j) at B[k*ldb + j], ldb >= max(N,1)
+ *           transB != 0: stored N x K (K x N column-major),
+ *                        element (k,j) at B[j*ldb + k],        ldb >= max(K,1)
+ *           (Section 6.3 reads b through transpose(b) as a view; transB hands
+ *            the library storage that already is that view.)
+ *       C   M x N, element (i,j) at C[i*ldc + j],              ldc >= max(N,1)
+ *   - Elements of C outside [0,M) x [0,N) (the ldc padding) are never written.
+ *   - M == 0 or N == 0: success, nothing launched.  K == 0: C is filled with
+ *     +0.0 (the empty sum).
+ *   - Work is enqueued on the stream given to gemm_f32_set_stream (default: the
+ *     null stream) and the call returns without waiting for it.
+ *   - Return value: GEMMF32_OK (0) or a negative gemmf32_status.  On error
+ *     nothing has been launched.  C must not be the same pointer as A or B
+ *     (GEMMF32_EALIAS); partially overlapping buffers are undefined behaviour.
+ *   - Dimensions are limited to 2^31 - 1 and every operand (rows * ld) to 2^40
+ *     elements (GEMMF32_EINVAL beyond that).
+ *   - Results are deterministic run to run for a fixed shape, strides and
+ *     pointer alignment; no floating-point atomics are used.
+ *   - The stream setting is one process-wide value; changing it while another
+ *     thread is inside a call is a race.  Calls themselves keep no other state.
+ */
+#ifndef GEMM_F32_H
+#define GEMM_F32_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GEMMF32_OK = 0,
+    GEMMF32_EINVAL = -1,  /* negative or oversized dimension, stride too small, bad flag */
+    GEMMF32_ENULL = -2,   /* a required pointer is NULL */
+    GEMMF32_EALIAS = -3,  /* C is the same buffer as A or B */
+    GEMMF32_ELAUNCH = -4, /* the HIP runtime refused; see gemm_f32_last_hip_error */
+    GEMMF32_ENOMEM = -5   /* reserved */
+} gemmf32_status;
+
+/*
+ * C = A * op(B)  (Section 6.1 compute expression; Section 6.3 `mm`).
+ * A, B, C: device pointers, layouts as above.  transB: 0 or 1.
+ */
+int gemm_f32(int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda,
+             const float *B, int64_t ldb,
+             float *C, int64_t ldc, int transB);
+
+/*
+ * batch independent products C_b = A_b * op(B_b), X_b = X + b*strideX
+ * (element strides; strideC must be >= the extent of one C so that outputs do
+ * not overlap -- not checked).  The paper has no batched form; this applies the
+ * Section 6.1 definition to each batch, the analogue of mapping the product
+ * over an outermost parallel dimension (mapPar, Section 6.2).
+ * batch == 0: success, nothing launched.
+ */
+int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
+                     const float *A, int64_t lda, int64_t strideA,
+                     const float *B, int64_t ldb, int64_t strideB,
+                     float *C, int64_t ldc, int64_t strideC, int transB);
+
+/*
+ * Array packing of B (Section 6.1, the packedB compute expression):
+ *     packedB[x][y][z] = B[y][x*P + z],  shape (ceil(N/P), K, P),
+ * with P = pack_b_panel_width() (the paper's 32 was its CPU's choice) and the
+ * ragged last panel filled with +0.0.
+ *   pack_b_panel_width()  P, in elements.
+ *   pack_b_size(N,K)      bytes the caller must provide for Bp
+ *                         (ceil(N/P)*K*P*4; 0 if N or K is 0 or negative).
+ *   pack_b(...)           reads op(B) (device, layout as above) and writes Bp
+ *                         (device, 16-byte aligned, caller-owned).  Bp must not
+ *                         overlap B.
+ */
+int64_t pack_b_panel_width(void);
+size_t pack_b_size(int64_t N, int64_t K);
+int pack_b(int64_t N, int64_t K, const float *B, int64_t ldb, int transB, float *Bp);
+
+/*
+ * C = A * B with B given as packedB from pack_b (Section 6.1, the compute
+ * expression rewritten on packedB: C[x,y] = sum_k A[x,k]*packedB[y/P][k][y%P]).
+ * Bp: device pointer, 16-byte aligned, produced by pack_b for the same (N,K).
+ */
+int gemm_f32_packed(int64_t M, int64_t N, int64_t K,
+                    const float *A, int64_t lda,
+                    const float *Bp,
+                    float *C, int64_t ldc);
+
+/* Stream for all later launches (a hipStream_t passed as void*; NULL = null
+ * stream).  The caller keeps ownership of the stream. */
+int gemm_f32_set_stream(void *hip_stream);
+
+/* Static, never-NULL description of a status code. */
+const char *gemm_f32_strerror(int status);
+
+/* hipError_t (as int) of the most recent GEMMF32_ELAUNCH on this thread, else 0. */
+int gemm_f32_last_hip_error(void);
+
+/*
+ * Which kernel variant the dispatcher would run for a shape, as a static
+ * string such as "t256x256x16/nn/vec" (diagnostics for benchmarks; the
+ * pointers are only inspected for alignment and may be NULL for "aligned").
+ */
+const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,
+                                  const float *A, int64_t lda,
+                                  const float *B, int64_t ldb,
+                                  const float *C, int64_t ldc, int transB);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_F32_H */

@@ -1,0 +1,155 @@
+"""ctypes binding for libgemmf32.so: same names as the C ABI in include/gemm_f32.h.
+
+Argument marshalling only.  Tensors are torch CUDA (HIP) tensors used as device
+memory; every arithmetic step runs inside the library's kernels.  There is no
+fallback: if the built library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgemmf32.so")
+
+_i64 = ctypes.c_int64
+_ptr = ctypes.c_void_p
+
+SYMBOLS = {
+    "gemm_f32": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
+    "gemm_f32_batched": (ctypes.c_int, [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64,
+                                        _ptr, _i64, _i64, ctypes.c_int]),
+    "pack_b_panel_width": (_i64, []),
+    "pack_b_size": (ctypes.c_size_t, [_i64, _i64]),
+    "pack_b": (ctypes.c_int, [_i64, _i64, _ptr, _i64, ctypes.c_int, _ptr]),
+    "gemm_f32_packed": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _ptr, _i64]),
+    "gemm_f32_set_stream": (ctypes.c_int, [_ptr]),
+    "gemm_f32_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "gemm_f32_last_hip_error": (ctypes.c_int, []),
+    "gemm_f32_variant_name": (ctypes.c_char_p, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64,
+                                                ctypes.c_int]),
+}
+
+_lib = None
+
+
+class GemmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gemm_f32 library error {status}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library (built beforehand; build it here only if no build exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build(force=True)
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(handle, name)   # AttributeError if the symbol is missing
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise GemmError(status, lib().gemm_f32_strerror(status).decode())
+
+
+def _dev_f32(t, name: str, ndim: int):
+    import torch
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda:
+        raise TypeError(f"{name} must be a float32 tensor on the GPU")
+    if t.dim() != ndim:
+        raise ValueError(f"{name} must have {ndim} dimensions")
+    if t.numel() > 0 and t.shape[-1] > 1 and t.stride(-1) != 1:
+        raise ValueError(f"{name} must have unit stride in its last dimension")
+    return t
+
+
+def _ld(t) -> int:
+    """Leading dimension (elements) of the last two axes."""
+    if t.numel() > 0 and t.shape[-2] > 1:
+        return max(int(t.stride(-2)), 1)
+    return max(int(t.shape[-1]), 1)
+
+
+def _use_current_stream(t) -> None:
+    import torch
+    lib().gemm_f32_set_stream(ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream))
+
+
+def gemm_f32(A, B, C, transB: bool = False) -> None:
+    """C[:] = A @ op(B) on the current torch stream.  A (M,K); B (K,N) or (N,K) if transB; C (M,N).
+    Row-strided views are passed through as lda / ldb / ldc."""
+    A = _dev_f32(A, "A", 2)
+    B = _dev_f32(B, "B", 2)
+    C = _dev_f32(C, "C", 2)
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    if (B.shape[1] if transB else B.shape[0]) != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32(M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), C.data_ptr(), _ld(C),
+                          int(bool(transB))))
+
+
+def gemm_f32_batched(A, B, C, transB: bool = False) -> None:
+    """C[b] = A[b] @ op(B[b]) for 3-D tensors with a leading batch axis."""
+    A = _dev_f32(A, "A", 3)
+    B = _dev_f32(B, "B", 3)
+    C = _dev_f32(C, "C", 3)
+    batch, M, K = A.shape
+    N = B.shape[1] if transB else B.shape[2]
+    if B.shape[0] != batch or (B.shape[2] if transB else B.shape[1]) != K or tuple(C.shape) != (batch, M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_batched(batch, M, N, K,
+                                  A.data_ptr(), _ld(A), int(A.stride(0)),
+                                  B.data_ptr(), _ld(B), int(B.stride(0)),
+                                  C.data_ptr(), _ld(C), int(C.stride(0)), int(bool(transB))))
+
+
+def pack_b_panel_width() -> int:
+    return int(lib().pack_b_panel_width())
+
+
+def pack_b_size(N: int, K: int) -> int:
+    return int(lib().pack_b_size(N, K))
+
+
+def pack_b(B, Bp, transB: bool = False) -> None:
+    """Writes packedB (ceil(N/P), K, P) into the float32 device tensor Bp (at least pack_b_size bytes)."""
+    B = _dev_f32(B, "B", 2)
+    N, K = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if not Bp.is_cuda or Bp.dtype != B.dtype or not Bp.is_contiguous():
+        raise TypeError("Bp must be a contiguous float32 tensor on the GPU")
+    if Bp.numel() * 4 < pack_b_size(N, K):
+        raise ValueError("Bp is smaller than pack_b_size(N, K)")
+    _use_current_stream(Bp)
+    _check(lib().pack_b(N, K, B.data_ptr(), _ld(B), int(bool(transB)), Bp.data_ptr()))
+
+
+def gemm_f32_packed(A, Bp, C) -> None:
+    """C[:] = A @ B with B given as the packed buffer written by pack_b for the same (N, K)."""
+    A = _dev_f32(A, "A", 2)
+    C = _dev_f32(C, "C", 2)
+    M, K = A.shape
+    N = C.shape[1]
+    if C.shape[0] != M:
+        raise ValueError("shape mismatch")
+    if not Bp.is_cuda or not Bp.is_contiguous() or Bp.numel() * 4 < pack_b_size(N, K):
+        raise ValueError("Bp does not hold a packed (N, K) operand")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_packed(M, N, K, A.data_ptr(), _ld(A), Bp.data_ptr(), C.data_ptr(), _ld(C)))
+
+
+def variant_name(M: int, N: int, K: int, lda=None, ldb=None, ldc=None, transB: bool = False) -> str:
+    lda = lda or max(K, 1)
+    ldb = ldb or max(K if transB else N, 1)
+    ldc = ldc or max(N, 1)
+    return lib().gemm_f32_variant_name(M, N, K, None, lda, None, ldb, None, ldc, int(bool(transB))).decode()

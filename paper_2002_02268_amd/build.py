@@ -1,0 +1,38 @@
+"""Builds the HIP library in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_HERE, "csrc")
+LIB = os.path.join(_HERE, "libgemmf32.so")
+SOURCES = ["gemm_f32.hip"]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    # packed-fp32 VALU forms are kept out of the generated code
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def sources():
+    return [os.path.join(CSRC, s) for s in SOURCES]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    deps.append(os.path.join(os.path.dirname(_HERE), "include", "gemm_f32.h"))
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force: bool = True, extra_flags=()) -> str:
+    """Compile csrc/ into libgemmf32.so.  Raises CalledProcessError on failure."""
+    if force or stale():
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *sources()]
+        subprocess.run(cmd, check=True)
+    return LIB

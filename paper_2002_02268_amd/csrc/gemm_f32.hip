@@ -1,0 +1,270 @@
+// C-ABI entry points and dispatch for the fp32 matrix product on gfx950.
+// Argument checks, choice of tile variant from the shape, launch on the configured stream.
+#include "../../include/gemm_f32.h"
+
+#include <type_traits>
+
+#include "gemm_kernels.hpp"
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+using namespace gemmf32;
+
+namespace {
+
+hipStream_t g_stream = nullptr;
+thread_local int g_last_hip_error = 0;
+
+constexpr int64_t kMaxDim = 2147483647LL;
+constexpr int64_t kMaxElems = 1LL << 40;
+
+int fail_hip(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return GEMMF32_ELAUNCH;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- variants -------------------------------------------------------------------------------
+enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, NUM_TILES = 4 };
+
+struct TileShape { int bm, bn; const char *name; };
+const TileShape kShapes[NUM_TILES] = {
+    {256, 256, "t256x256x16"}, {128, 128, "t128x128x16"}, {64, 64, "t64x64x32"}, {64, 64, "t64x64x64s1"}};
+
+template <int BMODE, bool VEC> struct Variants {
+    typedef Tile<256, 256, 16, 2, 2, BMODE, VEC, 2> Big;
+    typedef Tile<128, 128, 16, 2, 2, BMODE, VEC, 2> Mid;
+    typedef Tile<64, 64, 32, 2, 2, BMODE, VEC, 2> Small;
+    typedef Tile<64, 64, 64, 2, 2, BMODE, VEC, 1> Batch64;
+};
+
+template <class T> int launch(const KArgs &a)
+{
+    static bool attr_set = false;  // per instantiation; benign if set twice
+    auto kern = gemm_kernel<T>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return fail_hip(e);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), T::LDS_BYTES, g_stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
+}
+
+template <int BMODE, bool VEC> int launch_tile(int tile, const KArgs &a)
+{
+    typedef Variants<BMODE, VEC> V;
+    switch (tile) {
+    case T256: return launch<typename V::Big>(a);
+    case T128: return launch<typename V::Mid>(a);
+    case T64: return launch<typename V::Small>(a);
+    default: return launch<typename V::Batch64>(a);
+    }
+}
+
+int launch_variant(int bmode, bool vec, int tile, const KArgs &a)
+{
+    switch (bmode) {
+    case B_NN: return vec ? launch_tile<B_NN, true>(tile, a) : launch_tile<B_NN, false>(tile, a);
+    case B_NT: return vec ? launch_tile<B_NT, true>(tile, a) : launch_tile<B_NT, false>(tile, a);
+    default: return vec ? launch_tile<B_PACKED, true>(tile, a) : launch_tile<B_PACKED, false>(tile, a);
+    }
+}
+
+int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Tile choice: the largest tile that still gives every compute unit (256 of them) work.
+int choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
+{
+    if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
+        int t = std::atoi(f);
+        if (t >= 0 && t < NUM_TILES) return t;
+    }
+    if (M <= 64 && N <= 64 && K <= 64) return TB64;
+    const int64_t t256 = batch * cdiv(M, 256) * cdiv(N, 256);
+    const int64_t t128 = batch * cdiv(M, 128) * cdiv(N, 128);
+    if (t256 >= 200) return T256;
+    if (t128 >= 200) return T128;
+    return T64;
+}
+
+int choose_group_m(int tiles_m, int tiles_n, int64_t total)
+{
+    // each XCD walks total/8 consecutive tiles; aim for a square run
+    int64_t per_xcd = total / 8;
+    if (per_xcd < 1) per_xcd = 1;
+    int g = 1;
+    while ((int64_t)(2 * g) * (2 * g) <= per_xcd && 2 * g <= tiles_m) g *= 2;
+    (void)tiles_n;
+    return g;
+}
+
+struct Plan {
+    int status;
+    bool launch;
+    int bmode, tile;
+    bool vec;
+    KArgs args;
+};
+
+int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                 const float *B, const float *C, int64_t ldc)
+{
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return GEMMF32_EINVAL;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || batch > kMaxDim) return GEMMF32_EINVAL;
+    if (lda < (K > 1 ? K : 1) || ldc < (N > 1 ? N : 1)) return GEMMF32_EINVAL;
+    if (M * lda > kMaxElems || M * ldc > kMaxElems) return GEMMF32_EINVAL;
+    const bool has_out = batch > 0 && M > 0 && N > 0;
+    if (has_out && C == nullptr) return GEMMF32_ENULL;
+    if (has_out && K > 0 && (A == nullptr || B == nullptr)) return GEMMF32_ENULL;
+    if (has_out && (C == A || C == B)) return GEMMF32_EALIAS;
+    return GEMMF32_OK;
+}
+
+Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, int64_t sA,
+               const float *B, int64_t ldb, int64_t sB, float *C, int64_t ldc, int64_t sC, int bmode)
+{
+    Plan pl;
+    std::memset(&pl, 0, sizeof(pl));
+    pl.bmode = bmode;
+    pl.status = check_common(batch, M, N, K, A, lda, B, C, ldc);
+    if (pl.status != GEMMF32_OK) return pl;
+    if (bmode == B_NN && ldb < (N > 1 ? N : 1)) { pl.status = GEMMF32_EINVAL; return pl; }
+    if (bmode == B_NT && ldb < (K > 1 ? K : 1)) { pl.status = GEMMF32_EINVAL; return pl; }
+    if (bmode != B_PACKED && (bmode == B_NN ? K : N) * ldb > kMaxElems) { pl.status = GEMMF32_EINVAL; return pl; }
+    if (batch > 1 && (sA < 0 || sB < 0 || sC < 0)) { pl.status = GEMMF32_EINVAL; return pl; }
+    if (batch == 0 || M == 0 || N == 0) return pl;  // nothing to do
+
+    pl.tile = choose_tile(batch, M, N, K);
+    const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
+    const int64_t tiles_m = cdiv(M, bm), tiles_n = cdiv(N, bn);
+    const int64_t total = batch * tiles_m * tiles_n;
+    if (total > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
+
+    bool vec = aligned16(A) && aligned16(C) && lda % 4 == 0 && ldc % 4 == 0;
+    if (bmode != B_PACKED) vec = vec && aligned16(B) && ldb % 4 == 0;
+    if (batch > 1) vec = vec && sA % 4 == 0 && sC % 4 == 0 && (bmode == B_PACKED || sB % 4 == 0);
+    pl.vec = vec;
+
+    KArgs &a = pl.args;
+    a.A = A; a.B = B; a.C = C;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.sA = sA; a.sB = sB; a.sC = sC;
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.tiles_per_batch = (int)(tiles_m * tiles_n);
+    a.total_tiles = (int)total;
+    a.group_m = choose_group_m((int)tiles_m, (int)tiles_n, batch > 1 ? tiles_m * tiles_n : total);
+    a.n_padded = (int)(cdiv(N, kPanel) * kPanel);
+    pl.launch = true;
+    return pl;
+}
+
+int run_plan(const Plan &pl)
+{
+    if (pl.status != GEMMF32_OK) return pl.status;
+    if (!pl.launch) return GEMMF32_OK;
+    return launch_variant(pl.bmode, pl.vec, pl.tile, pl.args);
+}
+
+thread_local char g_variant_buf[64];
+
+}  // namespace
+
+extern "C" {
+
+int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, int transB)
+{
+    if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    return run_plan(make_plan(1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, transB ? B_NT : B_NN));
+}
+
+int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                     int64_t strideA, const float *B, int64_t ldb, int64_t strideB, float *C, int64_t ldc,
+                     int64_t strideC, int transB)
+{
+    if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    return run_plan(make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
+                              transB ? B_NT : B_NN));
+}
+
+int64_t pack_b_panel_width(void) { return kPanel; }
+
+size_t pack_b_size(int64_t N, int64_t K)
+{
+    if (N <= 0 || K <= 0) return 0;
+    return (size_t)(cdiv(N, kPanel) * K * kPanel) * sizeof(float);
+}
+
+int pack_b(int64_t N, int64_t K, const float *B, int64_t ldb, int transB, float *Bp)
+{
+    if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    if (N < 0 || K < 0 || N > kMaxDim || K > kMaxDim) return GEMMF32_EINVAL;
+    if (transB ? ldb < (K > 1 ? K : 1) : ldb < (N > 1 ? N : 1)) return GEMMF32_EINVAL;
+    if ((transB ? N : K) * ldb > kMaxElems) return GEMMF32_EINVAL;
+    if (N == 0 || K == 0) return GEMMF32_OK;
+    if (B == nullptr || Bp == nullptr) return GEMMF32_ENULL;
+    if (B == Bp) return GEMMF32_EALIAS;
+    if (!aligned16(Bp)) return GEMMF32_EINVAL;
+    const int64_t total_f4 = cdiv(N, kPanel) * K * (kPanel / 4);
+    const int64_t blocks = cdiv(total_f4, 256);
+    if (blocks > kMaxDim) return GEMMF32_EINVAL;
+    hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)blocks), dim3(256), 0, g_stream, B, Bp, (int)N, (int)K, ldb,
+                       transB, total_f4);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
+}
+
+int gemm_f32_packed(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *Bp, float *C,
+                    int64_t ldc)
+{
+    if (Bp != nullptr && !aligned16(Bp)) return GEMMF32_EINVAL;
+    return run_plan(make_plan(1, M, N, K, A, lda, 0, Bp, kPanel, 0, C, ldc, 0, B_PACKED));
+}
+
+int gemm_f32_set_stream(void *hip_stream)
+{
+    g_stream = reinterpret_cast<hipStream_t>(hip_stream);
+    return GEMMF32_OK;
+}
+
+const char *gemm_f32_strerror(int status)
+{
+    switch (status) {
+    case GEMMF32_OK: return "ok";
+    case GEMMF32_EINVAL: return "invalid dimension, stride, alignment or flag";
+    case GEMMF32_ENULL: return "null pointer";
+    case GEMMF32_EALIAS: return "output aliases an input";
+    case GEMMF32_ELAUNCH: return "HIP runtime error (see gemm_f32_last_hip_error)";
+    case GEMMF32_ENOMEM: return "out of memory";
+    default: return "unknown status";
+    }
+}
+
+int gemm_f32_last_hip_error(void) { return g_last_hip_error; }
+
+const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                                  int64_t ldb, const float *C, int64_t ldc, int transB)
+{
+    // alignment is judged on the pointers' low bits only; nothing is dereferenced
+    const float *a = A ? A : reinterpret_cast<const float *>(uintptr_t(16));
+    const float *b = B ? B : reinterpret_cast<const float *>(uintptr_t(32));
+    float *c = C ? const_cast<float *>(C) : reinterpret_cast<float *>(uintptr_t(48));
+    Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
+    if (pl.status != GEMMF32_OK) return "invalid";
+    if (!pl.launch) return "empty";
+    std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
+                  pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "vec" : "scalar");
+    return g_variant_buf;
+}
+
+}  // extern "C"

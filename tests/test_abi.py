@@ -1,0 +1,50 @@
+"""CPU checks of the boundary: the built library loads and exports every function that
+include/gemm_f32.h declares, and the host-side queries that need no GPU answer correctly."""
+from __future__ import annotations
+
+import os
+import re
+
+from paper_2002_02268_amd import binding
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "gemm_f32.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("gemm_f32", "gemm_f32_batched", "pack_b", "pack_b_size", "gemm_f32_packed",
+                 "gemm_f32_set_stream", "gemm_f32_strerror", "gemm_f32_last_hip_error"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.lib()
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in gemm_f32.h but not exported"
+        assert name in binding.SYMBOLS, f"{name} has no Python binding signature"
+
+
+def test_host_only_queries():
+    lib = binding.lib()
+    P = binding.pack_b_panel_width()
+    assert P > 0 and P % 4 == 0
+    assert binding.pack_b_size(0, 5) == 0 and binding.pack_b_size(5, 0) == 0
+    assert binding.pack_b_size(1, 1) == P * 4
+    assert binding.pack_b_size(P + 1, 7) == 2 * 7 * P * 4
+    assert lib.gemm_f32_strerror(0) == b"ok"
+    assert lib.gemm_f32_strerror(-99) == b"unknown status"
+    assert lib.gemm_f32_last_hip_error() == 0
+    # argument validation happens before anything touches a device
+    assert lib.gemm_f32(-1, 1, 1, None, 1, None, 1, None, 1, 0) == -1
+    assert lib.gemm_f32(4, 4, 4, None, 4, None, 4, None, 4, 0) == -2
+    assert lib.gemm_f32(0, 4, 4, None, 4, None, 4, None, 4, 0) == 0
+    assert lib.gemm_f32_batched(0, 4, 4, 4, None, 4, 16, None, 4, 16, None, 4, 16, 0) == 0
+    assert binding.variant_name(4096, 4096, 4096).startswith("t256")
+    assert binding.variant_name(1000, 1030, 999).endswith("scalar")

@@ -1,0 +1,376 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact where the arithmetic is exact (integer-valued operands, identity,
+indicator probes, packing); otherwise max|C - C_ref| <= 1e-3*sqrt(K/1024) (x3 for N(0,1)
+operands, whose products have 9x the variance of U(-1,1) ones) and relative Frobenius
+error <= 1e-5."""
+from __future__ import annotations
+
+import math
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2002_02268_amd import binding, synth  # noqa: E402
+
+NTHREADS = min(16, os.cpu_count() or 1)
+TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3"}
+
+
+def dev(x: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def padded_dev(x: np.ndarray, pad, fill=float("nan")):
+    """Device buffer with rows `pad` elements longer than x ("align4": padded so that the row
+    length is a multiple of 4 and at least 4 longer); returns (view, whole buffer)."""
+    if pad == "align4":
+        pad = (-x.shape[1]) % 4 + 4
+    buf = torch.full((x.shape[0], x.shape[1] + pad), fill, dtype=torch.float32, device="cuda")
+    view = buf[:, : x.shape[1]]
+    view.copy_(torch.from_numpy(np.ascontiguousarray(x)))
+    return view, buf
+
+
+def check_close(C: np.ndarray, ref: np.ndarray, K: int, scale: float = 1.0):
+    assert C.shape == ref.shape
+    assert np.isfinite(C).all()
+    diff = np.abs(C.astype(np.float64) - ref)
+    tol = scale * 1e-3 * math.sqrt(max(K, 1) / 1024.0)
+    assert diff.max(initial=0.0) <= tol, f"max abs err {diff.max()} > {tol}"
+    denom = np.linalg.norm(ref)
+    if denom > 0:
+        rel = np.linalg.norm(diff) / denom
+        assert rel <= 1e-5, f"relative Frobenius error {rel}"
+
+
+@pytest.fixture
+def force_tile():
+    def _set(name):
+        if name is None:
+            os.environ.pop("GEMMF32_FORCE_TILE", None)
+        else:
+            os.environ["GEMMF32_FORCE_TILE"] = TILES[name]
+    yield _set
+    os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+SMALL_SHAPES = [(1, 1, 1), (33, 65, 17), (64, 64, 64), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33)]
+
+
+@pytest.mark.parametrize("tile", ["t256", "t128", "t64", "tb64"])
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("pad", [0, 5, "align4"])
+def test_small_shapes_every_tile(force_tile, tile, transB, pad):
+    """Several tiles plus ragged tails in M, N and K; tight, odd (ld = dim+5, per-element path)
+    and 16-byte-friendly (ld rounded up to a multiple of 4: vector path with ragged edges)
+    strides; NaN in all padding and in old C."""
+    force_tile(tile)
+    for idx, (M, N, K) in enumerate(SMALL_SHAPES):
+        print(f"case tile={tile} transB={transB} pad={pad} M={M} N={N} K={K}", flush=True)
+        A = synth.uniform((M, K), 20 + idx, synth.TENSOR_A)
+        B = synth.uniform((N, K) if transB else (K, N), 20 + idx, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+        dA, _ = padded_dev(A, pad)
+        dB, _ = padded_dev(B, pad)
+        dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), pad)
+        binding.gemm_f32(dA, dB, dC, transB=transB)
+        torch.cuda.synchronize()
+        whole = bufC.cpu().numpy()
+        check_close(whole[:, :N], ref, K)
+        assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+
+
+@pytest.mark.parametrize("tile", ["t256", "t128", "t64", "tb64"])
+@pytest.mark.parametrize("transB", [False, True])
+def test_integer_operands_bit_exact(force_tile, tile, transB):
+    """Entries in {-2..2}: all partial sums are integers below 2^24, exact in any order."""
+    force_tile(tile)
+    for idx, (M, N, K) in enumerate([(100, 90, 300), (257, 513, 65), (64, 64, 64)]):
+        A = synth.small_ints((M, K), 40 + idx, synth.TENSOR_A)
+        B = synth.small_ints((N, K) if transB else (K, N), 40 + idx, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(dev(A), dev(B), dC, transB=transB)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+
+
+def test_identity_and_indicator_probes_bit_exact(force_tile):
+    for tile in TILES:
+        force_tile(tile)
+        M, N, K = 150, 140, 131
+        A = synth.uniform((M, K), 50, synth.TENSOR_A)
+        dC = torch.empty((M, K), device="cuda")
+        binding.gemm_f32(dev(A), dev(np.eye(K, dtype=np.float32)), dC)
+        assert np.array_equal(dC.cpu().numpy(), A)
+        binding.gemm_f32(dev(A), dev(np.eye(K, dtype=np.float32)), dC, transB=True)
+        assert np.array_equal(dC.cpu().numpy(), A)
+        B = synth.uniform((K, N), 50, synth.TENSOR_B)
+        for (i, k) in [(0, 0), (M - 1, K - 1), (77, 129), (149, 3)]:
+            E = np.zeros((M, K), np.float32)
+            E[i, k] = 1.0
+            dC = torch.full((M, N), float("nan"), device="cuda")
+            binding.gemm_f32(dev(E), dev(B), dC)
+            want = np.zeros((M, N), np.float32)
+            want[i] = B[k]
+            assert np.array_equal(dC.cpu().numpy(), want)
+            binding.gemm_f32(dev(E), dev(B.T), dC, transB=True)
+            assert np.array_equal(dC.cpu().numpy(), want)
+
+
+def test_all_ones_closed_form():
+    for (M, N, K) in [(70, 300, 1000), (256, 256, 4096)]:
+        dC = torch.empty((M, N), device="cuda")
+        binding.gemm_f32(torch.ones((M, K), device="cuda"), torch.ones((K, N), device="cuda"), dC)
+        assert torch.equal(dC, torch.full((M, N), float(K), device="cuda"))
+
+
+def test_masked_lanes_contribute_exact_zeros():
+    """Operands sit inside larger NaN / Inf-filled buffers; tails in M, N and K are all ragged."""
+    M, N, K = 131, 77, 45
+    A = synth.uniform((M, K), 60, synth.TENSOR_A)
+    B = synth.uniform((K, N), 60, synth.TENSOR_B)
+    ref = oracle.gemm_f32(A, B)
+    for fill in (float("nan"), float("inf")):
+        bigA = torch.full((M + 40, K + 40), fill, device="cuda")
+        bigB = torch.full((K + 40, N + 40), fill, device="cuda")
+        bigA[:M, :K] = dev(A)
+        bigB[:K, :N] = dev(B)
+        dC = torch.empty((M, N), device="cuda")
+        binding.gemm_f32(bigA[:M, :K], bigB[:K, :N], dC)
+        check_close(dC.cpu().numpy(), ref, K)
+
+
+def test_nan_in_range_propagates_only_to_its_row_and_column():
+    M, N, K = 70, 90, 40
+    A = synth.uniform((M, K), 61, synth.TENSOR_A)
+    B = synth.uniform((K, N), 61, synth.TENSOR_B)
+    A[13, 7] = np.nan
+    dC = torch.empty((M, N), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    C = dC.cpu().numpy()
+    assert np.isnan(C[13]).all() and np.isfinite(np.delete(C, 13, axis=0)).all()
+
+
+def test_empty_dimensions():
+    dA = torch.empty((0, 8), device="cuda")
+    dB = torch.empty((8, 5), device="cuda")
+    binding.gemm_f32(dA, dB, torch.empty((0, 5), device="cuda"))
+    binding.gemm_f32(torch.empty((4, 8), device="cuda"), torch.empty((8, 0), device="cuda"),
+                     torch.empty((4, 0), device="cuda"))
+    dC = torch.full((37, 41), float("nan"), device="cuda")
+    binding.gemm_f32(torch.empty((37, 0), device="cuda"), torch.empty((0, 41), device="cuda"), dC)
+    C = dC.cpu().numpy()
+    assert np.array_equal(C, np.zeros((37, 41), np.float32)) and not np.signbit(C).any()
+    binding.gemm_f32_batched(torch.empty((0, 4, 4), device="cuda"), torch.empty((0, 4, 4), device="cuda"),
+                             torch.empty((0, 4, 4), device="cuda"))
+
+
+def test_error_codes():
+    lib = binding.lib()
+    buf = torch.zeros(64 * 64, device="cuda")
+    other = torch.zeros(64 * 64, device="cuda")
+    out = torch.zeros(64 * 64, device="cuda")
+    a, b, c = buf.data_ptr(), other.data_ptr(), out.data_ptr()
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, c, 8, 0) == 0
+    assert lib.gemm_f32(-1, 8, 8, a, 8, b, 8, c, 8, 0) == -1
+    assert lib.gemm_f32(8, 8, 8, a, 7, b, 8, c, 8, 0) == -1
+    assert lib.gemm_f32(8, 9, 8, a, 8, b, 8, c, 9, 0) == -1      # ldb < N
+    assert lib.gemm_f32(8, 9, 4, a, 4, b, 8, c, 9, 1) == 0       # transB: ldb >= K is enough
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, c, 7, 0) == -1
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, c, 8, 2) == -1
+    assert lib.gemm_f32(8, 8, 8, None, 8, b, 8, c, 8, 0) == -2
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, None, 8, 0) == -2
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, a, 8, 0) == -3
+    assert lib.gemm_f32(8, 8, 8, a, 8, b, 8, b, 8, 0) == -3
+    assert lib.gemm_f32(1 << 31, 8, 8, a, 8, b, 8, c, 8, 0) == -1
+    assert lib.pack_b(8, 8, a, 7, 0, c) == -1
+    assert lib.pack_b(8, 8, a, 8, 0, c + 4) == -1
+    assert lib.gemm_f32_strerror(-3).decode().startswith("output aliases")
+    torch.cuda.synchronize()
+
+
+def test_run_to_run_bitwise_determinism():
+    A, B = synth.make_operands("ragged")
+    dA, dB = dev(A), dev(B)
+    outs = []
+    for _ in range(3):
+        dC = torch.empty((1000, 1030), device="cuda")
+        binding.gemm_f32(dA, dB, dC)
+        outs.append(dC.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_transpose_identity_on_gpu():
+    """(AB)^T = B^T A^T and the transB flag: same product within tolerance."""
+    A = synth.uniform((210, 330), 62, synth.TENSOR_A)
+    B = synth.uniform((330, 190), 62, synth.TENSOR_B)
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dC = torch.empty((210, 190), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    check_close(dC.cpu().numpy(), ref, 330)
+    dCt = torch.empty((190, 210), device="cuda")
+    binding.gemm_f32(dev(B.T), dev(A.T), dCt)
+    check_close(dCt.cpu().numpy().T, ref, 330)
+    binding.gemm_f32(dev(B.T), dev(A), dCt, transB=True)
+    check_close(dCt.cpu().numpy().T, ref, 330)
+
+
+# --------------------------------------------------------------------- the five workloads
+
+def test_workload_square1024_full_oracle():
+    A, B = synth.make_operands("square1024")
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dC = torch.full((1024, 1024), float("nan"), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    check_close(dC.cpu().numpy(), ref, 1024)
+
+
+def test_workload_ragged_full_oracle_with_guards():
+    A, B = synth.make_operands("ragged")
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    guard = torch.full((1000 + 2, 1030), float("nan"), device="cuda")   # one guard row each side
+    dC = guard[1:1001]
+    binding.gemm_f32(dev(A), dev(B), dC)
+    whole = guard.cpu().numpy()
+    check_close(whole[1:1001], ref, 999)
+    assert np.isnan(whole[0]).all() and np.isnan(whole[1001]).all()
+
+
+def test_workload_ragged_integer_bit_exact():
+    A, B = synth.make_operands("ragged", dist="ints")
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dC = torch.empty((1000, 1030), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+
+
+def _sampled_rows_and_freivalds(A, B, C, transB, K, seed, scale=1.0, nrows=48):
+    """At sizes the O(n^3) oracle cannot cover in seconds: the oracle on seeded sample rows
+    (all columns), plus A(Bx) = Cx over the whole output in fp64."""
+    M = A.shape[0]
+    rows = np.unique(np.concatenate([[0, M - 1], (synth._bits24(seed, 7, nrows) % M)]))
+    ref = oracle.gemm_f32(np.ascontiguousarray(A[rows]), B, transB=transB, nthreads=NTHREADS)
+    check_close(C[rows], ref, K, scale)
+    N = C.shape[1]
+    x = synth.signs(N, seed)
+    Bx = (B.astype(np.float64) @ x) if transB else (B.astype(np.float64).T @ x)
+    lhs = A.astype(np.float64) @ Bx
+    tol = scale * 1e-3 * math.sqrt(K / 1024.0) * math.sqrt(N)
+    assert np.max(np.abs(C.astype(np.float64) @ x - lhs)) <= tol
+
+
+def test_workload_square4096_sampled_rows_and_vector_check():
+    A, B = synth.make_operands("square4096")
+    dC = torch.full((4096, 4096), float("nan"), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    C = dC.cpu().numpy()
+    assert np.isfinite(C).all()
+    _sampled_rows_and_freivalds(A, B, C, False, 4096, seed=2)
+
+
+def test_workload_square4096_integer_bit_exact_vs_library_int_product():
+    """Whole 4096^2 output, exact: integer-valued operands against an int64 product of a row
+    sample by the oracle, and the +-1 vector check (exact in fp64) over everything."""
+    A, B = synth.make_operands("square4096", dist="ints")
+    dC = torch.empty((4096, 4096), device="cuda")
+    binding.gemm_f32(dev(A), dev(B), dC)
+    C = dC.cpu().numpy()
+    rows = np.arange(0, 4096, 97)
+    ref = oracle.gemm_f32(np.ascontiguousarray(A[rows]), B, nthreads=NTHREADS)
+    assert np.array_equal(C[rows].astype(np.float64), ref)
+    x = synth.signs(4096, 2)
+    assert np.array_equal(C.astype(np.float64) @ x, A.astype(np.float64) @ (B.astype(np.float64) @ x))
+
+
+def test_workload_transb2048_and_packed():
+    A, Bt = synth.make_operands("transb2048")          # Bt is B stored N x K
+    dA, dBt = dev(A), dev(Bt)
+    dC = torch.full((2048, 2048), float("nan"), device="cuda")
+    binding.gemm_f32(dA, dBt, dC, transB=True)
+    C = dC.cpu().numpy()
+    _sampled_rows_and_freivalds(A, Bt, C, True, 2048, seed=3, scale=3.0)
+
+    P = binding.pack_b_panel_width()
+    nbytes = binding.pack_b_size(2048, 2048)
+    assert nbytes == (2048 // P) * 2048 * P * 4
+    dBp = torch.full((nbytes // 4,), float("nan"), device="cuda")
+    binding.pack_b(dBt, dBp, transB=True)
+    want = oracle.pack_b(Bt, P, transB=True)
+    assert np.array_equal(dBp.cpu().numpy().reshape(want.shape), want)
+    dC2 = torch.full((2048, 2048), float("nan"), device="cuda")
+    binding.gemm_f32_packed(dA, dBp, dC2)
+    C2 = dC2.cpu().numpy()
+    _sampled_rows_and_freivalds(A, Bt, C2, True, 2048, seed=3, scale=3.0)
+    rows = np.arange(0, 2048, 171)
+    ref = oracle.gemm_f32_packed(np.ascontiguousarray(A[rows]), want, 2048, nthreads=NTHREADS)
+    check_close(C2[rows], ref, 2048, 3.0)
+
+
+@pytest.mark.parametrize("N,K,transB,pad", [(130, 70, False, 0), (130, 70, True, 3), (64, 9, False, 5),
+                                            (300, 257, True, 0), (1, 1, False, 0)])
+def test_pack_b_bit_exact_and_packed_product(N, K, transB, pad):
+    P = binding.pack_b_panel_width()
+    B = synth.uniform((N, K) if transB else (K, N), 70, synth.TENSOR_B)
+    dB, _ = padded_dev(B, pad)
+    dBp = torch.full((binding.pack_b_size(N, K) // 4,), float("nan"), device="cuda")
+    binding.pack_b(dB, dBp, transB=transB)
+    want = oracle.pack_b(B, P, transB=transB)
+    got = dBp.cpu().numpy().reshape(want.shape)
+    assert np.array_equal(got, want) and not np.signbit(got[:, :, :][got == 0]).any()
+    for M in (1, 67, 200):
+        A = synth.uniform((M, K), 71, synth.TENSOR_A)
+        for apad in (0, 3):
+            dA, _ = padded_dev(A, apad)
+            dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), apad)
+            binding.gemm_f32_packed(dA, dBp, dC)
+            whole = bufC.cpu().numpy()
+            check_close(whole[:, :N], oracle.gemm_f32_packed(A, want, N), K)
+            assert np.isnan(whole[:, N:]).all()
+    Ai = synth.small_ints((90, K), 72, synth.TENSOR_A)
+    Bi = synth.small_ints((N, K) if transB else (K, N), 72, synth.TENSOR_B)
+    binding.pack_b(dev(Bi), dBp, transB=transB)
+    dC = torch.empty((90, N), device="cuda")
+    binding.gemm_f32_packed(dev(Ai), dBp, dC)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm_f32(Ai, Bi, transB=transB))
+
+
+def test_workload_batched64_full_oracle():
+    A, B = synth.make_operands("batched64")
+    ref = oracle.gemm_f32_batched(A, B, nthreads=NTHREADS)
+    dC = torch.full((4096, 64, 64), float("nan"), device="cuda")
+    binding.gemm_f32_batched(dev(A), dev(B), dC)
+    C = dC.cpu().numpy()
+    assert np.isfinite(C).all()
+    diff = np.abs(C.astype(np.float64) - ref)
+    assert diff.max() <= 1e-3 * math.sqrt(64 / 1024.0)
+    per_batch = np.sqrt((diff ** 2).sum(axis=(1, 2))) / np.sqrt((ref ** 2).sum(axis=(1, 2)))
+    assert per_batch.max() <= 1e-5
+
+
+def test_batched_integer_bit_exact_ragged_and_transb():
+    for transB in (False, True):
+        A = synth.small_ints((37, 50, 70), 80, synth.TENSOR_A)
+        B = synth.small_ints((37, 45, 70) if transB else (37, 70, 45), 80, synth.TENSOR_B)
+        ref = oracle.gemm_f32_batched(A, B, transB=transB, nthreads=NTHREADS)
+        dC = torch.full((37, 50, 45), float("nan"), device="cuda")
+        binding.gemm_f32_batched(dev(A), dev(B), dC, transB=transB)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+
+
+def test_batched_poisoned_neighbour_does_not_leak():
+    A = synth.uniform((9, 64, 64), 81, synth.TENSOR_A)
+    B = synth.uniform((9, 64, 64), 81, synth.TENSOR_B)
+    ref = oracle.gemm_f32_batched(A, B)
+    A[4] = np.nan
+    dC = torch.empty((9, 64, 64), device="cuda")
+    binding.gemm_f32_batched(dev(A), dev(B), dC)
+    C = dC.cpu().numpy()
+    assert np.isnan(C[4]).all()
+    for b in (3, 5):
+        check_close(C[b], ref[b], 64)
