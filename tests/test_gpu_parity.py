@@ -259,7 +259,7 @@ def _sampled_rows_and_freivalds(A, B, C, transB, K, seed, scale=1.0, nrows=48):
     check_close(C[rows], ref, K, scale)
     N = C.shape[1]
     x = synth.signs(N, seed)
-    Bx = (B.astype(np.float64) @ x) if transB else (B.astype(np.float64).T @ x)
+    Bx = (B.astype(np.float64).T @ x) if transB else (B.astype(np.float64) @ x)
     lhs = A.astype(np.float64) @ Bx
     tol = scale * 1e-3 * math.sqrt(K / 1024.0) * math.sqrt(N)
     assert np.max(np.abs(C.astype(np.float64) @ x - lhs)) <= tol
