@@ -113,6 +113,9 @@ def main() -> int:
     ap.add_argument("--workload", default="square4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only --workload")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
+                         "--steps times: the known-size kernel that HBM byte counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -125,6 +128,16 @@ def main() -> int:
     from paper_2002_02268_amd import binding, synth
     binding.lib()
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        B = torch.rand(4096, 4096, device="cuda")
+        Bp = torch.empty(binding.pack_b_size(4096, 4096) // 4, device="cuda")
+        for _ in range(args.steps):
+            binding.pack_b(B, Bp)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "pack_b 4096x4096", "read_bytes": 4096 * 4096 * 4,
+                          "write_bytes": 4096 * 4096 * 4, "launches": args.steps}))
+        return 0
 
     main_run = Runner(args.workload)
     w = main_run.w

@@ -29,18 +29,20 @@ int fail_hip(hipError_t e)
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- variants -------------------------------------------------------------------------------
-enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, NUM_TILES = 4 };
+enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, NUM_TILES = 6 };
 
-struct TileShape { int bm, bn; const char *name; };
+struct TileShape { int bm, bn, bk; const char *name; };
 const TileShape kShapes[NUM_TILES] = {
-    {256, 256, "t256x256x16"}, {128, 128, "t128x128x16"}, {64, 64, "t64x64x32"}, {64, 64, "t64x64x64s1"}};
+    {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
+    {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"}};
 
-template <int BMODE, bool VEC> struct Variants {
-    typedef Tile<256, 256, 16, 2, 2, BMODE, VEC, 2> Big;
-    typedef Tile<128, 128, 16, 2, 2, BMODE, VEC, 2> Mid;
-    typedef Tile<64, 64, 32, 2, 2, BMODE, VEC, 2> Small;
-    typedef Tile<64, 64, 64, 2, 2, BMODE, VEC, 1> Batch64;
-};
+template <int ID, int BMODE, bool VEC> struct Variant;
+template <int BMODE, bool VEC> struct Variant<T256, BMODE, VEC> { typedef Tile<256, 256, 16, 2, 2, BMODE, VEC, 1> type; };
+template <int BMODE, bool VEC> struct Variant<T128, BMODE, VEC> { typedef Tile<128, 128, 16, 2, 2, BMODE, VEC, 2> type; };
+template <int BMODE, bool VEC> struct Variant<T64, BMODE, VEC> { typedef Tile<64, 64, 32, 2, 2, BMODE, VEC, 2> type; };
+template <int BMODE, bool VEC> struct Variant<TB64, BMODE, VEC> { typedef Tile<64, 64, 64, 2, 2, BMODE, VEC, 2> type; };
+template <int BMODE, bool VEC> struct Variant<T256x128, BMODE, VEC> { typedef Tile<256, 128, 16, 2, 2, BMODE, VEC, 2> type; };
+template <int BMODE, bool VEC> struct Variant<T128x256, BMODE, VEC> { typedef Tile<128, 256, 16, 2, 2, BMODE, VEC, 2> type; };
 
 template <class T> int launch(const KArgs &a)
 {
@@ -52,7 +54,9 @@ template <class T> int launch(const KArgs &a)
         if (e != hipSuccess) return fail_hip(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), T::LDS_BYTES, g_stream, a);
+    // a product whose K fits one slab never touches the second LDS buffer
+    const int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), lds_bytes, g_stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e);
     return GEMMF32_OK;
@@ -60,12 +64,13 @@ template <class T> int launch(const KArgs &a)
 
 template <int BMODE, bool VEC> int launch_tile(int tile, const KArgs &a)
 {
-    typedef Variants<BMODE, VEC> V;
     switch (tile) {
-    case T256: return launch<typename V::Big>(a);
-    case T128: return launch<typename V::Mid>(a);
-    case T64: return launch<typename V::Small>(a);
-    default: return launch<typename V::Batch64>(a);
+    case T256: return launch<typename Variant<T256, BMODE, VEC>::type>(a);
+    case T128: return launch<typename Variant<T128, BMODE, VEC>::type>(a);
+    case T64: return launch<typename Variant<T64, BMODE, VEC>::type>(a);
+    case T256x128: return launch<typename Variant<T256x128, BMODE, VEC>::type>(a);
+    case T128x256: return launch<typename Variant<T128x256, BMODE, VEC>::type>(a);
+    default: return launch<typename Variant<TB64, BMODE, VEC>::type>(a);
     }
 }
 

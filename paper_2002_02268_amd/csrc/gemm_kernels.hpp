@@ -12,8 +12,12 @@
 //     stride padded by 4 floats, so one 16-byte LDS read gives a lane the operands of
 //     four MFMA steps;  slabs of B stored K x N (or packed) sit as [k][n] and a lane
 //     reads NB adjacent columns at once, which also makes its C stores NB floats wide;
-//   * slab t+1 is fetched from global memory into registers while slab t is multiplied,
-//     then written to the other LDS buffer: one barrier per slab.
+//   * software pipeline, two LDS buffers, one barrier per slab: while slab t is being
+//     multiplied, slab t+1 (fetched into registers one slab earlier) is written to the other
+//     LDS buffer and slab t+2 is requested from global memory; operand fragments for the
+//     next 8 columns of k are read from LDS while the current 8 are on the matrix pipe, and
+//     the barrier sits before the last 8-column group so that the first fragments of the
+//     next slab are already in flight when the current slab's last MFMAs issue.
 //
 // Lane maps of v_mfma_f32_32x32x2_f32 used below (lane l, l32 = l % 32, h = l / 32):
 //   A operand: A[i = l32][k = h]      B operand: B[k = h][j = l32]
@@ -57,28 +61,31 @@ template <> struct VecOf<4> { typedef v4f type; };
 template <int N> __device__ __forceinline__ float vget(const typename VecOf<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, bool VEC_, int STAGES_>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, bool VEC_, int OCC_ = 1>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
-    static constexpr int BMODE = BMODE_, STAGES = STAGES_;
+    static constexpr int BMODE = BMODE_, OCC = OCC_;
     static constexpr bool VEC = VEC_;
     static constexpr int THREADS = 64 * WGM * WGN;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
+    static constexpr int G = BK / 8;                           // 8-column groups per slab
     static constexpr int SA = BK + 4;                          // A rows in LDS: [BM][SA]
     static constexpr int SB = (BMODE == B_NT) ? (BK + 4) : BN; // B in LDS: [BN][SB] (NT) or [BK][BN]
     static constexpr int A_TILE = BM * SA;
     static constexpr int B_TILE = (BMODE == B_NT) ? BN * SB : BK * BN;
     static constexpr int STAGE_FLOATS = A_TILE + B_TILE;
-    static constexpr int LDS_BYTES = STAGES * STAGE_FLOATS * 4;
+    static constexpr int LDS_BYTES = 2 * STAGE_FLOATS * 4;
     static constexpr int A_F4 = BM * BK / 4, A_ITERS = A_F4 / THREADS;
     static constexpr int B_F4 = BN * BK / 4, B_ITERS = B_F4 / THREADS;
+    static constexpr int A_F4_ROW = BK / 4;                               // 16-byte chunks per A row
+    static constexpr int B_F4_ROW = (BMODE == B_NT) ? BK / 4 : BN / 4;    // per B row in the slab
     static_assert(BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0, "wave tiles are multiples of 32");
-    static_assert(BK % 8 == 0, "a slab holds whole 8-column groups");
+    static_assert(BK % 16 == 0, "a slab holds an even number of 8-column groups");
     static_assert(A_F4 % THREADS == 0 && B_F4 % THREADS == 0, "loads divide evenly over threads");
     static_assert(NB == 1 || NB == 2 || NB == 4, "NB columns are read as one LDS vector");
     static_assert(BMODE != B_PACKED || BN % kPanel == 0 || kPanel % BN == 0, "tile vs panel");
-    static_assert(STAGES == 1 || STAGES == 2, "single or double buffered");
+    static_assert(LDS_BYTES <= 160 * 1024, "fits the 160 KB of LDS per compute unit");
 };
 
 // Maps the hardware workgroup id to a tile.  Workgroups are handed to the 8 XCDs round
@@ -102,21 +109,35 @@ __device__ __forceinline__ void decode_tile(const KArgs &p, int &batch, int &tm,
     tn = r / gm;
 }
 
-template <class T>
-__global__ void __launch_bounds__(T::THREADS) gemm_kernel(const KArgs p)
+// Barrier between LDS producers and consumers.  Only LDS traffic has to be complete: global
+// loads requested for a later slab stay in flight across it.
+__device__ __forceinline__ void lds_barrier()
 {
-    constexpr int BM = T::BM, BN = T::BN, BK = T::BK;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <bool VEC> __device__ __forceinline__ v4f load4(const float *src)
+{
+    if constexpr (VEC) return *reinterpret_cast<const v4f *>(src);
+    return v4f{src[0], src[1], src[2], src[3]};
+}
+
+// One BM x BN tile.  EDGE: the tile crosses the M or N boundary, loads and stores are
+// predicated (loop-invariant predicates); otherwise every access is in range.
+template <class T, bool EDGE>
+__device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
+{
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
     constexpr int MB = T::MB, NB = T::NB, SA = T::SA, SB = T::SB;
     constexpr int NTHR = T::THREADS;
     constexpr int A_ITERS = T::A_ITERS, B_ITERS = T::B_ITERS;
-    constexpr int A_F4_ROW = BK / 4;                                  // 16-byte chunks per A row
-    constexpr int B_F4_ROW = (T::BMODE == B_NT) ? BK / 4 : BN / 4;    // per B row in the slab
+    constexpr int A_F4_ROW = T::A_F4_ROW, B_F4_ROW = T::B_F4_ROW;
+    constexpr int NBV = (T::BMODE == B_NT) ? NB : 4;   // B fragment vectors per 8-column group
     typedef typename VecOf<NB>::type vnb;
+    typedef typename std::conditional<T::BMODE == B_NT, v4f, vnb>::type bfrag_t;
 
-    extern __shared__ __align__(16) float lds[];
-
-    int batch, tm, tn;
-    decode_tile(p, batch, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const float *__restrict__ A = p.A + (int64_t)batch * p.sA;
     const float *__restrict__ B = p.B + (int64_t)batch * p.sB;
@@ -128,131 +149,158 @@ __global__ void __launch_bounds__(T::THREADS) gemm_kernel(const KArgs p)
     const int l32 = lane & 31, half = lane >> 5;
     const int wm0 = (wave / T::WGN) * T::WM, wn0 = (wave % T::WGN) * T::WN;
 
-    const bool interior = (m0 + BM <= M) && (n0 + BN <= N);
+    // ---- per-thread load slots: global pointer (at slab 0), LDS offset, edge predicate ----
+    const float *pa[A_ITERS];
+    const float *pb[B_ITERS];
+    int sa_off[A_ITERS], sb_off[B_ITERS];
+    int a_ok[A_ITERS];          // EDGE: row in range
+    int b_ok[B_ITERS];          // EDGE: 0 none, 1 all four elements, 2 some (NN only)
+    int b_col[B_ITERS];         // NN/packed: first global column of the chunk
+#pragma unroll
+    for (int r = 0; r < A_ITERS; ++r) {
+        const int f = tid + r * NTHR;
+        const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
+        sa_off[r] = row * SA + c;
+        a_ok[r] = (m0 + row < M);
+        const int gi = (EDGE && !a_ok[r]) ? 0 : (m0 + row);
+        pa[r] = A + (int64_t)gi * p.lda + c;
+    }
+#pragma unroll
+    for (int r = 0; r < B_ITERS; ++r) {
+        const int f = tid + r * NTHR;
+        const int row = f / B_F4_ROW, c = (f % B_F4_ROW) * 4;
+        sb_off[r] = row * SB + c;
+        if constexpr (T::BMODE == B_NT) {
+            b_ok[r] = (n0 + row < N);
+            b_col[r] = 0;
+            const int gj = (EDGE && !b_ok[r]) ? 0 : (n0 + row);
+            pb[r] = B + (int64_t)gj * p.ldb + c;
+        } else if constexpr (T::BMODE == B_NN) {
+            const int gj = n0 + c;
+            b_col[r] = gj;
+            b_ok[r] = (gj + 3 < N) ? 1 : (gj < N ? 2 : 0);
+            pb[r] = B + (int64_t)row * p.ldb + ((EDGE && !b_ok[r]) ? 0 : gj);
+        } else {
+            const int gj = n0 + c;
+            b_col[r] = gj;
+            b_ok[r] = (gj < p.n_padded);
+            const int gjc = (EDGE && !b_ok[r]) ? 0 : gj;
+            pb[r] = B + ((int64_t)(gjc / kPanel) * K + row) * kPanel + (gjc % kPanel);
+        }
+    }
+    const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
 
     v4f ra[A_ITERS], rb[B_ITERS];
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    // ---- global -> registers for the slab starting at column k0 -------------------------
-    auto load_a = [&](int k0, auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
+    // global -> registers, whole slab in range along k
+    auto load_slab = [&]() {
 #pragma unroll
         for (int r = 0; r < A_ITERS; ++r) {
-            const int f = tid + r * NTHR;
-            const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
-            const int gi = m0 + row, gk = k0 + c;
-            const float *src = A + (int64_t)gi * p.lda + gk;
-            if (!MASKED && T::VEC) {
-                ra[r] = *reinterpret_cast<const v4f *>(src);
-            } else if (!MASKED) {
-                ra[r] = v4f{src[0], src[1], src[2], src[3]};
+            if (!EDGE || a_ok[r]) ra[r] = load4<T::VEC>(pa[r]);
+            else ra[r] = zero4;
+        }
+#pragma unroll
+        for (int r = 0; r < B_ITERS; ++r) {
+            if constexpr (T::BMODE == B_PACKED) {
+                if (!EDGE || b_ok[r]) rb[r] = load4<true>(pb[r]);
+                else rb[r] = zero4;
+            } else if constexpr (T::BMODE == B_NT) {
+                if (!EDGE || b_ok[r]) rb[r] = load4<T::VEC>(pb[r]);
+                else rb[r] = zero4;
             } else {
-                v4f v = {0.f, 0.f, 0.f, 0.f};
-                if (gi < M) {
-                    if (T::VEC && gk + 3 < K) {
-                        v = *reinterpret_cast<const v4f *>(src);
-                    } else {
+                if (!EDGE || b_ok[r] == 1) {
+                    rb[r] = load4<T::VEC>(pb[r]);
+                } else {
+                    v4f v = zero4;
+                    if (b_ok[r] == 2) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (gk + e < K) v[e] = src[e];
+                            if (b_col[r] + e < N) v[e] = pb[r][e];
                     }
+                    rb[r] = v;
                 }
-                ra[r] = v;
             }
         }
     };
-    auto load_b = [&](int k0, auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
+    // global -> registers for the ragged last slab: kleft (< BK) columns of k remain
+    auto load_tail = [&](int kleft) {
+#pragma unroll
+        for (int r = 0; r < A_ITERS; ++r) {
+            const int c = ((tid + r * NTHR) % A_F4_ROW) * 4;
+            v4f v = zero4;
+            if (a_ok[r]) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < kleft) v[e] = pa[r][e];
+            }
+            ra[r] = v;
+        }
 #pragma unroll
         for (int r = 0; r < B_ITERS; ++r) {
             const int f = tid + r * NTHR;
-            const int row = f / B_F4_ROW, c = (f % B_F4_ROW) * 4;
-            if (T::BMODE == B_NT) {
-                // B stored N x K: row = column of C, c = offset along k
-                const int gj = n0 + row, gk = k0 + c;
-                const float *src = B + (int64_t)gj * p.ldb + gk;
-                if (!MASKED && T::VEC) {
-                    rb[r] = *reinterpret_cast<const v4f *>(src);
-                } else if (!MASKED) {
-                    rb[r] = v4f{src[0], src[1], src[2], src[3]};
-                } else {
-                    v4f v = {0.f, 0.f, 0.f, 0.f};
-                    if (gj < N) {
-                        if (T::VEC && gk + 3 < K) {
-                            v = *reinterpret_cast<const v4f *>(src);
-                        } else {
+            v4f v = zero4;
+            if constexpr (T::BMODE == B_NT) {
+                const int c = (f % B_F4_ROW) * 4;
+                if (b_ok[r]) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (gk + e < K) v[e] = src[e];
-                        }
-                    }
-                    rb[r] = v;
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < kleft) v[e] = pb[r][e];
                 }
-            } else if (T::BMODE == B_NN) {
-                // B stored K x N: row = offset along k, c = column offset
-                const int gk = k0 + row, gj = n0 + c;
-                const float *src = B + (int64_t)gk * p.ldb + gj;
-                if (!MASKED && T::VEC) {
-                    rb[r] = *reinterpret_cast<const v4f *>(src);
-                } else if (!MASKED) {
-                    rb[r] = v4f{src[0], src[1], src[2], src[3]};
-                } else {
-                    v4f v = {0.f, 0.f, 0.f, 0.f};
-                    if (gk < K) {
-                        if (T::VEC && gj + 3 < N) {
-                            v = *reinterpret_cast<const v4f *>(src);
-                        } else {
+            } else if constexpr (T::BMODE == B_NN) {
+                const int row = f / B_F4_ROW;
+                if (row < kleft && b_ok[r]) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (gj + e < N) v[e] = src[e];
-                        }
-                    }
-                    rb[r] = v;
+                    for (int e = 0; e < 4; ++e)
+                        if (b_col[r] + e < N) v[e] = pb[r][e];
                 }
             } else {
-                // packed B: [panel][k][kPanel]; columns past N are stored zeros, columns past
-                // the last panel do not exist
-                const int gk = k0 + row, gj = n0 + c;
-                const int panel = gj / kPanel, z = gj % kPanel;
-                const float *src = B + ((int64_t)panel * K + gk) * kPanel + z;
-                if (!MASKED) {
-                    rb[r] = *reinterpret_cast<const v4f *>(src);
-                } else {
-                    v4f v = {0.f, 0.f, 0.f, 0.f};
-                    if (gk < K && gj < p.n_padded) v = *reinterpret_cast<const v4f *>(src);
-                    rb[r] = v;
-                }
+                const int row = f / B_F4_ROW;
+                if (row < kleft && b_ok[r]) v = load4<true>(pb[r]);
             }
+            rb[r] = v;
         }
     };
-    auto load_slab = [&](int k0) {
-        if (interior && k0 + BK <= K) {
-            load_a(k0, std::false_type{});
-            load_b(k0, std::false_type{});
-        } else {
-            load_a(k0, std::true_type{});
-            load_b(k0, std::true_type{});
-        }
+    auto advance = [&](int steps) {            // steps is wave-uniform: 0 or 1
+        const int64_t da = steps ? BK : 0, db = steps ? b_step : 0;
+#pragma unroll
+        for (int r = 0; r < A_ITERS; ++r) pa[r] += da;
+#pragma unroll
+        for (int r = 0; r < B_ITERS; ++r) pb[r] += db;
     };
-
-    // ---- registers -> LDS -----------------------------------------------------------------
     auto store_slab = [&](int stage) {
         float *As = lds + stage * T::STAGE_FLOATS;
         float *Bs = As + T::A_TILE;
 #pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) {
-            const int f = tid + r * NTHR;
-            const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
-            *reinterpret_cast<v4f *>(&As[row * SA + c]) = ra[r];
-        }
+        for (int r = 0; r < A_ITERS; ++r) *reinterpret_cast<v4f *>(&As[sa_off[r]]) = ra[r];
 #pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) {
-            const int f = tid + r * NTHR;
-            const int row = f / B_F4_ROW, c = (f % B_F4_ROW) * 4;
-            *reinterpret_cast<v4f *>(&Bs[row * SB + c]) = rb[r];
+        for (int r = 0; r < B_ITERS; ++r) *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = rb[r];
+    };
+
+    // ---- LDS -> fragments -> MFMA -----------------------------------------------------------
+    struct Frag {
+        v4f a[MB];
+        bfrag_t b[NBV];
+    };
+    const int a_frag_off = (wm0 + l32) * SA + 4 * half;
+    const int b_frag_off = (T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + 4 * half)
+                                              : (T::A_TILE + 4 * half * SB + wn0 + NB * l32);
+    auto read_frag = [&](Frag &fr, int stage, int g) {
+        const float *base = lds + stage * T::STAGE_FLOATS;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            fr.a[i] = *reinterpret_cast<const v4f *>(base + a_frag_off + 32 * i * SA + 8 * g);
+        if constexpr (T::BMODE == B_NT) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j)   // column of block j: wn0 + 32*j + l32
+                fr.b[j] = *reinterpret_cast<const v4f *>(base + b_frag_off + 32 * j * SB + 8 * g);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)    // column of block j: wn0 + NB*l32 + j
+                fr.b[e] = *reinterpret_cast<const vnb *>(base + b_frag_off + (8 * g + e) * SB);
         }
     };
 
-    // ---- LDS -> MFMA ----------------------------------------------------------------------
     v16f acc[MB][NB];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
@@ -261,88 +309,123 @@ __global__ void __launch_bounds__(T::THREADS) gemm_kernel(const KArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    auto compute_slab = [&](int stage) {
-        const float *As = lds + stage * T::STAGE_FLOATS;
-        const float *Bs = As + T::A_TILE;
-        const float *a_base = As + (wm0 + l32) * SA + 4 * half;
+    auto mfma_group = [&](const Frag &fr) {
 #pragma unroll
-        for (int g = 0; g < BK / 8; ++g) {
-            v4f a[MB];
+        for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int i = 0; i < MB; ++i)
-                a[i] = *reinterpret_cast<const v4f *>(a_base + 32 * i * SA + 8 * g);
-            if (T::BMODE == B_NT) {
-                // column of block j: wn0 + 32*j + l32
-                v4f b[NB];
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    b[j] = *reinterpret_cast<const v4f *>(Bs + (wn0 + 32 * j + l32) * SB + 4 * half + 8 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < MB; ++i)
-#pragma unroll
-                        for (int j = 0; j < NB; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][e], b[j][e], acc[i][j], 0, 0, 0);
-            } else {
-                // column of block j: wn0 + NB*l32 + j
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const vnb b = *reinterpret_cast<const vnb *>(Bs + (8 * g + e + 4 * half) * SB + wn0 + NB * l32);
-#pragma unroll
-                    for (int i = 0; i < MB; ++i)
-#pragma unroll
-                        for (int j = 0; j < NB; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][e], vget<NB>(b, j), acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NB; ++j) {
+                    float bv;
+                    if constexpr (T::BMODE == B_NT) bv = fr.b[j][e];
+                    else bv = vget<NB>(fr.b[e], j);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fr.a[i][e], bv, acc[i][j], 0, 0, 0);
                 }
-            }
-        }
     };
 
-    // ---- main loop ------------------------------------------------------------------------
-    const int nk = (K + BK - 1) / BK;
-    if (T::STAGES == 2) {
-        if (nk > 0) {
-            load_slab(0);
-            store_slab(0);
+    // ---- main loop over the full slabs --------------------------------------------------------
+    // Issue order inside a slab is pinned with scheduling groups: the LDS reads, LDS writes and
+    // global loads are spread one at a time between MFMAs instead of being issued in a burst
+    // (a burst from all waves at once fills the LDS queue and stalls MFMA issue behind it).
+    const int nkf = K / BK;
+    const int kleft = K - nkf * BK;
+    Frag f0, f1;
+    constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
+    constexpr int N_READ = MB + NBV;               // LDS reads of one fragment set
+    constexpr int N_MOVE = A_ITERS + B_ITERS;      // LDS writes (= global loads) of one slab
+    auto slab_body = [&](const int t, auto more_tag) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        const int cur = t & 1;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            Frag &now = (g & 1) ? f1 : f0;
+            Frag &next = (g & 1) ? f0 : f1;
+            bool reads = false;
+            if (g + 1 < G) {
+                read_frag(next, cur, g + 1);
+                reads = true;
+            } else if (MORE) {
+                lds_barrier();                 // slab t+1 is complete in the other buffer
+                read_frag(next, cur ^ 1, 0);
+                reads = true;
+            }
+            if (g == 0 && MORE) {
+                store_slab(cur ^ 1);           // slab t+1, requested one slab ago
+                advance((t + 2 < nkf) ? 1 : 0);   // 0: harmless re-request of the last slab
+                load_slab();                   // slab t+2
+            }
+            mfma_group(now);
+            // pin the interleaving of this group's instructions
+            constexpr int SPREAD = 2;          // MFMAs between two memory instructions
+            int used = 0;
+            if (reads) {
+#pragma unroll
+                for (int i = 0; i < N_READ; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+                }
+                used += N_READ;
+            }
+            if (g == 0 && MORE) {
+#pragma unroll
+                for (int i = 0; i < N_MOVE; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, SPREAD, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // LDS write
+                }
+#pragma unroll
+                for (int i = 0; i < N_MOVE; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
+                }
+                used += (SPREAD + 1) * N_MOVE;
+            }
+            (void)used;
+            (void)N_MFMA;
         }
+    };
+    if (nkf > 0) {
+        load_slab();
+        store_slab(0);
+        if (nkf > 1) { advance(1); load_slab(); }
+        lds_barrier();
+        read_frag(f0, 0, 0);
+        for (int t = 0; t + 1 < nkf; ++t) slab_body(t, std::true_type{});
+        slab_body(nkf - 1, std::false_type{});
+    }
+    // ---- ragged last slab (K % BK columns), not pipelined -------------------------------------
+    if (kleft > 0) {
+        if (nkf > 0) advance(1);
+        load_tail(kleft);
+        __syncthreads();                           // everyone is done reading both buffers
+        store_slab(0);
         __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            const bool more = kt + 1 < nk;
-            if (more) load_slab((kt + 1) * BK);
-            compute_slab(cur);
-            if (more) store_slab(cur ^ 1);
-            __syncthreads();
-        }
-    } else {
-        for (int kt = 0; kt < nk; ++kt) {
-            load_slab(kt * BK);
-            if (kt > 0) __syncthreads();
-            store_slab(0);
-            __syncthreads();
-            compute_slab(0);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (8 * g < kleft) {
+                read_frag(f0, 0, g);
+                mfma_group(f0);
+            }
         }
     }
 
-    // ---- epilogue: accumulators -> C (overwrite; masked at the M / N edges) ---------------
+    // ---- epilogue: accumulators -> C (overwrite; predicated at the M / N edges) ---------------
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int gi = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * half + (v % 4);
-            if (T::BMODE == B_NT) {
+            if constexpr (T::BMODE == B_NT) {
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int gj = n0 + wn0 + 32 * j + l32;
-                    if (interior || (gi < M && gj < N)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
+                    if (!EDGE || (gi < M && gj < N)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
                 }
             } else {
                 const int gj = n0 + wn0 + NB * l32;
                 float *dst = C + (int64_t)gi * p.ldc + gj;
                 bool done = false;
                 if constexpr (T::VEC && NB > 1) {
-                    if (interior || (gi < M && gj + NB <= N)) {
+                    if (!EDGE || (gi < M && gj + NB <= N)) {
                         vnb o;
 #pragma unroll
                         for (int j = 0; j < NB; ++j) o[j] = acc[i][j][v];
@@ -353,11 +436,22 @@ __global__ void __launch_bounds__(T::THREADS) gemm_kernel(const KArgs p)
                 if (!done) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        if (interior || (gi < M && gj + j < N)) dst[j] = acc[i][j][v];
+                        if (!EDGE || (gi < M && gj + j < N)) dst[j] = acc[i][j][v];
                 }
             }
         }
     }
+}
+
+template <class T>
+__global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
+{
+    extern __shared__ __align__(16) float lds[];
+    int batch, tm, tn;
+    decode_tile(p, batch, tm, tn);
+    const bool interior = ((tm + 1) * T::BM <= p.M) && ((tn + 1) * T::BN <= p.N);
+    if (interior) gemm_tile<T, false>(p, lds, batch, tm, tn);
+    else gemm_tile<T, true>(p, lds, batch, tm, tn);
 }
 
 // Array packing (Section 6.1): Bp[x][y][z] = opB[y][x*kPanel + z], zero beyond column N.
