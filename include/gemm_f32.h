@@ -114,7 +114,7 @@ int gemm_f32_last_hip_error(void);
 
 /*
  * Which kernel variant the dispatcher would run for a shape, as a static
- * string such as "t256x256x16/nn/vec" (diagnostics for benchmarks; the
+ * string such as "t256x256x16/nn/a16" (diagnostics for benchmarks; the
  * pointers are only inspected for alignment and may be NULL for "aligned").
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,

@@ -36,13 +36,13 @@ const TileShape kShapes[NUM_TILES] = {
     {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
     {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"}};
 
-template <int ID, int BMODE, bool VEC> struct Variant;
-template <int BMODE, bool VEC> struct Variant<T256, BMODE, VEC> { typedef Tile<256, 256, 16, 2, 2, BMODE, VEC, 1> type; };
-template <int BMODE, bool VEC> struct Variant<T128, BMODE, VEC> { typedef Tile<128, 128, 16, 2, 2, BMODE, VEC, 2> type; };
-template <int BMODE, bool VEC> struct Variant<T64, BMODE, VEC> { typedef Tile<64, 64, 32, 2, 2, BMODE, VEC, 2> type; };
-template <int BMODE, bool VEC> struct Variant<TB64, BMODE, VEC> { typedef Tile<64, 64, 64, 2, 2, BMODE, VEC, 2> type; };
-template <int BMODE, bool VEC> struct Variant<T256x128, BMODE, VEC> { typedef Tile<256, 128, 16, 2, 2, BMODE, VEC, 2> type; };
-template <int BMODE, bool VEC> struct Variant<T128x256, BMODE, VEC> { typedef Tile<128, 256, 16, 2, 2, BMODE, VEC, 2> type; };
+template <int ID, int BMODE> struct Variant;
+template <int BMODE> struct Variant<T256, BMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1> type; };
+template <int BMODE> struct Variant<T128, BMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2> type; };
+template <int BMODE> struct Variant<T64, BMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2> type; };
+template <int BMODE> struct Variant<TB64, BMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2> type; };
+template <int BMODE> struct Variant<T256x128, BMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2> type; };
+template <int BMODE> struct Variant<T128x256, BMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2> type; };
 
 template <class T> int launch(const KArgs &a)
 {
@@ -62,30 +62,34 @@ template <class T> int launch(const KArgs &a)
     return GEMMF32_OK;
 }
 
-template <int BMODE, bool VEC> int launch_tile(int tile, const KArgs &a)
+template <int BMODE> int launch_tile(int tile, const KArgs &a)
 {
     switch (tile) {
-    case T256: return launch<typename Variant<T256, BMODE, VEC>::type>(a);
-    case T128: return launch<typename Variant<T128, BMODE, VEC>::type>(a);
-    case T64: return launch<typename Variant<T64, BMODE, VEC>::type>(a);
-    case T256x128: return launch<typename Variant<T256x128, BMODE, VEC>::type>(a);
-    case T128x256: return launch<typename Variant<T128x256, BMODE, VEC>::type>(a);
-    default: return launch<typename Variant<TB64, BMODE, VEC>::type>(a);
+    case T256: return launch<typename Variant<T256, BMODE>::type>(a);
+    case T128: return launch<typename Variant<T128, BMODE>::type>(a);
+    case T64: return launch<typename Variant<T64, BMODE>::type>(a);
+    case T256x128: return launch<typename Variant<T256x128, BMODE>::type>(a);
+    case T128x256: return launch<typename Variant<T128x256, BMODE>::type>(a);
+    default: return launch<typename Variant<TB64, BMODE>::type>(a);
     }
 }
 
-int launch_variant(int bmode, bool vec, int tile, const KArgs &a)
+int launch_variant(int bmode, int tile, const KArgs &a)
 {
     switch (bmode) {
-    case B_NN: return vec ? launch_tile<B_NN, true>(tile, a) : launch_tile<B_NN, false>(tile, a);
-    case B_NT: return vec ? launch_tile<B_NT, true>(tile, a) : launch_tile<B_NT, false>(tile, a);
-    default: return vec ? launch_tile<B_PACKED, true>(tile, a) : launch_tile<B_PACKED, false>(tile, a);
+    case B_NN: return launch_tile<B_NN>(tile, a);
+    case B_NT: return launch_tile<B_NT>(tile, a);
+    default: return launch_tile<B_PACKED>(tile, a);
     }
 }
 
 int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Tile choice: the largest tile that still gives every compute unit (256 of them) work.
+// Tile choice.  Workgroups spread over 256 compute units, so a launch costs
+// ceil(tiles / 256) rounds of one tile each; a tile costs its area divided by the fraction
+// of the MFMA peak that variant sustains (measured on square problems).  The cheapest wins:
+// big tiles when they fill the chip evenly, smaller ones when the last round would be
+// mostly empty or the output is small.
 int choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
 {
     if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
@@ -93,11 +97,17 @@ int choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         if (t >= 0 && t < NUM_TILES) return t;
     }
     if (M <= 64 && N <= 64 && K <= 64) return TB64;
-    const int64_t t256 = batch * cdiv(M, 256) * cdiv(N, 256);
-    const int64_t t128 = batch * cdiv(M, 128) * cdiv(N, 128);
-    if (t256 >= 200) return T256;
-    if (t128 >= 200) return T128;
-    return T64;
+    static const struct { int id; double eff; } cand[] = {
+        {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {T64, 0.80}};
+    int best = T64;
+    double best_cost = 0;
+    for (const auto &c : cand) {
+        const TileShape &sh = kShapes[c.id];
+        const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
+        const double cost = (double)cdiv(tiles, 256) * sh.bm * sh.bn / c.eff;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = c.id; }
+    }
+    return best;
 }
 
 int choose_group_m(int tiles_m, int tiles_n, int64_t total)
@@ -176,7 +186,7 @@ int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
-    return launch_variant(pl.bmode, pl.vec, pl.tile, pl.args);
+    return launch_variant(pl.bmode, pl.tile, pl.args);
 }
 
 thread_local char g_variant_buf[64];
@@ -268,7 +278,7 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
     std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
-                  pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "vec" : "scalar");
+                  pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4");
     return g_variant_buf;
 }
 

@@ -34,6 +34,10 @@ namespace gemmf32 {
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+// Global-memory views with 4-byte alignment: operands whose base or leading dimension is not a
+// multiple of 16 bytes are still moved with one 16-byte (or 8-byte) instruction per lane.
+typedef v2f v2f_g __attribute__((aligned(4)));
+typedef v4f v4f_g __attribute__((aligned(4)));
 
 enum BMode : int { B_NN = 0, B_NT = 1, B_PACKED = 2 };
 
@@ -54,18 +58,17 @@ struct KArgs {
 };
 
 template <int N> struct VecOf;
-template <> struct VecOf<1> { typedef float type; };
-template <> struct VecOf<2> { typedef v2f type; };
-template <> struct VecOf<4> { typedef v4f type; };
+template <> struct VecOf<1> { typedef float type; typedef float gtype; };
+template <> struct VecOf<2> { typedef v2f type; typedef v2f_g gtype; };
+template <> struct VecOf<4> { typedef v4f type; typedef v4f_g gtype; };
 
 template <int N> __device__ __forceinline__ float vget(const typename VecOf<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, bool VEC_, int OCC_ = 1>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
     static constexpr int BMODE = BMODE_, OCC = OCC_;
-    static constexpr bool VEC = VEC_;
     static constexpr int THREADS = 64 * WGM * WGN;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
@@ -118,15 +121,14 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool VEC> __device__ __forceinline__ v4f load4(const float *src)
-{
-    if constexpr (VEC) return *reinterpret_cast<const v4f *>(src);
-    return v4f{src[0], src[1], src[2], src[3]};
-}
+__device__ __forceinline__ v4f load4(const float *src) { return *reinterpret_cast<const v4f_g *>(src); }
 
-// One BM x BN tile.  EDGE: the tile crosses the M or N boundary, loads and stores are
-// predicated (loop-invariant predicates); otherwise every access is in range.
-template <class T, bool EDGE>
+// One BM x BN tile.  EDGE = 0: every access is in range.  EDGE = 1: the tile crosses the M
+// boundary (or, for B stored N x K / packed, the N boundary): whole 16-byte chunks are either in
+// range or not.  EDGE = 2 (B stored K x N only): the tile crosses the N boundary, chunks of a
+// row of B may be partly in range.  Out-of-range operands are loaded from a clamped (valid)
+// address and replaced by zero with a select, so the steady-state loop stays branch free.
+template <class T, int EDGE>
 __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
 {
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
@@ -135,6 +137,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr int A_ITERS = T::A_ITERS, B_ITERS = T::B_ITERS;
     constexpr int A_F4_ROW = T::A_F4_ROW, B_F4_ROW = T::B_F4_ROW;
     constexpr int NBV = (T::BMODE == B_NT) ? NB : 4;   // B fragment vectors per 8-column group
+    constexpr bool B_ELEMENTWISE = (T::BMODE == B_NN && EDGE == 2);
     typedef typename VecOf<NB>::type vnb;
     typedef typename std::conditional<T::BMODE == B_NT, v4f, vnb>::type bfrag_t;
 
@@ -149,20 +152,21 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int l32 = lane & 31, half = lane >> 5;
     const int wm0 = (wave / T::WGN) * T::WM, wn0 = (wave % T::WGN) * T::WN;
 
-    // ---- per-thread load slots: global pointer (at slab 0), LDS offset, edge predicate ----
+    // ---- per-thread load slots: global pointer (at slab 0), LDS offset, edge predicates ----
     const float *pa[A_ITERS];
     const float *pb[B_ITERS];
     int sa_off[A_ITERS], sb_off[B_ITERS];
-    int a_ok[A_ITERS];          // EDGE: row in range
-    int b_ok[B_ITERS];          // EDGE: 0 none, 1 all four elements, 2 some (NN only)
-    int b_col[B_ITERS];         // NN/packed: first global column of the chunk
+    bool a_ok[A_ITERS];         // row of A in range
+    bool b_ok[B_ITERS];         // NT: row of B in range; packed: chunk present; NN: first column in range
+    int b_col[B_ITERS];         // NN / packed: first global column of the chunk
+    int b_d[B_ITERS][4];        // NN, EDGE 2: clamped offsets of the four elements from pb[r]
 #pragma unroll
     for (int r = 0; r < A_ITERS; ++r) {
         const int f = tid + r * NTHR;
         const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
         sa_off[r] = row * SA + c;
         a_ok[r] = (m0 + row < M);
-        const int gi = (EDGE && !a_ok[r]) ? 0 : (m0 + row);
+        const int gi = (m0 + row < M) ? (m0 + row) : (M - 1);
         pa[r] = A + (int64_t)gi * p.lda + c;
     }
 #pragma unroll
@@ -173,18 +177,21 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         if constexpr (T::BMODE == B_NT) {
             b_ok[r] = (n0 + row < N);
             b_col[r] = 0;
-            const int gj = (EDGE && !b_ok[r]) ? 0 : (n0 + row);
+            const int gj = (n0 + row < N) ? (n0 + row) : (N - 1);
             pb[r] = B + (int64_t)gj * p.ldb + c;
         } else if constexpr (T::BMODE == B_NN) {
             const int gj = n0 + c;
             b_col[r] = gj;
-            b_ok[r] = (gj + 3 < N) ? 1 : (gj < N ? 2 : 0);
-            pb[r] = B + (int64_t)row * p.ldb + ((EDGE && !b_ok[r]) ? 0 : gj);
+            b_ok[r] = (gj < N);
+            const int gjc = (gj < N) ? gj : (N - 1);
+            pb[r] = B + (int64_t)row * p.ldb + gjc;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b_d[r][e] = ((gj + e < N) ? (gj + e) : (N - 1)) - gjc;
         } else {
             const int gj = n0 + c;
             b_col[r] = gj;
             b_ok[r] = (gj < p.n_padded);
-            const int gjc = (EDGE && !b_ok[r]) ? 0 : gj;
+            const int gjc = (gj < p.n_padded) ? gj : 0;
             pb[r] = B + ((int64_t)(gjc / kPanel) * K + row) * kPanel + (gjc % kPanel);
         }
     }
@@ -197,30 +204,30 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     auto load_slab = [&]() {
 #pragma unroll
         for (int r = 0; r < A_ITERS; ++r) {
-            if (!EDGE || a_ok[r]) ra[r] = load4<T::VEC>(pa[r]);
-            else ra[r] = zero4;
+            v4f v = load4(pa[r]);
+            if constexpr (EDGE != 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
+            }
+            ra[r] = v;
         }
 #pragma unroll
         for (int r = 0; r < B_ITERS; ++r) {
-            if constexpr (T::BMODE == B_PACKED) {
-                if (!EDGE || b_ok[r]) rb[r] = load4<true>(pb[r]);
-                else rb[r] = zero4;
-            } else if constexpr (T::BMODE == B_NT) {
-                if (!EDGE || b_ok[r]) rb[r] = load4<T::VEC>(pb[r]);
-                else rb[r] = zero4;
-            } else {
-                if (!EDGE || b_ok[r] == 1) {
-                    rb[r] = load4<T::VEC>(pb[r]);
-                } else {
-                    v4f v = zero4;
-                    if (b_ok[r] == 2) {
+            v4f v;
+            if constexpr (B_ELEMENTWISE) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (b_col[r] + e < N) v[e] = pb[r][e];
-                    }
-                    rb[r] = v;
+                for (int e = 0; e < 4; ++e) {
+                    const float x = pb[r][b_d[r][e]];
+                    v[e] = (b_col[r] + e < N) ? x : 0.f;
+                }
+            } else {
+                v = load4(pb[r]);
+                if constexpr (EDGE != 0 && T::BMODE != B_NN) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = b_ok[r] ? v[e] : 0.f;
                 }
             }
+            rb[r] = v;
         }
     };
     // global -> registers for the ragged last slab: kleft (< BK) columns of k remain
@@ -252,11 +259,11 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 if (row < kleft && b_ok[r]) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (b_col[r] + e < N) v[e] = pb[r][e];
+                        if (b_col[r] + e < N) v[e] = pb[r][e];   // pb[r] is unclamped when b_ok
                 }
             } else {
                 const int row = f / B_F4_ROW;
-                if (row < kleft && b_ok[r]) v = load4<true>(pb[r]);
+                if (row < kleft && b_ok[r]) v = load4(pb[r]);
             }
             rb[r] = v;
         }
@@ -418,25 +425,25 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int gj = n0 + wn0 + 32 * j + l32;
-                    if (!EDGE || (gi < M && gj < N)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
+                    if (EDGE == 0 || (gi < M && gj < N)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
                 }
             } else {
                 const int gj = n0 + wn0 + NB * l32;
                 float *dst = C + (int64_t)gi * p.ldc + gj;
                 bool done = false;
-                if constexpr (T::VEC && NB > 1) {
-                    if (!EDGE || (gi < M && gj + NB <= N)) {
+                if constexpr (NB > 1) {
+                    if (EDGE == 0 || (gi < M && gj + NB <= N)) {
                         vnb o;
 #pragma unroll
                         for (int j = 0; j < NB; ++j) o[j] = acc[i][j][v];
-                        *reinterpret_cast<vnb *>(dst) = o;
+                        *reinterpret_cast<typename VecOf<NB>::gtype *>(dst) = o;
                         done = true;
                     }
                 }
                 if (!done) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        if (!EDGE || (gi < M && gj + j < N)) dst[j] = acc[i][j][v];
+                        if (EDGE == 0 || (gi < M && gj + j < N)) dst[j] = acc[i][j][v];
                 }
             }
         }
@@ -449,9 +456,10 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     extern __shared__ __align__(16) float lds[];
     int batch, tm, tn;
     decode_tile(p, batch, tm, tn);
-    const bool interior = ((tm + 1) * T::BM <= p.M) && ((tn + 1) * T::BN <= p.N);
-    if (interior) gemm_tile<T, false>(p, lds, batch, tm, tn);
-    else gemm_tile<T, true>(p, lds, batch, tm, tn);
+    const bool m_edge = (tm + 1) * T::BM > p.M, n_edge = (tn + 1) * T::BN > p.N;
+    if (!m_edge && !n_edge) gemm_tile<T, 0>(p, lds, batch, tm, tn);
+    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(p, lds, batch, tm, tn);
+    else gemm_tile<T, 1>(p, lds, batch, tm, tn);
 }
 
 // Array packing (Section 6.1): Bp[x][y][z] = opB[y][x*kPanel + z], zero beyond column N.
