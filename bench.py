@@ -21,6 +21,35 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = 157.3      # MI355X fp32 matrix peak: 256 CUs x 2.4 GHz x 256 flop/clk/CU
 HBM_GBS = 8000.0
 
+# HBM traffic of the dominant kernel, from rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch; summaries under profiles/).  Each is scaled by what the same counter reads for a plain copy
+# of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
+# one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
+TRAFFIC = {
+    "sources_sha256": "",
+    "square4096": {"fetch_kib": 0.0, "write_kib": 0.0, "copy_fetch_kib": 1.0, "copy_write_kib": 1.0},
+}
+COPY_KIB = 65536.0
+
+
+def kernel_sources_sha256() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2002_02268_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def traffic_bytes(workload: str):
+    t = TRAFFIC.get(workload)
+    if not t or TRAFFIC["sources_sha256"] != kernel_sources_sha256():
+        return None
+    fetch = t["fetch_kib"] * COPY_KIB / t["copy_fetch_kib"]
+    write = t["write_kib"] * COPY_KIB / t["copy_write_kib"]
+    return int((fetch + write) * 1024)
+
 
 def flops_of(w) -> float:
     b = w["batch"] or 1
@@ -113,10 +142,14 @@ def main() -> int:
     ap.add_argument("--workload", default="square4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only --workload")
+    ap.add_argument("--sources-sha256", action="store_true", help="print the kernel source hash and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
                          "--steps times: the known-size kernel that HBM byte counters are scaled by")
     args = ap.parse_args()
+    if args.sources_sha256:
+        print(kernel_sources_sha256())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
         return 2
@@ -176,7 +209,7 @@ def main() -> int:
                    "transB": w["transB"], "dist": w["dist"], "seed": w["seed"],
                    "variant": binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"])},
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": traffic_bytes(args.workload)},
         "extra": extra,
     }
     if not args.no_cpu_baseline:

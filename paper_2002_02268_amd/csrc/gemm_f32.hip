@@ -85,6 +85,38 @@ int launch_variant(int bmode, int tile, const KArgs &a)
 
 int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+template <int BMODE> int launch_batched64_mode(const BatchArgs &a)
+{
+    constexpr int SB = (BMODE == B_NT) ? 68 : 64;
+    constexpr int lds_bytes = 2 * (64 * 68 + 64 * SB) * 4;
+    static bool attr_set = false;
+    auto kern = batched64_kernel<BMODE>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return fail_hip(e);
+        attr_set = true;
+    }
+    // two workgroups per compute unit (what the LDS holds); more residency does not raise the
+    // achieved bandwidth, which already equals that of a plain device copy
+    const int grid = a.batch < 512 ? a.batch : 512;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, g_stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
+}
+
+int launch_batched64(int64_t batch, const float *A, int64_t lda, int64_t sA, const float *B, int64_t ldb,
+                     int64_t sB, float *C, int64_t ldc, int64_t sC, int transB)
+{
+    BatchArgs a;
+    a.A = A; a.B = B; a.C = C;
+    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.sA = sA; a.sB = sB; a.sC = sC;
+    a.batch = (int)batch;
+    return transB ? launch_batched64_mode<B_NT>(a) : launch_batched64_mode<B_NN>(a);
+}
+
 // Tile choice.  Workgroups spread over 256 compute units, so a launch costs
 // ceil(tiles / 256) rounds of one tile each; a tile costs its area divided by the fraction
 // of the MFMA peak that variant sustains (measured on square problems).  The cheapest wins:
@@ -207,6 +239,13 @@ int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K, const float
                      int64_t strideC, int transB)
 {
     if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    if (M == 64 && N == 64 && K == 64 && batch >= 2 && !std::getenv("GEMMF32_FORCE_TILE")) {
+        // streaming path for many 64^3 products; same argument checks as the general path
+        Plan pl = make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
+                            transB ? B_NT : B_NN);
+        if (pl.status != GEMMF32_OK) return pl.status;
+        return launch_batched64(batch, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, transB);
+    }
     return run_plan(make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
                               transB ? B_NT : B_NN));
 }

@@ -462,6 +462,108 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     else gemm_tile<T, 1>(p, lds, batch, tm, tn);
 }
 
+// Batched 64x64x64 products (one product = 48 KB of traffic for 0.5 MFLOP: bound by HBM, not by the
+// matrix pipe).  A workgroup of 4 waves (one 32x32 block each) walks products w, w + grid, ...;
+// the operands of product i+1 are in flight from global memory while product i is multiplied out
+// of LDS, and C is stored straight from the accumulators.  Two LDS buffers, one barrier per product.
+struct BatchArgs {
+    const float *A;
+    const float *B;
+    float *C;
+    int64_t lda, ldb, ldc;
+    int64_t sA, sB, sC;
+    int batch;
+};
+
+template <int BMODE>   // B_NN or B_NT
+__global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
+{
+    constexpr int SA = 68;                                  // A (and N x K stored B) rows: 64 + 4 pad
+    constexpr int SB = (BMODE == B_NT) ? 68 : 64;
+    constexpr int A_TILE = 64 * SA, B_TILE = 64 * SB, STAGE = A_TILE + B_TILE;
+    extern __shared__ __align__(16) float lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+
+    // load slots: 4 chunks of A and 4 of B per thread, 16 bytes each
+    int64_t ga[4], gb[4];
+    int sa[4], sb[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int f = tid + r * 256;
+        const int row = f >> 4, c = (f & 15) * 4;           // 16 chunks per 64-float row
+        ga[r] = (int64_t)row * p.lda + c;
+        sa[r] = row * SA + c;
+        gb[r] = (int64_t)row * p.ldb + c;
+        sb[r] = row * SB + c;
+    }
+    v4f ra[4], rb[4];
+    auto load_product = [&](int b) {
+        const float *A = p.A + (int64_t)b * p.sA;
+        const float *B = p.B + (int64_t)b * p.sB;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ra[r] = load4(A + ga[r]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rb[r] = load4(B + gb[r]);
+    };
+
+    const int a_frag = (wm0 + l32) * SA + 4 * half;
+    const int b_frag = (BMODE == B_NT) ? (A_TILE + (wn0 + l32) * SB + 4 * half)
+                                       : (A_TILE + 4 * half * SB + wn0 + l32);
+    struct Frag { v4f a; float b[4]; };
+    auto read_frag = [&](Frag &fr, const float *base, int g) {
+        fr.a = *reinterpret_cast<const v4f *>(base + a_frag + 8 * g);
+        if constexpr (BMODE == B_NT) {
+            const v4f t = *reinterpret_cast<const v4f *>(base + b_frag + 8 * g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) fr.b[e] = t[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) fr.b[e] = base[b_frag + (8 * g + e) * SB];
+        }
+    };
+
+    int b = blockIdx.x;
+    if (b >= p.batch) return;
+    load_product(b);
+    int cur = 0;
+    for (; b < p.batch; b += gridDim.x) {
+        float *stage = lds + cur * STAGE;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<v4f *>(stage + sa[r]) = ra[r];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<v4f *>(stage + A_TILE + sb[r]) = rb[r];
+        lds_barrier();
+        const int nb = b + (int)gridDim.x;
+        if (nb < p.batch) load_product(nb);                 // in flight during the multiply
+
+        v16f acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        Frag f0, f1;
+        read_frag(f0, stage, 0);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            Frag &now = (g & 1) ? f1 : f0;
+            Frag &next = (g & 1) ? f0 : f1;
+            if (g + 1 < 8) read_frag(next, stage, g + 1);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(now.a[e], now.b[e], acc, 0, 0, 0);
+        }
+        float *C = p.C + (int64_t)b * p.sC;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int gi = wm0 + 8 * (v / 4) + 4 * half + (v % 4);
+            C[(int64_t)gi * p.ldc + wn0 + l32] = acc[v];
+        }
+        cur ^= 1;
+    }
+}
+
 // Array packing (Section 6.1): Bp[x][y][z] = opB[y][x*kPanel + z], zero beyond column N.
 // One thread per 4 consecutive z; reads are row-contiguous for B stored K x N.
 __global__ void __launch_bounds__(256) pack_b_kernel(const float *__restrict__ B, float *__restrict__ Bp,

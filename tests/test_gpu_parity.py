@@ -374,3 +374,43 @@ def test_batched_poisoned_neighbour_does_not_leak():
     assert np.isnan(C[4]).all()
     for b in (3, 5):
         check_close(C[b], ref[b], 64)
+
+
+@pytest.mark.parametrize("transB", [False, True])
+def test_batched64_streaming_path_many_products_bit_exact(transB):
+    """More products than resident workgroups (each workgroup walks several), a count that is
+    not a multiple of the grid, padded leading dimensions and batch strides, NaN in all padding."""
+    batch = 1100
+    A = synth.small_ints((batch, 64, 64), 82, synth.TENSOR_A)
+    B = synth.small_ints((batch, 64, 64), 82, synth.TENSOR_B)
+    ref = oracle.gemm_f32_batched(A, B, transB=transB, nthreads=NTHREADS)
+    bufA = torch.full((batch, 66, 68), float("nan"), device="cuda")
+    bufB = torch.full((batch, 65, 72), float("nan"), device="cuda")
+    bufC = torch.full((batch, 67, 68), float("nan"), device="cuda")
+    dA, dB, dC = bufA[:, :64, :64], bufB[:, :64, :64], bufC[:, :64, :64]
+    dA.copy_(torch.from_numpy(A))
+    dB.copy_(torch.from_numpy(B))
+    binding.gemm_f32_batched(dA, dB, dC, transB=transB)
+    whole = bufC.cpu().numpy()
+    assert np.array_equal(whole[:, :64, :64].astype(np.float64), ref)
+    assert np.isnan(whole[:, 64:, :]).all() and np.isnan(whole[:, :, 64:]).all()
+    # the same products through the general tiled kernel agree bit for bit in the exact regime
+    os.environ["GEMMF32_FORCE_TILE"] = "3"
+    try:
+        dC2 = torch.full((batch, 64, 64), float("nan"), device="cuda")
+        binding.gemm_f32_batched(dA, dB, dC2, transB=transB)
+        assert np.array_equal(dC2.cpu().numpy().astype(np.float64), ref)
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+def test_batched64_uniform_values_and_two_products():
+    for batch in (2, 3, 513):
+        A = synth.uniform((batch, 64, 64), 83, synth.TENSOR_A)
+        B = synth.uniform((batch, 64, 64), 83, synth.TENSOR_B)
+        ref = oracle.gemm_f32_batched(A, B, nthreads=NTHREADS)
+        dC = torch.full((batch, 64, 64), float("nan"), device="cuda")
+        binding.gemm_f32_batched(dev(A), dev(B), dC)
+        C = dC.cpu().numpy()
+        for b in range(batch):
+            check_close(C[b], ref[b], 64)
