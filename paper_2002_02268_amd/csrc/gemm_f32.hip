@@ -268,11 +268,19 @@ int pack_b(int64_t N, int64_t K, const float *B, int64_t ldb, int transB, float 
     if (B == nullptr || Bp == nullptr) return GEMMF32_ENULL;
     if (B == Bp) return GEMMF32_EALIAS;
     if (!aligned16(Bp)) return GEMMF32_EINVAL;
-    const int64_t total_f4 = cdiv(N, kPanel) * K * (kPanel / 4);
-    const int64_t blocks = cdiv(total_f4, 256);
-    if (blocks > kMaxDim) return GEMMF32_EINVAL;
-    hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)blocks), dim3(256), 0, g_stream, B, Bp, (int)N, (int)K, ldb,
-                       transB, total_f4);
+    if (transB) {
+        const int64_t k_blocks = cdiv(K, 64);
+        const int64_t blocks = cdiv(N, kPanel) * 2 * k_blocks;
+        if (blocks > kMaxDim) return GEMMF32_EINVAL;
+        hipLaunchKernelGGL(pack_b_transposed_kernel, dim3((unsigned)blocks), dim3(256), 0, g_stream, B, Bp, (int)N,
+                           (int)K, ldb, (int)k_blocks);
+    } else {
+        const int64_t total_f4 = cdiv(N, kPanel) * K * (kPanel / 4);
+        const int64_t blocks = cdiv(total_f4, 1024);
+        if (blocks > kMaxDim) return GEMMF32_EINVAL;
+        hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)blocks), dim3(256), 0, g_stream, B, Bp, (int)N, (int)K, ldb,
+                           total_f4);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e);
     return GEMMF32_OK;

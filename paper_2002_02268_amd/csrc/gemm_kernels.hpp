@@ -565,24 +565,82 @@ __global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
 }
 
 // Array packing (Section 6.1): Bp[x][y][z] = opB[y][x*kPanel + z], zero beyond column N.
-// One thread per 4 consecutive z; reads are row-contiguous for B stored K x N.
+// B stored K x N: a re-laid-out copy.  One thread moves four 16-byte pieces (all four loads are
+// issued before the first store); a piece never straddles a panel because kPanel % 4 == 0.
 __global__ void __launch_bounds__(256) pack_b_kernel(const float *__restrict__ B, float *__restrict__ Bp,
-                                                      int N, int K, int64_t ldb, int transB, int64_t total_f4)
+                                                      int N, int K, int64_t ldb, int64_t total_f4)
 {
-    const int64_t f = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (f >= total_f4) return;
     constexpr int F4_ROW = kPanel / 4;
-    const int z = (int)(f % F4_ROW) * 4;
-    const int64_t xy = f / F4_ROW;
-    const int y = (int)(xy % K);
-    const int x = (int)(xy / K);
-    v4f v = {0.f, 0.f, 0.f, 0.f};
+    v4f v[4];
+    int64_t f[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int col = x * kPanel + z + e;
-        if (col < N) v[e] = transB ? B[(int64_t)col * ldb + y] : B[(int64_t)y * ldb + col];
+    for (int i = 0; i < 4; ++i) {
+        f[i] = (int64_t)blockIdx.x * 1024 + i * 256 + threadIdx.x;
+        v[i] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (f[i] < total_f4) {
+            const int z = (int)(f[i] % F4_ROW) * 4;
+            const int64_t xy = f[i] / F4_ROW;
+            const int y = (int)(xy % K);
+            const int col = (int)(xy / K) * kPanel + z;
+            const float *src = B + (int64_t)y * ldb + col;
+            if (col + 3 < N) {
+                v[i] = load4(src);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < N) v[i][e] = src[e];
+            }
+        }
     }
-    *reinterpret_cast<v4f *>(Bp + f * 4) = v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (f[i] < total_f4) *reinterpret_cast<v4f *>(Bp + f[i] * 4) = v[i];
+}
+
+// B stored N x K: the packing is a transpose.  A workgroup moves a 64 (columns of B) x 64 (k)
+// block through LDS: 16-byte global reads along k, 16-byte global writes along z, 4-byte LDS
+// accesses on an odd row stride (at most 2-way bank conflicts either way).
+__global__ void __launch_bounds__(256) pack_b_transposed_kernel(const float *__restrict__ B, float *__restrict__ Bp,
+                                                                 int N, int K, int64_t ldb, int k_blocks)
+{
+    constexpr int S = 65;
+    __shared__ float t[64 * S];                    // t[k][n]
+    const int kb = blockIdx.x % k_blocks;
+    const int nb = blockIdx.x / k_blocks;          // 64-column block: panel nb / 2, half nb % 2
+    const int n0 = nb * 64, k0 = kb * 64;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int f = tid + r * 256;
+        const int n = f >> 4, k = (f & 15) * 4;    // 16 pieces per row of 64 k
+        const int gn = n0 + n, gk = k0 + k;
+        v4f v = {0.f, 0.f, 0.f, 0.f};
+        if (gn < N) {
+            const float *src = B + (int64_t)gn * ldb + gk;
+            if (gk + 3 < K) {
+                v = load4(src);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (gk + e < K) v[e] = src[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[(k + e) * S + n] = v[e];
+    }
+    __syncthreads();
+    float *dst_panel = Bp + (int64_t)(nb >> 1) * K * kPanel + (nb & 1) * 64;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int f = tid + r * 256;
+        const int k = f >> 4, n = (f & 15) * 4;    // 16 pieces per row of 64 columns
+        if (k0 + k < K) {
+            v4f v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = t[k * S + n + e];
+            *reinterpret_cast<v4f *>(dst_panel + (int64_t)(k0 + k) * kPanel + n) = v;
+        }
+    }
 }
 
 }  // namespace gemmf32
