@@ -54,7 +54,7 @@ template <class T> int launch(const KArgs &a)
         if (e != hipSuccess) return fail_hip(e);
         attr_set = true;
     }
-    // a product whose K fits one slab never touches the second LDS buffer
+    // a product whose K fits one slab never touches a second LDS buffer
     const int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
     hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), lds_bytes, g_stream, a);
     hipError_t e = hipGetLastError();

@@ -29,6 +29,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace gemmf32 {
 
 typedef float v2f __attribute__((ext_vector_type(2)));
@@ -121,6 +124,42 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Pins the issue order of the code that precedes it in the same basic block: N_MEM memory
+// instructions (LDS reads, LDS writes, global loads, in program order) are spread evenly over
+// N_MFMA MFMAs instead of being issued in a burst.  A burst from all waves of a workgroup at once
+// fills the LDS queue, and the in-order wave then cannot issue its next MFMA.
+template <int N_MFMA, int N_MEM> __device__ __forceinline__ void spread_memory_between_mfma()
+{
+    constexpr int MEM_MASK = 0x100 | 0x200 | 0x020;   // LDS read | LDS write | global load
+    if constexpr (N_MEM == 0) {
+        return;
+    } else if constexpr (N_MEM <= N_MFMA) {
+        constexpr int STRIDE = N_MFMA / N_MEM;
+#pragma unroll
+        for (int i = 0; i < N_MEM; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, STRIDE, 0);
+            __builtin_amdgcn_sched_group_barrier(MEM_MASK, 1, 0);
+        }
+    } else {
+        constexpr int Q = (N_MEM + N_MFMA - 1) / N_MFMA;
+#pragma unroll
+        for (int i = 0; i < N_MFMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(MEM_MASK, Q, 0);
+        }
+    }
+}
+
 __device__ __forceinline__ v4f load4(const float *src) { return *reinterpret_cast<const v4f_g *>(src); }
 
 // One BM x BN tile.  EDGE = 0: every access is in range.  EDGE = 1: the tile crosses the M
@@ -200,19 +239,20 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     v4f ra[A_ITERS], rb[B_ITERS];
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    // global -> registers, whole slab in range along k
-    auto load_slab = [&]() {
-#pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) {
+    // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B); the slab is in
+    // range along k
+    auto load_slot = [&](auto slot_tag) {
+        constexpr int S = decltype(slot_tag)::value;
+        if constexpr (S < A_ITERS) {
+            constexpr int r = S;
             v4f v = load4(pa[r]);
             if constexpr (EDGE != 0) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
             }
             ra[r] = v;
-        }
-#pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) {
+        } else {
+            constexpr int r = S - A_ITERS;
             v4f v;
             if constexpr (B_ELEMENTWISE) {
 #pragma unroll
@@ -230,6 +270,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             rb[r] = v;
         }
     };
+    auto load_slab = [&]() { static_for<A_ITERS + B_ITERS>(load_slot); };
     // global -> registers for the ragged last slab: kleft (< BK) columns of k remain
     auto load_tail = [&](int kleft) {
 #pragma unroll
@@ -282,6 +323,19 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         for (int r = 0; r < A_ITERS; ++r) *reinterpret_cast<v4f *>(&As[sa_off[r]]) = ra[r];
 #pragma unroll
         for (int r = 0; r < B_ITERS; ++r) *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = rb[r];
+    };
+    // one slot: registers (slab t+1) -> LDS, then request the same slot of slab t+2
+    auto move_slot = [&](auto slot_tag, int stage, int steps) {
+        constexpr int S = decltype(slot_tag)::value;
+        float *As = lds + stage * T::STAGE_FLOATS;
+        if constexpr (S < A_ITERS) {
+            *reinterpret_cast<v4f *>(&As[sa_off[S]]) = ra[S];
+            pa[S] += steps ? BK : 0;
+        } else {
+            *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[S - A_ITERS]]) = rb[S - A_ITERS];
+            pb[S - A_ITERS] += steps ? b_step : (int64_t)0;
+        }
+        load_slot(slot_tag);
     };
 
     // ---- LDS -> fragments -> MFMA -----------------------------------------------------------
@@ -340,55 +394,33 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
     constexpr int N_READ = MB + NBV;               // LDS reads of one fragment set
     constexpr int N_MOVE = A_ITERS + B_ITERS;      // LDS writes (= global loads) of one slab
+    // The slots of a slab are moved in the groups that precede the barrier (all but the last one).
+    constexpr int MOVE_GROUPS = (G > 1) ? G - 1 : 1;
     auto slab_body = [&](const int t, auto more_tag) {
         constexpr bool MORE = decltype(more_tag)::value;
         const int cur = t & 1;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
+        const int steps = (t + 2 < nkf) ? 1 : 0;   // 0: harmless re-request of the last slab
+        static_for<G>([&](auto g_tag) {
+            constexpr int g = decltype(g_tag)::value;
             Frag &now = (g & 1) ? f1 : f0;
             Frag &next = (g & 1) ? f0 : f1;
-            bool reads = false;
-            if (g + 1 < G) {
+            constexpr bool READS = (g + 1 < G) || MORE;
+            if constexpr (g + 1 < G) {
                 read_frag(next, cur, g + 1);
-                reads = true;
-            } else if (MORE) {
+            } else if constexpr (MORE) {
                 lds_barrier();                 // slab t+1 is complete in the other buffer
                 read_frag(next, cur ^ 1, 0);
-                reads = true;
             }
-            if (g == 0 && MORE) {
-                store_slab(cur ^ 1);           // slab t+1, requested one slab ago
-                advance((t + 2 < nkf) ? 1 : 0);   // 0: harmless re-request of the last slab
-                load_slab();                   // slab t+2
+            constexpr int SLOTS = (MORE && g < MOVE_GROUPS) ? (N_MOVE - g + MOVE_GROUPS - 1) / MOVE_GROUPS : 0;
+            if constexpr (SLOTS > 0) {
+                static_for<SLOTS>([&](auto i_tag) {
+                    constexpr int slot = g + decltype(i_tag)::value * MOVE_GROUPS;
+                    move_slot(std::integral_constant<int, slot>{}, cur ^ 1, steps);
+                });
             }
             mfma_group(now);
-            // pin the interleaving of this group's instructions
-            constexpr int SPREAD = 2;          // MFMAs between two memory instructions
-            int used = 0;
-            if (reads) {
-#pragma unroll
-                for (int i = 0; i < N_READ; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-                }
-                used += N_READ;
-            }
-            if (g == 0 && MORE) {
-#pragma unroll
-                for (int i = 0; i < N_MOVE; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, SPREAD, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // LDS write
-                }
-#pragma unroll
-                for (int i = 0; i < N_MOVE; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
-                }
-                used += (SPREAD + 1) * N_MOVE;
-            }
-            (void)used;
-            (void)N_MFMA;
-        }
+            spread_memory_between_mfma<N_MFMA, (READS ? N_READ : 0) + 2 * SLOTS>();
+        });
     };
     if (nkf > 0) {
         load_slab();
