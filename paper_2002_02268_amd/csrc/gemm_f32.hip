@@ -38,9 +38,9 @@ const TileShape kShapes[NUM_TILES] = {
 
 template <int ID, int BMODE> struct Variant;
 template <int BMODE> struct Variant<T256, BMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1> type; };
-template <int BMODE> struct Variant<T128, BMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2> type; };
-template <int BMODE> struct Variant<T64, BMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2> type; };
-template <int BMODE> struct Variant<TB64, BMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2> type; };
+template <int BMODE> struct Variant<T128, BMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2, 2> type; };
+template <int BMODE> struct Variant<T64, BMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2, 2> type; };
+template <int BMODE> struct Variant<TB64, BMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2, 2> type; };
 template <int BMODE> struct Variant<T256x128, BMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2> type; };
 template <int BMODE> struct Variant<T128x256, BMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2> type; };
 
@@ -130,7 +130,7 @@ int choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
     }
     if (M <= 64 && N <= 64 && K <= 64) return TB64;
     static const struct { int id; double eff; } cand[] = {
-        {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {T64, 0.80}};
+        {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {TB64, 0.80}, {T64, 0.78}};
     int best = T64;
     double best_cost = 0;
     for (const auto &c : cand) {

@@ -68,10 +68,12 @@ template <> struct VecOf<4> { typedef v4f type; typedef v4f_g gtype; };
 template <int N> __device__ __forceinline__ float vget(const typename VecOf<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1, int PF_ = 1>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
     static constexpr int BMODE = BMODE_, OCC = OCC_;
+    static constexpr int PF = PF_;                             // slabs held in registers ahead of the LDS write (1 or 2)
+    static_assert(PF_ == 1 || PF_ == 2, "prefetch depth");
     static constexpr int THREADS = 64 * WGM * WGN;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
@@ -175,10 +177,11 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr int NTHR = T::THREADS;
     constexpr int A_ITERS = T::A_ITERS, B_ITERS = T::B_ITERS;
     constexpr int A_F4_ROW = T::A_F4_ROW, B_F4_ROW = T::B_F4_ROW;
-    constexpr int NBV = (T::BMODE == B_NT) ? NB : 4;   // B fragment vectors per 8-column group
+    constexpr bool B_KMAJOR = (T::BMODE == B_NT);           // B fragments are 4 consecutive k of one column
+    constexpr int NBV = B_KMAJOR ? NB : 4;   // B fragment vectors per 8-column group
     constexpr bool B_ELEMENTWISE = (T::BMODE == B_NN && EDGE == 2);
     typedef typename VecOf<NB>::type vnb;
-    typedef typename std::conditional<T::BMODE == B_NT, v4f, vnb>::type bfrag_t;
+    typedef typename std::conditional<B_KMAJOR, v4f, vnb>::type bfrag_t;
 
     const int m0 = tm * BM, n0 = tn * BN;
     const float *__restrict__ A = p.A + (int64_t)batch * p.sA;
@@ -208,10 +211,13 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         const int gi = (m0 + row < M) ? (m0 + row) : (M - 1);
         pa[r] = A + (int64_t)gi * p.lda + c;
     }
+    auto b_slot_row = [&](int r) {          // row of the B slab (k, or n for N x K storage) of slot r
+        return (tid + r * NTHR) / B_F4_ROW;
+    };
 #pragma unroll
     for (int r = 0; r < B_ITERS; ++r) {
         const int f = tid + r * NTHR;
-        const int row = f / B_F4_ROW, c = (f % B_F4_ROW) * 4;
+        const int row = b_slot_row(r), c = (f % B_F4_ROW) * 4;
         sb_off[r] = row * SB + c;
         if constexpr (T::BMODE == B_NT) {
             b_ok[r] = (n0 + row < N);
@@ -236,43 +242,49 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     }
     const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
 
-    v4f ra[A_ITERS], rb[B_ITERS];
+    // Staging registers: PF sets.  Set s holds a slab between its global load and its LDS write.
+    constexpr int PF = T::PF;
+    v4f ra[PF][A_ITERS], rb[PF][B_ITERS];
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B); the slab is in
-    // range along k
-    auto load_slot = [&](auto slot_tag) {
-        constexpr int S = decltype(slot_tag)::value;
+    // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B) of the slab that
+    // starts a_off / b_off elements after slab 0; the slab is in range along k
+    auto load_slot = [&](auto slot_tag, auto set_tag, int64_t a_off, int64_t b_off) {
+        constexpr int S = decltype(slot_tag)::value, SET = decltype(set_tag)::value;
         if constexpr (S < A_ITERS) {
             constexpr int r = S;
-            v4f v = load4(pa[r]);
+            v4f v = load4(pa[r] + a_off);
             if constexpr (EDGE != 0) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
             }
-            ra[r] = v;
+            ra[SET][r] = v;
         } else {
             constexpr int r = S - A_ITERS;
             v4f v;
             if constexpr (B_ELEMENTWISE) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float x = pb[r][b_d[r][e]];
+                    const float x = (pb[r] + b_off)[b_d[r][e]];
                     v[e] = (b_col[r] + e < N) ? x : 0.f;
                 }
             } else {
-                v = load4(pb[r]);
+                v = load4(pb[r] + b_off);
                 if constexpr (EDGE != 0 && T::BMODE != B_NN) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = b_ok[r] ? v[e] : 0.f;
                 }
             }
-            rb[r] = v;
+            rb[SET][r] = v;
         }
     };
-    auto load_slab = [&]() { static_for<A_ITERS + B_ITERS>(load_slot); };
-    // global -> registers for the ragged last slab: kleft (< BK) columns of k remain
-    auto load_tail = [&](int kleft) {
+    auto load_slab = [&](auto set_tag, int slab) {
+        const int64_t a_off = (int64_t)slab * BK, b_off = (int64_t)slab * b_step;
+        static_for<A_ITERS + B_ITERS>([&](auto slot_tag) { load_slot(slot_tag, set_tag, a_off, b_off); });
+    };
+    // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain
+    auto load_tail = [&](int slab, int kleft) {
+        const int64_t a_off = (int64_t)slab * BK, b_off = (int64_t)slab * b_step;
 #pragma unroll
         for (int r = 0; r < A_ITERS; ++r) {
             const int c = ((tid + r * NTHR) % A_F4_ROW) * 4;
@@ -280,62 +292,51 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             if (a_ok[r]) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (c + e < kleft) v[e] = pa[r][e];
+                    if (c + e < kleft) v[e] = (pa[r] + a_off)[e];
             }
-            ra[r] = v;
+            ra[0][r] = v;
         }
 #pragma unroll
         for (int r = 0; r < B_ITERS; ++r) {
-            const int f = tid + r * NTHR;
+            const float *src = pb[r] + b_off;
             v4f v = zero4;
             if constexpr (T::BMODE == B_NT) {
-                const int c = (f % B_F4_ROW) * 4;
+                const int c = ((tid + r * NTHR) % B_F4_ROW) * 4;
                 if (b_ok[r]) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (c + e < kleft) v[e] = pb[r][e];
+                        if (c + e < kleft) v[e] = src[e];
                 }
             } else if constexpr (T::BMODE == B_NN) {
-                const int row = f / B_F4_ROW;
-                if (row < kleft && b_ok[r]) {
+                if (b_slot_row(r) < kleft && b_ok[r]) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (b_col[r] + e < N) v[e] = pb[r][e];   // pb[r] is unclamped when b_ok
+                        if (b_col[r] + e < N) v[e] = src[e];   // pb[r] is unclamped when b_ok
                 }
             } else {
-                const int row = f / B_F4_ROW;
-                if (row < kleft && b_ok[r]) v = load4(pb[r]);
+                if (b_slot_row(r) < kleft && b_ok[r]) v = load4(src);
             }
-            rb[r] = v;
+            rb[0][r] = v;
         }
     };
-    auto advance = [&](int steps) {            // steps is wave-uniform: 0 or 1
-        const int64_t da = steps ? BK : 0, db = steps ? b_step : 0;
-#pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) pa[r] += da;
-#pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) pb[r] += db;
-    };
-    auto store_slab = [&](int stage) {
+    auto store_slab = [&](int stage, auto set_tag) {
+        constexpr int SET = decltype(set_tag)::value;
         float *As = lds + stage * T::STAGE_FLOATS;
         float *Bs = As + T::A_TILE;
 #pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) *reinterpret_cast<v4f *>(&As[sa_off[r]]) = ra[r];
+        for (int r = 0; r < A_ITERS; ++r) *reinterpret_cast<v4f *>(&As[sa_off[r]]) = ra[SET][r];
 #pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = rb[r];
+        for (int r = 0; r < B_ITERS; ++r) *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = rb[SET][r];
     };
-    // one slot: registers (slab t+1) -> LDS, then request the same slot of slab t+2
-    auto move_slot = [&](auto slot_tag, int stage, int steps) {
-        constexpr int S = decltype(slot_tag)::value;
+    // Moving a staged slab into LDS and requesting a later slab into the same registers is a list of
+    // actions executed in order, one per slot: write the slot to LDS, reload it.
+    constexpr int N_ACTIONS = A_ITERS + B_ITERS;
+    auto do_action = [&](auto a_tag, int stage, auto set_tag, int64_t a_off, int64_t b_off) {
+        constexpr int a = decltype(a_tag)::value, SET = decltype(set_tag)::value;
         float *As = lds + stage * T::STAGE_FLOATS;
-        if constexpr (S < A_ITERS) {
-            *reinterpret_cast<v4f *>(&As[sa_off[S]]) = ra[S];
-            pa[S] += steps ? BK : 0;
-        } else {
-            *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[S - A_ITERS]]) = rb[S - A_ITERS];
-            pb[S - A_ITERS] += steps ? b_step : (int64_t)0;
-        }
-        load_slot(slot_tag);
+        if constexpr (a < A_ITERS) *reinterpret_cast<v4f *>(&As[sa_off[a]]) = ra[SET][a];
+        else *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[a - A_ITERS]]) = rb[SET][a - A_ITERS];
+        load_slot(a_tag, set_tag, a_off, b_off);
     };
 
     // ---- LDS -> fragments -> MFMA -----------------------------------------------------------
@@ -378,7 +379,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     float bv;
-                    if constexpr (T::BMODE == B_NT) bv = fr.b[j][e];
+                    if constexpr (B_KMAJOR) bv = fr.b[j][e];
                     else bv = vget<NB>(fr.b[e], j);
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fr.a[i][e], bv, acc[i][j], 0, 0, 0);
                 }
@@ -393,13 +394,20 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     Frag f0, f1;
     constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
     constexpr int N_READ = MB + NBV;               // LDS reads of one fragment set
-    constexpr int N_MOVE = A_ITERS + B_ITERS;      // LDS writes (= global loads) of one slab
-    // The slots of a slab are moved in the groups that precede the barrier (all but the last one).
+    // The actions of a slab run in the groups that precede the barrier (all but the last one),
+    // the same number in each, in order.
     constexpr int MOVE_GROUPS = (G > 1) ? G - 1 : 1;
-    auto slab_body = [&](const int t, auto more_tag) {
+    constexpr int PER_GROUP = (N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
+    // Slab t: multiply it out of LDS buffer t % 2 while
+    // slab t+1 goes from register set (t+1) % PF into the other buffer and slab t+1+PF is requested
+    // into the same registers (past the end: a harmless re-request of the last full slab).
+    auto slab_body = [&](const int t, auto par_tag, auto more_tag) {
+        constexpr int PAR = decltype(par_tag)::value;      // t % 2 when PF == 2 (register set choice)
         constexpr bool MORE = decltype(more_tag)::value;
         const int cur = t & 1;
-        const int steps = (t + 2 < nkf) ? 1 : 0;   // 0: harmless re-request of the last slab
+        typedef std::integral_constant<int, (PAR + 1) % PF> set_t;
+        const int req = (t + 1 + PF < nkf) ? (t + 1 + PF) : (nkf - 1);
+        const int64_t a_off = (int64_t)req * BK, b_off = (int64_t)req * b_step;
         static_for<G>([&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
             Frag &now = (g & 1) ? f1 : f0;
@@ -411,32 +419,55 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 lds_barrier();                 // slab t+1 is complete in the other buffer
                 read_frag(next, cur ^ 1, 0);
             }
-            constexpr int SLOTS = (MORE && g < MOVE_GROUPS) ? (N_MOVE - g + MOVE_GROUPS - 1) / MOVE_GROUPS : 0;
-            if constexpr (SLOTS > 0) {
-                static_for<SLOTS>([&](auto i_tag) {
-                    constexpr int slot = g + decltype(i_tag)::value * MOVE_GROUPS;
-                    move_slot(std::integral_constant<int, slot>{}, cur ^ 1, steps);
+            constexpr int FIRST = g * PER_GROUP;
+            constexpr int COUNT = !MORE ? 0 : (FIRST >= N_ACTIONS ? 0 : (FIRST + PER_GROUP > N_ACTIONS ? N_ACTIONS - FIRST : PER_GROUP));
+            constexpr int MOVE_MEM = 2 * COUNT;    // one LDS write and one global load per action
+            if constexpr (COUNT > 0) {
+                static_for<COUNT>([&](auto i_tag) {
+                    do_action(std::integral_constant<int, FIRST + decltype(i_tag)::value>{}, cur ^ 1, set_t{}, a_off, b_off);
                 });
             }
             mfma_group(now);
-            spread_memory_between_mfma<N_MFMA, (READS ? N_READ : 0) + 2 * SLOTS>();
+            spread_memory_between_mfma<N_MFMA, (READS ? N_READ : 0) + MOVE_MEM>();
         });
     };
+    typedef std::integral_constant<int, 0> i0;
+    typedef std::integral_constant<int, 1> i1;
     if (nkf > 0) {
-        load_slab();
-        store_slab(0);
-        if (nkf > 1) { advance(1); load_slab(); }
+        const int last = nkf - 1;
+        load_slab(i0{}, 0);
+        store_slab(0, i0{});
+        // slab j (1 <= j <= PF) waits in register set j % PF
+        if constexpr (PF == 1) {
+            load_slab(i0{}, last < 1 ? last : 1);
+        } else {
+            load_slab(i1{}, last < 1 ? last : 1);
+            load_slab(i0{}, last < 2 ? last : 2);
+        }
         lds_barrier();
         read_frag(f0, 0, 0);
-        for (int t = 0; t + 1 < nkf; ++t) slab_body(t, std::true_type{});
-        slab_body(nkf - 1, std::false_type{});
+        if constexpr (PF == 1) {
+            for (int t = 0; t + 1 < nkf; ++t) slab_body(t, i0{}, std::true_type{});
+            slab_body(nkf - 1, i0{}, std::false_type{});
+        } else {
+            int t = 0;
+            for (; t + 2 < nkf; t += 2) {
+                slab_body(t, i0{}, std::true_type{});
+                slab_body(t + 1, i1{}, std::true_type{});
+            }
+            if (t + 2 == nkf) {
+                slab_body(t, i0{}, std::true_type{});
+                slab_body(t + 1, i1{}, std::false_type{});
+            } else {
+                slab_body(t, i0{}, std::false_type{});
+            }
+        }
     }
     // ---- ragged last slab (K % BK columns), not pipelined -------------------------------------
     if (kleft > 0) {
-        if (nkf > 0) advance(1);
-        load_tail(kleft);
+        load_tail(nkf, kleft);
         __syncthreads();                           // everyone is done reading both buffers
-        store_slab(0);
+        store_slab(0, i0{});
         __syncthreads();
 #pragma unroll
         for (int g = 0; g < G; ++g) {
