@@ -139,6 +139,46 @@ def cpu_baseline(runner, target_s=12.0):
                       f"{t:.1f} s, fp64 triple loop"}
 
 
+def ladder(torch, binding, synth):
+    """ms per step and TFLOP/s of each ladder level on the two square workloads (median of 5 windows)."""
+    out = {"ladder": {}}
+    for name in ("square1024", "square4096"):
+        w = synth.WORKLOADS[name]
+        A, B = synth.make_operands(name)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        dC = torch.empty((w["M"], w["N"]), device="cuda")
+        dBp = torch.empty(binding.pack_b_size(w["N"], w["K"]) // 4, device="cuda")
+        binding.pack_b(dB, dBp)
+        rows = []
+        for level in range(binding.gemm_f32_ladder_levels()):
+            def step():
+                if level >= 4:
+                    binding.pack_b(dB, dBp)
+                binding.gemm_f32_ladder(level, dA, dB, dC, dBp)
+            step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            once = time.perf_counter() - t0
+            reps = int(max(3, min(500, 0.05 / max(once, 1e-6))))
+            windows = []
+            for _ in range(5):
+                s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                s.record()
+                for _ in range(reps):
+                    step()
+                e.record()
+                torch.cuda.synchronize()
+                windows.append(s.elapsed_time(e) / reps)
+            ms = sorted(windows)[2]
+            rows.append({"level": level, "name": binding.gemm_f32_ladder_name(level), "ms": round(ms, 5),
+                         "tflops": round(flops_of(w) / (ms * 1e-3) / 1e12, 3),
+                         "frac_peak": round(flops_of(w) / (ms * 1e-3) / 1e12 / PEAK_TFLOPS, 4)})
+        out["ladder"][name] = rows
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,6 +187,10 @@ def main() -> int:
     ap.add_argument("--workload", default="square4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only --workload")
+    ap.add_argument("--ladder", action="store_true",
+                    help="time the seven ladder levels (baseline ... parallel) on square1024 and square4096 "
+                         "and print one JSON object; levels 4-6 include pack_b in every step, as the paper's "
+                         "array-packing versions include their packing loop")
     ap.add_argument("--sources-sha256", action="store_true", help="print the kernel source hash and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
@@ -175,6 +219,10 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": "pack_b 4096x4096", "read_bytes": 4096 * 4096 * 4,
                           "write_bytes": 4096 * 4096 * 4, "launches": args.steps}))
+        return 0
+
+    if args.ladder:
+        print(json.dumps(ladder(torch, binding, synth)))
         return 0
 
     main_run = Runner(args.workload)

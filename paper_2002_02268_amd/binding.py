@@ -28,6 +28,10 @@ SYMBOLS = {
     "gemm_f32_last_hip_error": (ctypes.c_int, []),
     "gemm_f32_variant_name": (ctypes.c_char_p, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64,
                                                 ctypes.c_int]),
+    "gemm_f32_ladder_levels": (ctypes.c_int, []),
+    "gemm_f32_ladder_name": (ctypes.c_char_p, [ctypes.c_int]),
+    "gemm_f32_ladder": (ctypes.c_int, [ctypes.c_int, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr, _i64]),
+    "gemm_f32_ladder_set_stream": (ctypes.c_int, [_ptr]),
 }
 
 _lib = None
@@ -153,3 +157,29 @@ def variant_name(M: int, N: int, K: int, lda=None, ldb=None, ldc=None, transB: b
     ldb = ldb or max(K if transB else N, 1)
     ldc = ldc or max(N, 1)
     return lib().gemm_f32_variant_name(M, N, K, None, lda, None, ldb, None, ldc, int(bool(transB))).decode()
+
+
+def gemm_f32_ladder_levels() -> int:
+    return int(lib().gemm_f32_ladder_levels())
+
+
+def gemm_f32_ladder_name(level: int) -> str:
+    return lib().gemm_f32_ladder_name(int(level)).decode()
+
+
+def gemm_f32_ladder(level: int, A, B, C, Bp=None) -> None:
+    """C[:] = A @ B by ladder level `level` (B row-major K x N; Bp: packed B for levels >= 4)."""
+    import torch
+    A = _dev_f32(A, "A", 2)
+    B = _dev_f32(B, "B", 2)
+    C = _dev_f32(C, "C", 2)
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    if level >= 4 and (Bp is None or Bp.numel() * 4 < pack_b_size(N, K)):
+        raise ValueError("levels 4-6 need the packed operand from pack_b")
+    stream = ctypes.c_void_p(torch.cuda.current_stream(C.device).cuda_stream)
+    lib().gemm_f32_ladder_set_stream(stream)
+    _check(lib().gemm_f32_ladder(int(level), M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B),
+                                 Bp.data_ptr() if Bp is not None else None, C.data_ptr(), _ld(C)))

@@ -7,20 +7,23 @@ import re
 
 from paper_2002_02268_amd import binding
 
-HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "gemm_f32.h")
+INCLUDE = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+    names = []
+    for header in sorted(os.listdir(INCLUDE)):
+        text = open(os.path.join(INCLUDE, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
     return sorted(set(names))
 
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("gemm_f32", "gemm_f32_batched", "pack_b", "pack_b_size", "gemm_f32_packed",
-                 "gemm_f32_set_stream", "gemm_f32_strerror", "gemm_f32_last_hip_error"):
+                 "gemm_f32_set_stream", "gemm_f32_strerror", "gemm_f32_last_hip_error",
+                 "gemm_f32_ladder", "gemm_f32_ladder_levels", "gemm_f32_ladder_name"):
         assert must in names
 
 
@@ -48,3 +51,15 @@ def test_host_only_queries():
     assert lib.gemm_f32_batched(0, 4, 4, 4, None, 4, 16, None, 4, 16, None, 4, 16, 0) == 0
     assert binding.variant_name(4096, 4096, 4096).startswith("t256")
     assert binding.variant_name(1000, 1030, 999).endswith("a4")
+
+
+def test_ladder_host_queries():
+    assert binding.gemm_f32_ladder_levels() == 7
+    names = [binding.gemm_f32_ladder_name(i) for i in range(7)]
+    assert names == ["baseline", "blocking", "vectorization", "loop permutation", "array packing",
+                     "cache blocks", "parallel"]
+    assert binding.gemm_f32_ladder_name(7) == "invalid"
+    lib = binding.lib()
+    assert lib.gemm_f32_ladder(9, 4, 4, 4, None, 4, None, 4, None, None, 4) == -1
+    assert lib.gemm_f32_ladder(0, 4, 4, 4, None, 4, None, 4, None, None, 4) == -2
+    assert lib.gemm_f32_ladder(0, 0, 4, 4, None, 4, None, 4, None, None, 4) == 0
