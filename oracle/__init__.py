@@ -17,6 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
+_SRC2 = os.path.join(_HERE, "binomial_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle_gemm.so")
 
 _i64 = ctypes.c_int64
@@ -26,9 +27,10 @@ _dp = ctypes.POINTER(ctypes.c_double)
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (OpenMP only splits independent rows)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
-               "-ffp-contract=off", "-o", _LIB, _SRC]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC2]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -52,6 +54,8 @@ def _load():
         lib.oracle_gemm_f32_packed.argtypes = [_i64, _i64, _i64, _fp, _i64, _fp, _i64, _dp, _i64,
                                                ctypes.c_int]
         lib.oracle_gemm_f32_packed.restype = ctypes.c_int
+        lib.oracle_binomial3x3_f32.argtypes = [_i64, _i64, _fp, _i64, _dp, _i64]
+        lib.oracle_binomial3x3_f32.restype = ctypes.c_int
         lib.oracle_threads_used.argtypes = [ctypes.c_int]
         lib.oracle_threads_used.restype = ctypes.c_int
         _lib = lib
@@ -165,3 +169,15 @@ def gemm_f32_packed(A: np.ndarray, Bp: np.ndarray, N: int, nthreads: int = 1) ->
     if rc != 0:
         raise ValueError(f"oracle_gemm_f32_packed rejected its arguments (rc={rc})")
     return C
+
+
+def binomial3x3_f32(img: np.ndarray) -> np.ndarray:
+    """3x3 binomial filter (weights 1-2-1 x 1-2-1, /16, repeat-edge) of a 2-D float32 image, in float64.
+    Row-strided views are accepted."""
+    img = _f32_2d(img, "img")
+    H, W = img.shape
+    out = np.full((H, W), np.nan, dtype=np.float64)
+    rc = _load().oracle_binomial3x3_f32(H, W, _ptr(img, _fp), _ld(img), _ptr(out, _dp), max(W, 1))
+    if rc != 0:
+        raise ValueError(f"oracle_binomial3x3_f32 rejected its arguments (rc={rc})")
+    return out
