@@ -225,6 +225,34 @@ def main() -> int:
         print(json.dumps(ladder(torch, binding, synth)))
         return 0
 
+    if args.workload.startswith("binomial"):
+        # second workload (3x3 binomial filter): HBM-bound, 8 algorithmic bytes per pixel
+        n = int(args.workload[len("binomial"):] or 8192)
+        img = torch.from_numpy(synth.uniform((n, n), 7, synth.TENSOR_A)).cuda()
+        res = torch.empty_like(img)
+        for _ in range(args.warmup):
+            binding.binomial3x3_f32(img, res)
+        torch.cuda.synchronize()
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        s_ev.record()
+        for _ in range(args.steps):
+            binding.binomial3x3_f32(img, res)
+        e_ev.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ev_ms = s_ev.elapsed_time(e_ev) / args.steps
+        gbs = 8.0 * n * n / (ev_ms * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "3x3 binomial filter Gpixel/s", "value": round(n * n / (wall_ms * 1e-3) / 1e9, 2),
+            "unit": "Gpixel/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": args.workload, "H": n, "W": n, "dist": "uniform", "seed": 7},
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
+                         "frac": round(gbs / HBM_GBS, 4), "traffic": None}}))
+        return 0
+
     main_run = Runner(args.workload)
     w = main_run.w
     wall_ms, ev_ms = main_run.time(args.steps, args.warmup)
@@ -251,6 +279,24 @@ def main() -> int:
                 extra["pack_b_2048"] = {"ms": round(wl, 5),
                                         "algorithmic_GBs": round(8.0 * r.w["N"] * r.w["K"] / (ev * 1e-3) / 1e9, 1)}
             del r
+            torch.cuda.empty_cache()
+
+        for n in (4096, 8192):
+            img = torch.rand(n, n, device="cuda")
+            res = torch.empty_like(img)
+            for _ in range(10):
+                binding.binomial3x3_f32(img, res)
+            torch.cuda.synchronize()
+            s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s_ev.record()
+            for _ in range(100):
+                binding.binomial3x3_f32(img, res)
+            e_ev.record()
+            torch.cuda.synchronize()
+            ms = s_ev.elapsed_time(e_ev) / 100
+            extra[f"binomial3x3_{n}"] = {"ms": round(ms, 5), "algorithmic_GBs": round(8.0 * n * n / (ms * 1e-3) / 1e9, 1),
+                                         "frac_hbm_peak": round(8.0 * n * n / (ms * 1e-3) / 1e9 / HBM_GBS, 4)}
+            del img, res
             torch.cuda.empty_cache()
 
     out = {

@@ -32,6 +32,8 @@ SYMBOLS = {
     "gemm_f32_ladder_name": (ctypes.c_char_p, [ctypes.c_int]),
     "gemm_f32_ladder": (ctypes.c_int, [ctypes.c_int, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr, _i64]),
     "gemm_f32_ladder_set_stream": (ctypes.c_int, [_ptr]),
+    "binomial3x3_f32": (ctypes.c_int, [_i64, _i64, _ptr, _i64, _ptr, _i64]),
+    "binomial3x3_f32_set_stream": (ctypes.c_int, [_ptr]),
 }
 
 _lib = None
@@ -183,3 +185,15 @@ def gemm_f32_ladder(level: int, A, B, C, Bp=None) -> None:
     lib().gemm_f32_ladder_set_stream(stream)
     _check(lib().gemm_f32_ladder(int(level), M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B),
                                  Bp.data_ptr() if Bp is not None else None, C.data_ptr(), _ld(C)))
+
+
+def binomial3x3_f32(img, out) -> None:
+    """out[:] = 3x3 binomial filter of img (2-D float32 device tensors of equal shape; row strides allowed)."""
+    import torch
+    img = _dev_f32(img, "img", 2)
+    out = _dev_f32(out, "out", 2)
+    if tuple(img.shape) != tuple(out.shape):
+        raise ValueError("shape mismatch")
+    H, W = img.shape
+    lib().binomial3x3_f32_set_stream(ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
+    _check(lib().binomial3x3_f32(H, W, img.data_ptr(), _ld(img), out.data_ptr(), _ld(out)))

@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libgemmf32.so")
-SOURCES = ["gemm_f32.hip", "ladder.hip"]
+SOURCES = ["gemm_f32.hip", "ladder.hip", "binomial.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

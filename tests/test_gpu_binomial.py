@@ -1,0 +1,84 @@
+"""GPU parity of binomial3x3_f32 (through the C ABI) against the CPU oracle.
+
+Tolerance: the kernel forms the separated sums in fp32 (at most 8 additions and 5 multiplications by
+small powers of two per pixel, each rounding relative 2^-24 of a partial sum bounded by 16*max|in|,
+then an exact scaling by 1/16): |error| <= 8 * 2^-24 * max|in| < 5e-7 for |in| < 1; the tests allow
+1e-6.  Integer-valued images (|sum| < 2^24) are exact and compared bit for bit."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2002_02268_amd import binding, synth  # noqa: E402
+
+from test_gpu_parity import dev, padded_dev  # noqa: E402
+
+SHAPES = [(1, 1), (1, 9), (7, 1), (3, 3), (33, 70), (65, 1027), (100, 4), (40, 2049), (129, 1024)]
+
+
+@pytest.mark.parametrize("pad", [0, 3, "align4"])
+def test_binomial_small_shapes(pad):
+    for idx, (H, W) in enumerate(SHAPES):
+        print(f"binomial H={H} W={W} pad={pad}", flush=True)
+        img = synth.uniform((H, W), 600 + idx, synth.TENSOR_A)
+        ref = oracle.binomial3x3_f32(img)
+        d_in, _ = padded_dev(img, pad)
+        d_out, buf = padded_dev(np.full((H, W), np.nan, np.float32), pad)
+        binding.binomial3x3_f32(d_in, d_out)
+        whole = buf.cpu().numpy()
+        assert np.isfinite(whole[:, :W]).all()
+        assert np.max(np.abs(whole[:, :W].astype(np.float64) - ref)) <= 1e-6
+        assert np.isnan(whole[:, W:]).all(), "ld padding was written"
+
+
+def test_binomial_integer_images_bit_exact():
+    for idx, (H, W) in enumerate([(70, 130), (33, 1025), (257, 64)]):
+        img = synth.small_ints((H, W), 620 + idx, synth.TENSOR_A, -100, 100)
+        ref = oracle.binomial3x3_f32(img)
+        d_out = torch.full((H, W), float("nan"), device="cuda")
+        binding.binomial3x3_f32(dev(img), d_out)
+        assert np.array_equal(d_out.cpu().numpy().astype(np.float64), ref)
+
+
+def test_binomial_constant_and_impulse():
+    d_out = torch.empty((50, 77), device="cuda")
+    binding.binomial3x3_f32(torch.full((50, 77), 2.5, device="cuda"), d_out)
+    assert torch.equal(d_out, torch.full((50, 77), 2.5, device="cuda"))
+    img = np.zeros((40, 50), np.float32)
+    img[0, 0] = 16.0
+    img[20, 30] = 16.0
+    img[39, 49] = 16.0
+    binding.binomial3x3_f32(dev(img), d_out[:40, :50])
+    got = d_out[:40, :50].cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), oracle.binomial3x3_f32(img))
+    assert got[0, 0] == 9 and got[39, 49] == 9 and got[20, 30] == 4 and got[19, 29] == 1
+
+
+def test_binomial_4096_full_oracle_and_guard_rows():
+    img = synth.uniform((4096, 4096), 640, synth.TENSOR_A)
+    ref = oracle.binomial3x3_f32(img)
+    guard = torch.full((4098, 4096), float("nan"), device="cuda")
+    binding.binomial3x3_f32(dev(img), guard[1:4097])
+    whole = guard.cpu().numpy()
+    assert np.max(np.abs(whole[1:4097].astype(np.float64) - ref)) <= 1e-6
+    assert np.isnan(whole[0]).all() and np.isnan(whole[4097]).all()
+
+
+def test_binomial_empty_and_errors():
+    lib = binding.lib()
+    a = torch.zeros(64, device="cuda")
+    b = torch.zeros(64, device="cuda")
+    assert lib.binomial3x3_f32(0, 8, a.data_ptr(), 8, b.data_ptr(), 8) == 0
+    assert lib.binomial3x3_f32(8, 0, a.data_ptr(), 1, b.data_ptr(), 1) == 0
+    assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 7, b.data_ptr(), 8) == -1
+    assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 8, b.data_ptr(), 7) == -1
+    assert lib.binomial3x3_f32(-1, 8, a.data_ptr(), 8, b.data_ptr(), 8) == -1
+    assert lib.binomial3x3_f32(8, 8, None, 8, b.data_ptr(), 8) == -2
+    assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 8, a.data_ptr(), 8) == -3
+    assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 8, b.data_ptr(), 8) == 0
+    torch.cuda.synchronize()
