@@ -11,7 +11,13 @@
  *
  * Conventions shared by every entry point
  *   - All matrix pointers are DEVICE pointers owned by the caller.  The library
- *     never allocates, frees or retains them.
+ *     never allocates, frees or retains them.  The only device memory the
+ *     library owns is a workspace for products whose output is too small to
+ *     occupy the chip (few tiles, long K): their K range is split, partial
+ *     products go to the workspace and a second pass sums them in a fixed order.
+ *     It is allocated on first need (at most 256 MiB; GEMMF32_ENOMEM if that
+ *     fails), reused, and released by gemm_f32_shutdown.  It is one per process:
+ *     calls that may split K must not run concurrently on different streams.
  *   - Row-major storage with element strides (BLAS style):
  *       A   M x K, element (i,k) at A[i*lda + k],              lda >= max(K,1)
  *       B   transB == 0: K x N, element (k,j) at B[k*ldb + j], ldb >= max(N,1)
@@ -51,7 +57,7 @@ typedef enum {
     GEMMF32_ENULL = -2,   /* a required pointer is NULL */
     GEMMF32_EALIAS = -3,  /* C is the same buffer as A or B */
     GEMMF32_ELAUNCH = -4, /* the HIP runtime refused; see gemm_f32_last_hip_error */
-    GEMMF32_ENOMEM = -5   /* reserved */
+    GEMMF32_ENOMEM = -5   /* the split-K workspace could not be allocated */
 } gemmf32_status;
 
 /*
@@ -109,12 +115,15 @@ int gemm_f32_set_stream(void *hip_stream);
 /* Static, never-NULL description of a status code. */
 const char *gemm_f32_strerror(int status);
 
-/* hipError_t (as int) of the most recent GEMMF32_ELAUNCH on this thread, else 0. */
+/* hipError_t (as int) of the most recent GEMMF32_ELAUNCH / GEMMF32_ENOMEM on this thread, else 0. */
 int gemm_f32_last_hip_error(void);
+
+/* Releases the split-K workspace (waits for the device).  The library stays usable. */
+void gemm_f32_shutdown(void);
 
 /*
  * Which kernel variant the dispatcher would run for a shape, as a static
- * string such as "t256x256x16/nn/a16" (diagnostics for benchmarks; the
+ * string such as "t256x256x16/nn/a16" or "t64x64x64/nn/a16/splitk32" (diagnostics for benchmarks; the
  * pointers are only inspected for alignment and may be NULL for "aligned").
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,

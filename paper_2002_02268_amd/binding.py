@@ -26,6 +26,7 @@ SYMBOLS = {
     "gemm_f32_set_stream": (ctypes.c_int, [_ptr]),
     "gemm_f32_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "gemm_f32_last_hip_error": (ctypes.c_int, []),
+    "gemm_f32_shutdown": (None, []),
     "gemm_f32_variant_name": (ctypes.c_char_p, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64,
                                                 ctypes.c_int]),
     "gemm_f32_ladder_levels": (ctypes.c_int, []),

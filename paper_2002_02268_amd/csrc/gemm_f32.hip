@@ -117,28 +117,56 @@ int launch_batched64(int64_t batch, const float *A, int64_t lda, int64_t sA, con
     return transB ? launch_batched64_mode<B_NT>(a) : launch_batched64_mode<B_NN>(a);
 }
 
-// Tile choice.  Workgroups spread over 256 compute units, so a launch costs
-// ceil(tiles / 256) rounds of one tile each; a tile costs its area divided by the fraction
-// of the MFMA peak that variant sustains (measured on square problems).  The cheapest wins:
-// big tiles when they fill the chip evenly, smaller ones when the last round would be
-// mostly empty or the output is small.
-int choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
+// Tile and split choice.  Workgroups spread over 256 compute units, so a launch costs
+// ceil(workgroups / 256) rounds of one tile each.  A tile over a K range of length k costs
+// 2*BM*BN*(k + kOverheadK) flops at the fraction of one compute unit's MFMA peak (0.6144 Tflop/s)
+// that the variant sustains (measured on square problems); kOverheadK stands for the first-slab
+// latency and the epilogue.  Splitting K into S ranges multiplies the workgroups by S and adds a
+// second pass that sums S partial products.  The cheapest (variant, S) wins: big tiles when they
+// fill the chip evenly, smaller ones when the last round would be mostly empty, a K split when
+// the output alone cannot occupy the chip.
+constexpr double kCuFlopsPerUs = 157.3e6 / 256.0;
+constexpr double kOverheadK = 256.0;
+constexpr int64_t kMaxWorkspaceBytes = 256LL << 20;
+
+struct Choice { int tile; int split; };
+
+Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
 {
+    int forced_tile = -1, forced_split = -1;
     if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
         int t = std::atoi(f);
-        if (t >= 0 && t < NUM_TILES) return t;
+        if (t >= 0 && t < NUM_TILES) forced_tile = t;
     }
-    if (M <= 64 && N <= 64 && K <= 64) return TB64;
+    if (const char *f = std::getenv("GEMMF32_FORCE_SPLITK")) {
+        int t = std::atoi(f);
+        if (t >= 1 && t <= 256) forced_split = t;
+    }
     static const struct { int id; double eff; } cand[] = {
         {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {TB64, 0.80}, {T64, 0.78}};
-    int best = T64;
-    double best_cost = 0;
+    Choice best = {TB64, 1};
+    double best_cost = -1;
     for (const auto &c : cand) {
+        if (forced_tile >= 0 && c.id != forced_tile) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
-        const double cost = (double)cdiv(tiles, 256) * sh.bm * sh.bn / c.eff;
-        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = c.id; }
+        for (int S = 1; S <= 64; S *= 2) {
+            if (forced_split >= 1) S = forced_split;
+            if (S > 1) {
+                // every range holds whole slabs and at least two of them; one product only
+                if (batch != 1 || K < (int64_t)S * 2 * sh.bk) break;
+                if ((int64_t)S * M * N * 4 > kMaxWorkspaceBytes) break;
+            }
+            const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
+            double cost = (double)cdiv(tiles * S, 256) * 2.0 * sh.bm * sh.bn * (k_range + kOverheadK) /
+                          (kCuFlopsPerUs * c.eff);
+            if (S > 1) cost += 6.0 + (double)(S + 1) * M * N * 4.0 / 3.0e6;   // second pass: launch + traffic at 3 TB/s
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
+            if (forced_split >= 1) break;
+        }
     }
+    if (best_cost < 0 && forced_tile >= 0) best = {forced_tile, 1};   // forced split did not fit: no split
+    if (M <= 64 && N <= 64 && K <= 64 && forced_tile < 0) best = {TB64, 1};
     return best;
 }
 
@@ -157,9 +185,36 @@ struct Plan {
     int status;
     bool launch;
     int bmode, tile;
+    int split;           // K ranges (1: no split)
+    int64_t user_ldc;    // leading dimension of the caller's C (args.ldc is the workspace's when split)
     bool vec;
     KArgs args;
 };
+
+// Workspace of the split-K first pass (S dense M x N partial products).  Owned by the library, grown
+// on demand, freed by gemm_f32_shutdown.  One per process: calls that split K must not overlap.
+float *g_workspace = nullptr;
+size_t g_workspace_bytes = 0;
+
+int ensure_workspace(size_t bytes)
+{
+    if (bytes <= g_workspace_bytes) return GEMMF32_OK;
+    if (g_workspace != nullptr) {
+        hipError_t e = hipFree(g_workspace);   // waits for work that may still use it
+        g_workspace = nullptr;
+        g_workspace_bytes = 0;
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&g_workspace), bytes);
+    if (e != hipSuccess) {
+        g_workspace = nullptr;
+        (void)hipGetLastError();
+        g_last_hip_error = (int)e;
+        return GEMMF32_ENOMEM;
+    }
+    g_workspace_bytes = bytes;
+    return GEMMF32_OK;
+}
 
 int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                  const float *B, const float *C, int64_t ldc)
@@ -189,10 +244,12 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (batch > 1 && (sA < 0 || sB < 0 || sC < 0)) { pl.status = GEMMF32_EINVAL; return pl; }
     if (batch == 0 || M == 0 || N == 0) return pl;  // nothing to do
 
-    pl.tile = choose_tile(batch, M, N, K);
+    const Choice ch = choose_tile(batch, M, N, K);
+    pl.tile = ch.tile;
+    pl.split = ch.split;
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
     const int64_t tiles_m = cdiv(M, bm), tiles_n = cdiv(N, bn);
-    const int64_t total = batch * tiles_m * tiles_n;
+    const int64_t total = (pl.split > 1 ? pl.split : batch) * tiles_m * tiles_n;
     if (total > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
 
     bool vec = aligned16(A) && aligned16(C) && lda % 4 == 0 && ldc % 4 == 0;
@@ -200,6 +257,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (batch > 1) vec = vec && sA % 4 == 0 && sC % 4 == 0 && (bmode == B_PACKED || sB % 4 == 0);
     pl.vec = vec;
 
+    pl.user_ldc = ldc;
     KArgs &a = pl.args;
     a.A = A; a.B = B; a.C = C;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
@@ -210,6 +268,23 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.total_tiles = (int)total;
     a.group_m = choose_group_m((int)tiles_m, (int)tiles_n, batch > 1 ? tiles_m * tiles_n : total);
     a.n_padded = (int)(cdiv(N, kPanel) * kPanel);
+    a.k_total = 0;
+    a.k_panel = (int)K;
+    if (pl.split > 1) {
+        // K ranges of whole slabs; range s starts k_range columns (rows of B) after range s-1 and
+        // writes the dense partial product s of the workspace (pointer filled in by run_plan)
+        const int bk = kShapes[pl.tile].bk;
+        const int64_t k_range = cdiv(cdiv(K, pl.split), bk) * bk;
+        pl.split = (int)cdiv(K, k_range);           // ranges that are not empty
+        a.K = (int)k_range;
+        a.k_total = (int)K;
+        a.sA = k_range;
+        a.sB = (bmode == B_NN) ? k_range * ldb : (bmode == B_NT ? k_range : k_range * kPanel);
+        a.sC = M * N;
+        a.ldc = N;
+        a.total_tiles = (int)(pl.split * tiles_m * tiles_n);
+        if (pl.split == 1) { a.K = (int)K; a.k_total = 0; a.sA = a.sB = a.sC = 0; a.ldc = ldc; }
+    }
     pl.launch = true;
     return pl;
 }
@@ -218,7 +293,23 @@ int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
-    return launch_variant(pl.bmode, pl.tile, pl.args);
+    if (pl.split <= 1) return launch_variant(pl.bmode, pl.tile, pl.args);
+    // split K: partial products into the workspace, then one pass that sums them in order
+    KArgs a = pl.args;
+    const int64_t mn = (int64_t)a.M * a.N;
+    int rc = ensure_workspace((size_t)pl.split * mn * sizeof(float));
+    if (rc != GEMMF32_OK) return rc;
+    float *C = a.C;
+    const int64_t ldc = pl.user_ldc;
+    a.C = g_workspace;
+    rc = launch_variant(pl.bmode, pl.tile, a);
+    if (rc != GEMMF32_OK) return rc;
+    const int64_t chunks = (int64_t)a.M * ((a.N + 3) / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv(chunks, 256)), dim3(256), 0, g_stream, g_workspace, C,
+                       a.M, a.N, ldc, pl.split);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
 }
 
 thread_local char g_variant_buf[64];
@@ -314,6 +405,13 @@ const char *gemm_f32_strerror(int status)
 
 int gemm_f32_last_hip_error(void) { return g_last_hip_error; }
 
+void gemm_f32_shutdown(void)
+{
+    if (g_workspace != nullptr) (void)hipFree(g_workspace);
+    g_workspace = nullptr;
+    g_workspace_bytes = 0;
+}
+
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                   int64_t ldb, const float *C, int64_t ldc, int transB)
 {
@@ -324,8 +422,12 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
-    std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
-                  pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4");
+    if (pl.split > 1)
+        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/splitk%d", kShapes[pl.tile].name,
+                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.split);
+    else
+        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
+                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4");
     return g_variant_buf;
 }
 

@@ -58,6 +58,9 @@ struct KArgs {
     int tiles_per_batch;     // tiles_m * tiles_n
     int total_tiles;         // tiles_per_batch * batch == gridDim.x
     int n_padded;            // packed B: number of columns present in the buffer
+    int k_total;             // split-K: length of the whole reduction (0: no split).  The "batch" index
+                             // then counts K ranges of length K; the last one may be shorter
+    int k_panel;             // packed B: rows per panel (the whole K, also when split)
 };
 
 template <int N> struct VecOf;
@@ -187,7 +190,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const float *__restrict__ A = p.A + (int64_t)batch * p.sA;
     const float *__restrict__ B = p.B + (int64_t)batch * p.sB;
     float *__restrict__ C = p.C + (int64_t)batch * p.sC;
-    const int M = p.M, N = p.N, K = p.K;
+    const int M = p.M, N = p.N;
+    // split-K: this workgroup reduces over K range number `batch` (strides sA / sB step along k)
+    const int K = (p.k_total > 0 && p.k_total - batch * p.K < p.K) ? (p.k_total - batch * p.K) : p.K;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -237,7 +242,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             b_col[r] = gj;
             b_ok[r] = (gj < p.n_padded);
             const int gjc = (gj < p.n_padded) ? gj : 0;
-            pb[r] = B + ((int64_t)(gjc / kPanel) * K + row) * kPanel + (gjc % kPanel);
+            pb[r] = B + ((int64_t)(gjc / kPanel) * p.k_panel + row) * kPanel + (gjc % kPanel);
         }
     }
     const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
@@ -624,6 +629,33 @@ __global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
             C[(int64_t)gi * p.ldc + wn0 + l32] = acc[v];
         }
         cur ^= 1;
+    }
+}
+
+// Split-K second pass: C[i][j] = sum over the S partial products W[s][i][j] (dense M x N each), s
+// ascending, so the result does not depend on how the first pass was scheduled.
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ W, float *__restrict__ C,
+                                                             int M, int N, int64_t ldc, int S)
+{
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;      // first of 4 elements of a row
+    const int64_t mn = (int64_t)M * N;
+    const int n4 = (N + 3) / 4;
+    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (chunk >= (int64_t)M * n4) return;
+    const int i = (int)(chunk / n4), j = (int)(chunk % n4) * 4;
+    (void)e;
+    const float *src = W + (int64_t)i * N + j;
+    float *dst = C + (int64_t)i * ldc + j;
+    if (j + 3 < N) {
+        v4f acc = load4(src);
+        for (int s = 1; s < S; ++s) acc += load4(src + s * mn);
+        *reinterpret_cast<v4f_g *>(dst) = acc;
+    } else {
+        for (int c = 0; j + c < N; ++c) {
+            float acc = src[c];
+            for (int s = 1; s < S; ++s) acc += src[s * mn + c];
+            dst[c] = acc;
+        }
     }
 }
 

@@ -414,3 +414,71 @@ def test_batched64_uniform_values_and_two_products():
         C = dC.cpu().numpy()
         for b in range(batch):
             check_close(C[b], ref[b], 64)
+
+
+# --------------------------------------------------------------------- split-K (few tiles, long K)
+
+@pytest.mark.parametrize("transB", [False, True])
+def test_split_k_small_outputs_long_k(transB):
+    """Outputs too small to occupy the chip: the dispatcher splits K; the second pass sums the
+    partial products in a fixed order.  Ragged M, N and K, padded C with NaN guards."""
+    for idx, (M, N, K) in enumerate([(128, 128, 8192), (100, 70, 5003), (64, 64, 4096), (33, 257, 3000)]):
+        name = binding.variant_name(M, N, K, transB=transB)
+        assert "splitk" in name, name
+        print(f"split-K {name} M={M} N={N} K={K} transB={transB}", flush=True)
+        A = synth.uniform((M, K), 700 + idx, synth.TENSOR_A)
+        B = synth.uniform((N, K) if transB else (K, N), 700 + idx, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+        dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), 3)
+        binding.gemm_f32(dev(A), dev(B), dC, transB=transB)
+        whole = bufC.cpu().numpy()
+        check_close(whole[:, :N], ref, K)
+        assert np.isnan(whole[:, N:]).all()
+
+
+@pytest.mark.parametrize("split", [2, 3, 5, 16])
+def test_split_k_forced_factors_bit_exact_and_deterministic(split):
+    """Any split factor gives the exact result on integer operands (also through packed B), and the
+    same bits on every run for float operands."""
+    os.environ["GEMMF32_FORCE_SPLITK"] = str(split)
+    try:
+        M, N, K = 150, 200, 2000
+        A = synth.small_ints((M, K), 710, synth.TENSOR_A)
+        B = synth.small_ints((K, N), 710, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+        dA, dB = dev(A), dev(B)
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(dA, dB, dC)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+        dC.fill_(float("nan"))
+        binding.gemm_f32(dA, dev(B.T), dC, transB=True)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+        dBp = torch.empty(binding.pack_b_size(N, K) // 4, device="cuda")
+        binding.pack_b(dB, dBp)
+        dC.fill_(float("nan"))
+        binding.gemm_f32_packed(dA, dBp, dC)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+        Af = synth.uniform((M, K), 711, synth.TENSOR_A)
+        Bf = synth.uniform((K, N), 711, synth.TENSOR_B)
+        dAf, dBf = dev(Af), dev(Bf)
+        outs = []
+        for _ in range(3):
+            dC.fill_(float("nan"))
+            binding.gemm_f32(dAf, dBf, dC)
+            outs.append(dC.cpu().numpy())
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+        check_close(outs[0], oracle.gemm_f32(Af, Bf, nthreads=NTHREADS), K)
+    finally:
+        os.environ.pop("GEMMF32_FORCE_SPLITK", None)
+
+
+def test_shutdown_releases_workspace_and_library_stays_usable():
+    A = synth.uniform((64, 4096), 720, synth.TENSOR_A)
+    B = synth.uniform((4096, 64), 720, synth.TENSOR_B)
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dC = torch.empty((64, 64), device="cuda")
+    for _ in range(2):
+        binding.gemm_f32(dev(A), dev(B), dC)
+        check_close(dC.cpu().numpy(), ref, 4096)
+        torch.cuda.synchronize()
+        binding.lib().gemm_f32_shutdown()
