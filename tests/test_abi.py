@@ -50,7 +50,7 @@ def test_host_only_queries():
     assert lib.gemm_f32(0, 4, 4, None, 4, None, 4, None, 4, 0) == 0
     assert lib.gemm_f32_batched(0, 4, 4, 4, None, 4, 16, None, 4, 16, None, 4, 16, 0) == 0
     assert binding.variant_name(4096, 4096, 4096).startswith("t256")
-    assert binding.variant_name(1000, 1030, 999).endswith("a4")
+    assert "/a4" in binding.variant_name(1000, 1030, 999)
 
 
 def test_ladder_host_queries():
