@@ -186,6 +186,7 @@ struct Plan {
     bool launch;
     int bmode, tile;
     int split;           // K ranges (1: no split)
+    int tail_tiles;      // tiles of the last round that are split along K (0: none)
     int64_t user_ldc;    // leading dimension of the caller's C (args.ldc is the workspace's when split)
     bool vec;
     KArgs args;
@@ -270,6 +271,32 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.n_padded = (int)(cdiv(N, kPanel) * kPanel);
     a.k_total = 0;
     a.k_panel = (int)K;
+    a.tail_first = (int)total;
+    a.tail_split = 1;
+    a.tail_k = 0;
+    a.tail_slots = nullptr;
+    pl.tail_tiles = 0;
+    // Split tail: when the last round of tiles would leave most compute units idle, its tiles are
+    // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
+    // 16 become 256 pieces that run beside the full round).
+    if (pl.split == 1 && batch == 1 && total > 256 && total % 256 != 0 && total % 256 <= 128 &&
+        !std::getenv("GEMMF32_NO_TAIL_SPLIT")) {
+        const int bk = kShapes[pl.tile].bk;
+        const int64_t tail = total % 256, units = cdiv(K, bk);
+        int64_t S = 256 / tail;
+        if (S > units) S = units;
+        const int64_t units_per_piece = cdiv(units, S);
+        S = cdiv(units, units_per_piece);                    // no empty pieces
+        // worth it when a whole tile costs more than a piece plus the second pass
+        const double t_full = 2.0 * bm * bn * ((double)K + kOverheadK), t_piece = 2.0 * bm * bn * ((double)units_per_piece * bk + kOverheadK);
+        if (S > 1 && (t_full - t_piece) / (kCuFlopsPerUs * 0.8) > 8.0 && tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
+            a.tail_first = (int)(total - tail);
+            a.tail_split = (int)S;
+            a.tail_k = (int)(units_per_piece * bk);
+            a.total_tiles = (int)(total - tail + tail * S);
+            pl.tail_tiles = (int)tail;
+        }
+    }
     if (pl.split > 1) {
         // K ranges of whole slabs; range s starts k_range columns (rows of B) after range s-1 and
         // writes the dense partial product s of the workspace (pointer filled in by run_plan)
@@ -293,6 +320,20 @@ int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
+    if (pl.split <= 1 && pl.tail_tiles > 0) {
+        const TileShape &sh = kShapes[pl.tile];
+        KArgs a = pl.args;
+        int rc = ensure_workspace((size_t)pl.tail_tiles * a.tail_split * sh.bm * sh.bn * sizeof(float));
+        if (rc != GEMMF32_OK) return rc;
+        a.tail_slots = g_workspace;
+        rc = launch_variant(pl.bmode, pl.tile, a);
+        if (rc != GEMMF32_OK) return rc;
+        hipLaunchKernelGGL(tail_reduce_kernel, dim3((unsigned)(pl.tail_tiles * (sh.bm * sh.bn / 1024))), dim3(256), 0,
+                           g_stream, a, sh.bm, sh.bn);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail_hip(e);
+        return GEMMF32_OK;
+    }
     if (pl.split <= 1) return launch_variant(pl.bmode, pl.tile, pl.args);
     // split K: partial products into the workspace, then one pass that sums them in order
     KArgs a = pl.args;
@@ -422,7 +463,10 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
-    if (pl.split > 1)
+    if (pl.tail_tiles > 0)
+        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/tail%dx%d", kShapes[pl.tile].name,
+                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles, pl.args.tail_split);
+    else if (pl.split > 1)
         std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/splitk%d", kShapes[pl.tile].name,
                       pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.split);
     else

@@ -61,6 +61,11 @@ struct KArgs {
     int k_total;             // split-K: length of the whole reduction (0: no split).  The "batch" index
                              // then counts K ranges of length K; the last one may be shorter
     int k_panel;             // packed B: rows per panel (the whole K, also when split)
+    // Split tail: the tiles of the last, partly filled round (walk positions >= tail_first) are each
+    // cut into tail_split K ranges of tail_k columns, so that the round occupies the whole chip; the
+    // pieces go to dense BM x BN slots and tail_reduce_kernel sums them.  tail_split <= 1: off.
+    int tail_first, tail_split, tail_k;
+    float *tail_slots;
 };
 
 template <int N> struct VecOf;
@@ -103,14 +108,15 @@ struct Tile {
 // robin; ids are renumbered so that each XCD (own L2) receives one contiguous run of the
 // tile walk, and the walk goes down `group_m` tile rows before moving one tile column so
 // that a run forms a compact rectangle sharing rows of A and columns of B.
-__device__ __forceinline__ void decode_tile(const KArgs &p, int &batch, int &tm, int &tn)
+__device__ __forceinline__ int xcd_contiguous_id(int wg, int total)
 {
-    const int wg = blockIdx.x;
-    const int chunk = p.total_tiles >> 3, rem = p.total_tiles & 7;
+    const int chunk = total >> 3, rem = total & 7;
     const int x = wg & 7, q = wg >> 3;
-    const int logical = x * chunk + (x < rem ? x : rem) + q;
-    batch = logical / p.tiles_per_batch;
-    const int t = logical - batch * p.tiles_per_batch;
+    return x * chunk + (x < rem ? x : rem) + q;
+}
+// position t of the tile walk of one product -> tile row / column
+__device__ __forceinline__ void tile_coords(const KArgs &p, int t, int &tm, int &tn)
+{
     const int gsz = p.group_m * p.tiles_n;
     const int grp = t / gsz;
     const int first_m = grp * p.group_m;
@@ -172,9 +178,15 @@ __device__ __forceinline__ v4f load4(const float *src) { return *reinterpret_cas
 // range or not.  EDGE = 2 (B stored K x N only): the tile crosses the N boundary, chunks of a
 // row of B may be partly in range.  Out-of-range operands are loaded from a clamped (valid)
 // address and replaced by zero with a select, so the steady-state loop stays branch free.
-template <class T, int EDGE>
+// EDGE = 3: the tile crosses a boundary of a matrix that is at least one tile long in that
+// dimension: its origin is moved back so that it ends at the boundary, every load is in range as
+// for EDGE = 0, and only the rows and columns the tile owns are stored (the others belong to its
+// neighbour, which computes the same values).
+template <class T, int EDGE_MODE>
 __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
 {
+    constexpr bool SHIFTED = (EDGE_MODE == 3);
+    constexpr int EDGE = SHIFTED ? 0 : EDGE_MODE;            // how the loads treat the boundaries
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
     constexpr int MB = T::MB, NB = T::NB, SA = T::SA, SB = T::SB;
     constexpr int NTHR = T::THREADS;
@@ -186,7 +198,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     typedef typename VecOf<NB>::type vnb;
     typedef typename std::conditional<B_KMAJOR, v4f, vnb>::type bfrag_t;
 
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m_own = tm * BM, n_own = tn * BN;               // first row / column this tile stores
+    const int m0 = (SHIFTED && m_own + BM > p.M) ? p.M - BM : m_own;
+    const int n0 = (SHIFTED && n_own + BN > p.N) ? p.N - BN : n_own;
     const float *__restrict__ A = p.A + (int64_t)batch * p.sA;
     const float *__restrict__ B = p.B + (int64_t)batch * p.sB;
     float *__restrict__ C = p.C + (int64_t)batch * p.sC;
@@ -484,6 +498,8 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     }
 
     // ---- epilogue: accumulators -> C (overwrite; predicated at the M / N edges) ---------------
+    auto row_ok = [&](int gi) { return SHIFTED ? gi >= m_own : (EDGE == 0 || gi < M); };
+    auto cols_ok = [&](int gj, int n) { return SHIFTED ? gj >= n_own : (EDGE == 0 || gj + n <= N); };
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
@@ -493,14 +509,14 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int gj = n0 + wn0 + 32 * j + l32;
-                    if (EDGE == 0 || (gi < M && gj < N)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
+                    if (row_ok(gi) && cols_ok(gj, 1)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
                 }
             } else {
                 const int gj = n0 + wn0 + NB * l32;
                 float *dst = C + (int64_t)gi * p.ldc + gj;
                 bool done = false;
                 if constexpr (NB > 1) {
-                    if (EDGE == 0 || (gi < M && gj + NB <= N)) {
+                    if (row_ok(gi) && cols_ok(gj, NB)) {
                         vnb o;
 #pragma unroll
                         for (int j = 0; j < NB; ++j) o[j] = acc[i][j][v];
@@ -511,7 +527,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 if (!done) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        if (EDGE == 0 || (gi < M && gj + j < N)) dst[j] = acc[i][j][v];
+                        if (row_ok(gi) && cols_ok(gj + j, 1)) dst[j] = acc[i][j][v];
                 }
             }
         }
@@ -523,11 +539,64 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 {
     extern __shared__ __align__(16) float lds[];
     int batch, tm, tn;
-    decode_tile(p, batch, tm, tn);
+    KArgs q = p;
+    // whole tiles first, then the pieces of the split tail; each kind is spread over the XCDs separately
+    const bool is_piece = p.tail_split > 1 && (int)blockIdx.x >= p.tail_first;
+    const int logical = is_piece ? 0 : xcd_contiguous_id(blockIdx.x, p.tail_split > 1 ? p.tail_first : p.total_tiles);
+    if (is_piece) {
+        // one K range of one tile of the last round -> its slot
+        const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.total_tiles - p.tail_first);
+        const int t = piece / p.tail_split, s = piece - t * p.tail_split;
+        tile_coords(p, p.tail_first + t, tm, tn);
+        batch = 0;
+        const int k0 = s * p.tail_k;
+        q.K = (p.K - k0 < p.tail_k) ? (p.K - k0) : p.tail_k;
+        q.A = p.A + k0;
+        q.B = p.B + (T::BMODE == B_NN ? (int64_t)k0 * p.ldb : (T::BMODE == B_NT ? (int64_t)k0 : (int64_t)k0 * kPanel));
+        // dense BM x BN slot, addressed so that element (m0 + r, n0 + c) lands at r*BN + c
+        float *slot = p.tail_slots + (int64_t)piece * (T::BM * T::BN);
+        q.C = slot - ((int64_t)tm * T::BM * T::BN + (int64_t)tn * T::BN);
+        q.ldc = T::BN;
+    } else {
+        batch = logical / p.tiles_per_batch;
+        tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
+    }
     const bool m_edge = (tm + 1) * T::BM > p.M, n_edge = (tn + 1) * T::BN > p.N;
-    if (!m_edge && !n_edge) gemm_tile<T, 0>(p, lds, batch, tm, tn);
-    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(p, lds, batch, tm, tn);
-    else gemm_tile<T, 1>(p, lds, batch, tm, tn);
+    // an edge tile can be moved back inside the matrix unless the matrix is shorter than a tile
+    // (packed B: columns come in whole panels, so only rows move)
+    const bool can_shift = (!m_edge || p.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && p.N >= T::BN));
+    if (!m_edge && !n_edge) gemm_tile<T, 0>(q, lds, batch, tm, tn);
+    else if (can_shift) gemm_tile<T, 3>(q, lds, batch, tm, tn);
+    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
+    else gemm_tile<T, 1>(q, lds, batch, tm, tn);
+}
+
+// Sums the K ranges of the split tail tiles in ascending k and stores them into C.
+// One workgroup per (tail tile, 1024-element chunk of the tile).
+__global__ void __launch_bounds__(256) tail_reduce_kernel(const KArgs p, int BM, int BN)
+{
+    const int chunks_per_tile = BM * BN / 1024;
+    const int t = blockIdx.x / chunks_per_tile, chunk = blockIdx.x % chunks_per_tile;
+    int tm, tn;
+    tile_coords(p, p.tail_first + t, tm, tn);
+    const int e = chunk * 1024 + threadIdx.x * 4;            // element of the tile: row e / BN, 4 columns
+    const int r = e / BN, c = e % BN;
+    const int gi = tm * BM + r, gj = tn * BN + c;
+    if (gi >= p.M || gj >= p.N) return;
+    const float *slot = p.tail_slots + (int64_t)t * p.tail_split * (BM * BN) + e;
+    float *dst = p.C + (int64_t)gi * p.ldc + gj;
+    if (gj + 3 < p.N) {
+        v4f acc = *reinterpret_cast<const v4f *>(slot);
+#pragma unroll 8
+        for (int s = 1; s < p.tail_split; ++s) acc += *reinterpret_cast<const v4f *>(slot + (int64_t)s * (BM * BN));
+        *reinterpret_cast<v4f_g *>(dst) = acc;
+    } else {
+        for (int j = 0; gj + j < p.N; ++j) {
+            float acc = slot[j];
+            for (int s = 1; s < p.tail_split; ++s) acc += slot[(int64_t)s * (BM * BN) + j];
+            dst[j] = acc;
+        }
+    }
 }
 
 // Batched 64x64x64 products (one product = 48 KB of traffic for 0.5 MFLOP: bound by HBM, not by the

@@ -482,3 +482,53 @@ def test_shutdown_releases_workspace_and_library_stays_usable():
         check_close(dC.cpu().numpy(), ref, 4096)
         torch.cuda.synchronize()
         binding.lib().gemm_f32_shutdown()
+
+# --------------------------------------------------------------------- split tail (uneven tile counts)
+
+@pytest.mark.parametrize("tile", ["t128", "t64", "tb64"])
+@pytest.mark.parametrize("transB", [False, True])
+def test_split_tail_bit_exact(force_tile, tile, transB):
+    """More tiles than one round of 256, with a small remainder: the remainder's tiles are cut along K
+    and summed by a second pass.  Exact on integer operands; ragged edges, a K tail, padded C."""
+    force_tile(tile)
+    shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
+              "tb64": [(1000, 1030, 999), (1100, 1100, 1100)]}[tile]
+    for idx, (M, N, K) in enumerate(shapes):
+        name = binding.variant_name(M, N, K, transB=transB)
+        assert "/tail" in name, name
+        print(f"split tail {name} M={M} N={N} K={K}", flush=True)
+        A = synth.small_ints((M, K), 800 + idx, synth.TENSOR_A)
+        B = synth.small_ints((N, K) if transB else (K, N), 800 + idx, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+        dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), 2)
+        binding.gemm_f32(dev(A), dev(B), dC, transB=transB)
+        whole = bufC.cpu().numpy()
+        assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+        assert np.isnan(whole[:, N:]).all()
+
+
+def test_split_tail_ragged_workload_parity_determinism_and_packed():
+    """The ragged workload (272 tiles of 64x64) takes this path."""
+    assert "/tail" in binding.variant_name(1000, 1030, 999)
+    A, B = synth.make_operands("ragged")
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dA, dB = dev(A), dev(B)
+    outs = []
+    for _ in range(3):
+        dC = torch.full((1000, 1030), float("nan"), device="cuda")
+        binding.gemm_f32(dA, dB, dC)
+        outs.append(dC.cpu().numpy())
+    check_close(outs[0], ref, 999)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    dBp = torch.empty(binding.pack_b_size(1030, 999) // 4, device="cuda")
+    binding.pack_b(dB, dBp)
+    dC = torch.full((1000, 1030), float("nan"), device="cuda")
+    binding.gemm_f32_packed(dA, dBp, dC)
+    check_close(dC.cpu().numpy(), ref, 999)
+    os.environ["GEMMF32_NO_TAIL_SPLIT"] = "1"
+    try:
+        assert "/tail" not in binding.variant_name(1000, 1030, 999)
+        binding.gemm_f32(dA, dB, dC)
+        check_close(dC.cpu().numpy(), ref, 999)
+    finally:
+        os.environ.pop("GEMMF32_NO_TAIL_SPLIT", None)
