@@ -19,7 +19,9 @@ import oracle  # noqa: E402
 from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 NTHREADS = min(16, os.cpu_count() or 1)
-TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3"}
+TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3", "t256x128": "4", "t128x256": "5"}
+TILE_DIMS = {"t256": (256, 256), "t128": (128, 128), "t64": (64, 64), "tb64": (64, 64), "t256x128": (256, 128),
+             "t128x256": (128, 256)}
 
 
 def dev(x: np.ndarray):
@@ -63,7 +65,7 @@ def force_tile():
 SMALL_SHAPES = [(1, 1, 1), (33, 65, 17), (64, 64, 64), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33)]
 
 
-@pytest.mark.parametrize("tile", ["t256", "t128", "t64", "tb64"])
+@pytest.mark.parametrize("tile", list(TILES))
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("pad", [0, 5, "align4"])
 def test_small_shapes_every_tile(force_tile, tile, transB, pad):
@@ -86,7 +88,36 @@ def test_small_shapes_every_tile(force_tile, tile, transB, pad):
         assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
 
 
-@pytest.mark.parametrize("tile", ["t256", "t128", "t64", "tb64"])
+@pytest.mark.parametrize("tile", list(TILES))
+@pytest.mark.parametrize("transB", [False, True])
+def test_tile_boundary_sweep_bit_exact(force_tile, tile, transB):
+    """M and N one below, at, one above and well past a tile boundary, in every combination: edge
+    tiles shorter than a tile (masked loads) and edge tiles of longer matrices (moved back inside,
+    storing only their own rows and columns).  Integer operands, so every result is exact; C is
+    pre-filled with NaN and carries NaN padding that must survive."""
+    force_tile(tile)
+    BM, BN = TILE_DIMS[tile]
+    K = 37
+    for M in (BM - 1, BM, BM + 1, 2 * BM + 7):
+        for N in (BN - 1, BN, BN + 1, 2 * BN + 9):
+            print(f"case tile={tile} transB={transB} M={M} N={N}", flush=True)
+            A = synth.small_ints((M, K), 300 + M, synth.TENSOR_A)
+            B = synth.small_ints((N, K) if transB else (K, N), 300 + N, synth.TENSOR_B)
+            ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+            dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), 3)
+            binding.gemm_f32(dev(A), dev(B), dC, transB=transB)
+            whole = bufC.cpu().numpy()
+            assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+            assert np.isnan(whole[:, N:]).all()
+            # the packed form of the same operand
+            Bp = torch.full((binding.pack_b_size(N, K) // 4,), float("nan"), device="cuda")
+            binding.pack_b(dev(B), Bp, transB=transB)
+            dC2 = torch.full((M, N), float("nan"), device="cuda")
+            binding.gemm_f32_packed(dev(A), Bp, dC2)
+            assert np.array_equal(dC2.cpu().numpy().astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("tile", list(TILES))
 @pytest.mark.parametrize("transB", [False, True])
 def test_integer_operands_bit_exact(force_tile, tile, transB):
     """Entries in {-2..2}: all partial sums are integers below 2^24, exact in any order."""
