@@ -243,6 +243,21 @@ def main() -> int:
         wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         ev_ms = s_ev.elapsed_time(e_ev) / args.steps
         gbs = 8.0 * n * n / (ev_ms * 1e-3) / 1e9
+        # the three forms of the filter side by side (naive, separated through a temporary, scanline)
+        forms = []
+        tmp = torch.empty_like(img)
+        for v in range(binding.binomial3x3_f32_variants()):
+            for _ in range(5):
+                binding.binomial3x3_f32_variant(v, img, res, tmp)
+            a_ev, b_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a_ev.record()
+            for _ in range(50):
+                binding.binomial3x3_f32_variant(v, img, res, tmp)
+            b_ev.record()
+            torch.cuda.synchronize()
+            f_ms = a_ev.elapsed_time(b_ev) / 50
+            forms.append({"form": binding.binomial3x3_f32_variant_name(v), "ms": round(f_ms, 5),
+                          "algorithmic_GBs": round(8.0 * n * n / (f_ms * 1e-3) / 1e9, 1)})
         print(json.dumps({
             "metric": "3x3 binomial filter Gpixel/s", "value": round(n * n / (wall_ms * 1e-3) / 1e9, 2),
             "unit": "Gpixel/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -250,7 +265,8 @@ def main() -> int:
             "dtype": "f32", "data": "synthetic",
             "config": {"workload": args.workload, "H": n, "W": n, "dist": "uniform", "seed": 7},
             "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
-                         "frac": round(gbs / HBM_GBS, 4), "traffic": None}}))
+                         "frac": round(gbs / HBM_GBS, 4), "traffic": None},
+            "forms": forms}))
         return 0
 
     main_run = Runner(args.workload)

@@ -29,6 +29,23 @@ extern "C" {
 
 int binomial3x3_f32(int64_t H, int64_t W, const float *in, int64_t ld_in, float *out, int64_t ld_out);
 
+/*
+ * The same filter in the three forms the paper contrasts (Section 2.1: the two Halide programs;
+ * Section 5.1: the scanline form), kept so that they can be measured side by side:
+ *   0 "naive"      one thread per pixel, nine taps from the image;
+ *   1 "separated"  horizontal 1-2-1 pass into tmp, vertical 1-2-1 pass from tmp (tmp: DEVICE
+ *                  buffer of the caller, H rows of ld_tmp >= W floats, overwritten; must not be
+ *                  in or out);
+ *   2 "scanline"   binomial3x3_f32 above (tmp unused, may be NULL).
+ * All three compute the same value up to fp32 rounding order and are exact for images of small
+ * integers.  Variants 0 and 1 are limited to H <= 65535 (separated) / H <= 262140 (naive):
+ * larger images return GEMMF32_EINVAL.  Other arguments and errors as binomial3x3_f32.
+ */
+int binomial3x3_f32_variant(int variant, int64_t H, int64_t W, const float *in, int64_t ld_in, float *out,
+                            int64_t ld_out, float *tmp, int64_t ld_tmp);
+int binomial3x3_f32_variants(void);
+const char *binomial3x3_f32_variant_name(int variant);   /* "?" if out of range */
+
 /* Stream for later launches (hipStream_t as void*; NULL = null stream). */
 int binomial3x3_f32_set_stream(void *hip_stream);
 

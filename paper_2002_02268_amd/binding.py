@@ -35,6 +35,9 @@ SYMBOLS = {
     "gemm_f32_ladder_set_stream": (ctypes.c_int, [_ptr]),
     "binomial3x3_f32": (ctypes.c_int, [_i64, _i64, _ptr, _i64, _ptr, _i64]),
     "binomial3x3_f32_set_stream": (ctypes.c_int, [_ptr]),
+    "binomial3x3_f32_variant": (ctypes.c_int, [ctypes.c_int, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]),
+    "binomial3x3_f32_variants": (ctypes.c_int, []),
+    "binomial3x3_f32_variant_name": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
 _lib = None
@@ -198,3 +201,29 @@ def binomial3x3_f32(img, out) -> None:
     H, W = img.shape
     lib().binomial3x3_f32_set_stream(ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
     _check(lib().binomial3x3_f32(H, W, img.data_ptr(), _ld(img), out.data_ptr(), _ld(out)))
+
+
+def binomial3x3_f32_variants() -> int:
+    return int(lib().binomial3x3_f32_variants())
+
+
+def binomial3x3_f32_variant_name(variant: int) -> str:
+    return lib().binomial3x3_f32_variant_name(int(variant)).decode()
+
+
+def binomial3x3_f32_variant(variant: int, img, out, tmp=None) -> None:
+    """out[:] = 3x3 binomial filter of img by form `variant` (0 naive, 1 separated: needs tmp, 2 scanline)."""
+    import torch
+    img = _dev_f32(img, "img", 2)
+    out = _dev_f32(out, "out", 2)
+    if tuple(img.shape) != tuple(out.shape):
+        raise ValueError("shape mismatch")
+    if tmp is not None:
+        tmp = _dev_f32(tmp, "tmp", 2)
+        if tuple(tmp.shape) != tuple(img.shape):
+            raise ValueError("tmp must have the shape of the image")
+    H, W = img.shape
+    lib().binomial3x3_f32_set_stream(ctypes.c_void_p(torch.cuda.current_stream(out.device).cuda_stream))
+    _check(lib().binomial3x3_f32_variant(int(variant), H, W, img.data_ptr(), _ld(img), out.data_ptr(), _ld(out),
+                                         tmp.data_ptr() if tmp is not None else None,
+                                         _ld(tmp) if tmp is not None else max(W, 1)))

@@ -80,9 +80,97 @@ __global__ void __launch_bounds__(256) binomial3x3_kernel(const Args p)
     }
 }
 
+// ---- the two plainer forms of the same filter, kept to be measured beside the scanline kernel ----
+
+// Direct form: one thread per output pixel, the nine taps read straight from the image
+// (the first of the two Halide forms in Section 2.1).
+__global__ void __launch_bounds__(256) binomial3x3_naive_kernel(const Args p)
+{
+    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (x >= p.W || y >= p.H) return;
+    const int xl = x > 0 ? x - 1 : 0, xr = x + 1 < p.W ? x + 1 : p.W - 1;
+    const float *r0 = p.in + (int64_t)(y > 0 ? y - 1 : 0) * p.ld_in;
+    const float *r1 = p.in + (int64_t)y * p.ld_in;
+    const float *r2 = p.in + (int64_t)(y + 1 < p.H ? y + 1 : p.H - 1) * p.ld_in;
+    const float s = 1.f * r0[xl] + 2.f * r0[x] + 1.f * r0[xr]
+                  + 2.f * r1[xl] + 4.f * r1[x] + 2.f * r1[xr]
+                  + 1.f * r2[xl] + 2.f * r2[x] + 1.f * r2[xr];
+    p.out[(int64_t)y * p.ld_out + x] = s * 0.0625f;
+}
+
+// Separated form with the intermediate image materialised (the second Halide form of Section 2.1
+// with its first stage computed in full before the second): a horizontal 1-2-1 pass into tmp,
+// then a vertical 1-2-1 pass over tmp.  Twice the memory traffic of the scanline kernel.
+__global__ void __launch_bounds__(256) binomial_rows_kernel(const Args p)    // in -> out, horizontal, unscaled
+{
+    const int x = blockIdx.x * 256 + threadIdx.x;
+    const int y = blockIdx.y;
+    if (x >= p.W) return;
+    const float *row = p.in + (int64_t)y * p.ld_in;
+    p.out[(int64_t)y * p.ld_out + x] = row[x > 0 ? x - 1 : 0] + 2.f * row[x] + row[x + 1 < p.W ? x + 1 : p.W - 1];
+}
+__global__ void __launch_bounds__(256) binomial_cols_kernel(const Args p)    // in -> out, vertical, scaled by 1/16
+{
+    const int x = blockIdx.x * 256 + threadIdx.x;
+    const int y = blockIdx.y;
+    if (x >= p.W) return;
+    const float a = p.in[(int64_t)(y > 0 ? y - 1 : 0) * p.ld_in + x];
+    const float b = p.in[(int64_t)y * p.ld_in + x];
+    const float c = p.in[(int64_t)(y + 1 < p.H ? y + 1 : p.H - 1) * p.ld_in + x];
+    p.out[(int64_t)y * p.ld_out + x] = (a + 2.f * b + c) * 0.0625f;
+}
+
+int check_image_args(int64_t H, int64_t W, const float *in, int64_t ld_in, float *out, int64_t ld_out)
+{
+    if (H < 0 || W < 0 || H > 2147483647LL || W > 2147483647LL) return GEMMF32_EINVAL;
+    if (ld_in < (W > 1 ? W : 1) || ld_out < (W > 1 ? W : 1)) return GEMMF32_EINVAL;
+    if (H == 0 || W == 0) return 1;      // nothing to do
+    if (in == nullptr || out == nullptr) return GEMMF32_ENULL;
+    if (in == out) return GEMMF32_EALIAS;
+    return GEMMF32_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int binomial3x3_f32_variants(void) { return 3; }
+
+const char *binomial3x3_f32_variant_name(int variant)
+{
+    static const char *names[] = {"naive", "separated", "scanline"};
+    return (variant >= 0 && variant < 3) ? names[variant] : "?";
+}
+
+int binomial3x3_f32_variant(int variant, int64_t H, int64_t W, const float *in, int64_t ld_in, float *out,
+                            int64_t ld_out, float *tmp, int64_t ld_tmp)
+{
+    if (variant < 0 || variant >= 3) return GEMMF32_EINVAL;
+    if (variant == 2) return binomial3x3_f32(H, W, in, ld_in, out, ld_out);
+    const int st = check_image_args(H, W, in, ld_in, out, ld_out);
+    if (st != GEMMF32_OK) return st > 0 ? GEMMF32_OK : st;
+    Args a;
+    a.in = in; a.out = out; a.H = (int)H; a.W = (int)W; a.rows = 1; a.ld_in = ld_in; a.ld_out = ld_out;
+    if (variant == 0) {
+        // grid.y is limited to 65535: taller images would need a loop; they are refused instead
+        if ((H + 3) / 4 > 65535) return GEMMF32_EINVAL;
+        hipLaunchKernelGGL(binomial3x3_naive_kernel, dim3((unsigned)((W + 63) / 64), (unsigned)((H + 3) / 4)),
+                           dim3(256), 0, g_stream, a);
+    } else {
+        if (tmp == nullptr) return GEMMF32_ENULL;
+        if (ld_tmp < W) return GEMMF32_EINVAL;
+        if (tmp == in || tmp == out) return GEMMF32_EALIAS;
+        if (H > 65535) return GEMMF32_EINVAL;
+        Args h = a, v = a;
+        h.out = tmp; h.ld_out = ld_tmp;
+        v.in = tmp; v.ld_in = ld_tmp;
+        const dim3 grid((unsigned)((W + 255) / 256), (unsigned)H);
+        hipLaunchKernelGGL(binomial_rows_kernel, grid, dim3(256), 0, g_stream, h);
+        hipLaunchKernelGGL(binomial_cols_kernel, grid, dim3(256), 0, g_stream, v);
+    }
+    return hipGetLastError() == hipSuccess ? GEMMF32_OK : GEMMF32_ELAUNCH;
+}
 
 int binomial3x3_f32_set_stream(void *hip_stream)
 {

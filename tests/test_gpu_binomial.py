@@ -82,3 +82,48 @@ def test_binomial_empty_and_errors():
     assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 8, a.data_ptr(), 8) == -3
     assert lib.binomial3x3_f32(8, 8, a.data_ptr(), 8, b.data_ptr(), 8) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_binomial_every_form_matches_the_oracle(variant):
+    """The naive, separated and scanline forms (Section 2.1 / 5.1) against the one oracle: within the
+    rounding bound on real-valued images, bit for bit on integer images, ld padding untouched."""
+    assert binding.binomial3x3_f32_variants() == 3
+    assert binding.binomial3x3_f32_variant_name(variant) == ["naive", "separated", "scanline"][variant]
+    for idx, (H, W) in enumerate(SHAPES + [(300, 700)]):
+        print(f"binomial form={variant} H={H} W={W}", flush=True)
+        img = synth.uniform((H, W), 660 + idx, synth.TENSOR_A)
+        ints = synth.small_ints((H, W), 680 + idx, synth.TENSOR_A, -100, 100)
+        for image, exact in ((img, False), (ints, True)):
+            ref = oracle.binomial3x3_f32(image)
+            d_in, _ = padded_dev(image, 3)
+            d_out, buf = padded_dev(np.full((H, W), np.nan, np.float32), 5)
+            d_tmp, tbuf = padded_dev(np.full((H, W), np.nan, np.float32), 2)
+            binding.binomial3x3_f32_variant(variant, d_in, d_out, d_tmp)
+            whole = buf.cpu().numpy()
+            got = whole[:, :W].astype(np.float64)
+            if exact:
+                assert np.array_equal(got, ref)
+            else:
+                assert np.max(np.abs(got - ref)) <= 1e-6
+            assert np.isnan(whole[:, W:]).all(), "ld padding of out was written"
+            assert np.isnan(tbuf.cpu().numpy()[:, W:]).all(), "ld padding of tmp was written"
+
+
+def test_binomial_form_errors():
+    lib = binding.lib()
+    a = torch.zeros(64, device="cuda")
+    b = torch.zeros(64, device="cuda")
+    t = torch.zeros(64, device="cuda")
+    args = (8, 8, a.data_ptr(), 8, b.data_ptr(), 8)
+    assert lib.binomial3x3_f32_variant(3, *args, t.data_ptr(), 8) == -1
+    assert lib.binomial3x3_f32_variant(-1, *args, t.data_ptr(), 8) == -1
+    assert lib.binomial3x3_f32_variant(1, *args, None, 8) == -2           # separated form needs tmp
+    assert lib.binomial3x3_f32_variant(1, *args, t.data_ptr(), 7) == -1
+    assert lib.binomial3x3_f32_variant(1, *args, a.data_ptr(), 8) == -3
+    assert lib.binomial3x3_f32_variant(1, *args, b.data_ptr(), 8) == -3
+    assert lib.binomial3x3_f32_variant(0, *args, None, 8) == 0            # the other forms ignore tmp
+    assert lib.binomial3x3_f32_variant(2, *args, None, 8) == 0
+    assert lib.binomial3x3_f32_variant(1, 0, 8, a.data_ptr(), 8, b.data_ptr(), 8, None, 8) == 0
+    assert lib.binomial3x3_f32_variant(1, 70000, 1, a.data_ptr(), 1, b.data_ptr(), 1, t.data_ptr(), 1) == -1
+    torch.cuda.synchronize()
