@@ -18,6 +18,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
 _SRC2 = os.path.join(_HERE, "binomial_oracle.c")
+_SRC3 = os.path.join(_HERE, "gemm_ex_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle_gemm.so")
 
 _i64 = ctypes.c_int64
@@ -27,10 +28,10 @@ _dp = ctypes.POINTER(ctypes.c_double)
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (OpenMP only splits independent rows)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2))
+    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC2, _SRC3))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
-               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC2]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC2, _SRC3]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -56,6 +57,10 @@ def _load():
         lib.oracle_gemm_f32_packed.restype = ctypes.c_int
         lib.oracle_binomial3x3_f32.argtypes = [_i64, _i64, _fp, _i64, _dp, _i64]
         lib.oracle_binomial3x3_f32.restype = ctypes.c_int
+        lib.oracle_gemm_f32_ex.argtypes = [_i64, _i64, _i64, ctypes.c_float, _fp, _i64, ctypes.c_int,
+                                           _fp, _i64, ctypes.c_int, ctypes.c_float, _fp, _i64,
+                                           _dp, _i64, ctypes.c_int]
+        lib.oracle_gemm_f32_ex.restype = ctypes.c_int
         lib.oracle_threads_used.argtypes = [ctypes.c_int]
         lib.oracle_threads_used.restype = ctypes.c_int
         _lib = lib
@@ -181,3 +186,31 @@ def binomial3x3_f32(img: np.ndarray) -> np.ndarray:
     if rc != 0:
         raise ValueError(f"oracle_binomial3x3_f32 rejected its arguments (rc={rc})")
     return out
+
+
+def gemm_f32_ex(A: np.ndarray, B: np.ndarray, C0: np.ndarray | None = None, alpha: float = 1.0,
+                beta: float = 0.0, transA: bool = False, transB: bool = False,
+                nthreads: int = 1) -> np.ndarray:
+    """alpha * op(A) @ op(B) + beta * C0 in float64.  A is (M,K), or (K,M) when transA; B is (K,N),
+    or (N,K) when transB; C0 (float32, (M,N)) is read only when beta != 0."""
+    A = _f32_2d(A, "A")
+    B = _f32_2d(B, "B")
+    K, M = (A.shape if transA else A.shape[::-1])
+    Kb, N = (B.shape[::-1] if transB else B.shape)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    if C0 is not None:
+        C0 = _f32_2d(C0, "C0")
+        if C0.shape != (M, N):
+            raise ValueError("C0 has the wrong shape")
+    elif beta != 0.0:
+        raise ValueError("beta != 0 needs C0")
+    C = np.full((M, N), np.nan, dtype=np.float64)
+    rc = _load().oracle_gemm_f32_ex(M, N, K, float(alpha), _ptr(A, _fp), _ld(A), int(bool(transA)),
+                                    _ptr(B, _fp), _ld(B), int(bool(transB)), float(beta),
+                                    _ptr(C0, _fp) if C0 is not None else None,
+                                    _ld(C0) if C0 is not None else max(N, 1),
+                                    _ptr(C, _dp), max(N, 1), int(nthreads))
+    if rc != 0:
+        raise ValueError(f"oracle_gemm_f32_ex rejected its arguments (rc={rc})")
+    return C
