@@ -83,6 +83,31 @@ int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
                      float *C, int64_t ldc, int64_t strideC, int transB);
 
 /*
+ * General form:  C = alpha * op(A) * op(B) + beta * C.
+ * The paper's product (Section 6.1 / 6.3) is alpha = 1, beta = 0, transA = 0; Section 6.3 reads b
+ * through transpose(b) as a view of the caller's array, and transA applies the same view to a.
+ * alpha and beta are the usual library scalings layered on that product:
+ *     C[i][j] = alpha * (sum_k opA[i][k] * opB[k][j]) + beta * C_old[i][j],
+ * the sum in fp32 on the matrix pipe, the scalings and the addition in fp32.
+ *   transA == 0: A stored M x K, lda >= max(K,1).   transA == 1: A stored K x M, lda >= max(M,1).
+ *   transB, B, ldb, C, ldc: as gemm_f32.
+ *   beta == 0: the old contents of C are never read (they may be NaN).  beta != 0: every element of
+ *   C in [0,M) x [0,N) is read once and written once; the ldc padding is never touched.
+ *   alpha == 0 does not skip the product: NaN or Inf in A or B still reach C, as alpha * sum says.
+ *   K == 0: C = beta * C (zeros for beta == 0).
+ * Everything else (device pointers, stream, errors, no launch on error, the split-K workspace) as
+ * gemm_f32.  The batched form applies it to batch independent products with element strides.
+ */
+int gemm_f32_ex(int64_t M, int64_t N, int64_t K, float alpha,
+                const float *A, int64_t lda, int transA,
+                const float *B, int64_t ldb, int transB,
+                float beta, float *C, int64_t ldc);
+int gemm_f32_ex_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha,
+                        const float *A, int64_t lda, int64_t strideA, int transA,
+                        const float *B, int64_t ldb, int64_t strideB, int transB,
+                        float beta, float *C, int64_t ldc, int64_t strideC);
+
+/*
  * Array packing of B (Section 6.1, the packedB compute expression):
  *     packedB[x][y][z] = B[y][x*P + z],  shape (ceil(N/P), K, P),
  * with P = pack_b_panel_width() (the paper's 32 was its CPU's choice) and the

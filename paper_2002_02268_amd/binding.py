@@ -19,6 +19,10 @@ SYMBOLS = {
     "gemm_f32": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
     "gemm_f32_batched": (ctypes.c_int, [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64,
                                         _ptr, _i64, _i64, ctypes.c_int]),
+    "gemm_f32_ex": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_float, _ptr, _i64, ctypes.c_int, _ptr, _i64,
+                                   ctypes.c_int, ctypes.c_float, _ptr, _i64]),
+    "gemm_f32_ex_batched": (ctypes.c_int, [_i64, _i64, _i64, _i64, ctypes.c_float, _ptr, _i64, _i64, ctypes.c_int,
+                                           _ptr, _i64, _i64, ctypes.c_int, ctypes.c_float, _ptr, _i64, _i64]),
     "pack_b_panel_width": (_i64, []),
     "pack_b_size": (ctypes.c_size_t, [_i64, _i64]),
     "pack_b": (ctypes.c_int, [_i64, _i64, _ptr, _i64, ctypes.c_int, _ptr]),
@@ -122,6 +126,37 @@ def gemm_f32_batched(A, B, C, transB: bool = False) -> None:
                                   A.data_ptr(), _ld(A), int(A.stride(0)),
                                   B.data_ptr(), _ld(B), int(B.stride(0)),
                                   C.data_ptr(), _ld(C), int(C.stride(0)), int(bool(transB))))
+
+
+def gemm_f32_ex(A, B, C, alpha: float = 1.0, beta: float = 0.0, transA: bool = False, transB: bool = False) -> None:
+    """C[:] = alpha * op(A) @ op(B) + beta * C.  A (M,K), or (K,M) if transA; B (K,N), or (N,K) if transB."""
+    A = _dev_f32(A, "A", 2)
+    B = _dev_f32(B, "B", 2)
+    C = _dev_f32(C, "C", 2)
+    K, M = (A.shape if transA else A.shape[::-1])
+    Kb, N = (B.shape[::-1] if transB else B.shape)
+    if Kb != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_ex(M, N, K, float(alpha), A.data_ptr(), _ld(A), int(bool(transA)), B.data_ptr(), _ld(B),
+                             int(bool(transB)), float(beta), C.data_ptr(), _ld(C)))
+
+
+def gemm_f32_ex_batched(A, B, C, alpha: float = 1.0, beta: float = 0.0, transA: bool = False,
+                        transB: bool = False) -> None:
+    """Batched general form over a leading batch axis; batch strides are taken from the tensors."""
+    A = _dev_f32(A, "A", 3)
+    B = _dev_f32(B, "B", 3)
+    C = _dev_f32(C, "C", 3)
+    batch = A.shape[0]
+    K, M = (A.shape[1:] if transA else A.shape[:0:-1])
+    Kb, N = (B.shape[:0:-1] if transB else B.shape[1:])
+    if B.shape[0] != batch or Kb != K or tuple(C.shape) != (batch, M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_ex_batched(batch, M, N, K, float(alpha), A.data_ptr(), _ld(A), int(A.stride(0)),
+                                     int(bool(transA)), B.data_ptr(), _ld(B), int(B.stride(0)), int(bool(transB)),
+                                     float(beta), C.data_ptr(), _ld(C), int(C.stride(0))))
 
 
 def pack_b_panel_width() -> int:

@@ -36,13 +36,13 @@ const TileShape kShapes[NUM_TILES] = {
     {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
     {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"}};
 
-template <int ID, int BMODE> struct Variant;
-template <int BMODE> struct Variant<T256, BMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1> type; };
-template <int BMODE> struct Variant<T128, BMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2, 2> type; };
-template <int BMODE> struct Variant<T64, BMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2, 2> type; };
-template <int BMODE> struct Variant<TB64, BMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2, 2> type; };
-template <int BMODE> struct Variant<T256x128, BMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2> type; };
-template <int BMODE> struct Variant<T128x256, BMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2> type; };
+template <int ID, int BMODE, int AMODE> struct Variant;
+template <int BMODE, int AMODE> struct Variant<T256, BMODE, AMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1, 1, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T128, BMODE, AMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T64, BMODE, AMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<TB64, BMODE, AMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T256x128, BMODE, AMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T128x256, BMODE, AMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
 
 template <class T> int launch(const KArgs &a)
 {
@@ -62,24 +62,29 @@ template <class T> int launch(const KArgs &a)
     return GEMMF32_OK;
 }
 
-template <int BMODE> int launch_tile(int tile, const KArgs &a)
+template <int BMODE, int AMODE> int launch_tile(int tile, const KArgs &a)
 {
     switch (tile) {
-    case T256: return launch<typename Variant<T256, BMODE>::type>(a);
-    case T128: return launch<typename Variant<T128, BMODE>::type>(a);
-    case T64: return launch<typename Variant<T64, BMODE>::type>(a);
-    case T256x128: return launch<typename Variant<T256x128, BMODE>::type>(a);
-    case T128x256: return launch<typename Variant<T128x256, BMODE>::type>(a);
-    default: return launch<typename Variant<TB64, BMODE>::type>(a);
+    case T256: return launch<typename Variant<T256, BMODE, AMODE>::type>(a);
+    case T128: return launch<typename Variant<T128, BMODE, AMODE>::type>(a);
+    case T64: return launch<typename Variant<T64, BMODE, AMODE>::type>(a);
+    case T256x128: return launch<typename Variant<T256x128, BMODE, AMODE>::type>(a);
+    case T128x256: return launch<typename Variant<T128x256, BMODE, AMODE>::type>(a);
+    default: return launch<typename Variant<TB64, BMODE, AMODE>::type>(a);
     }
 }
 
-int launch_variant(int bmode, int tile, const KArgs &a)
+int launch_variant(int bmode, int amode, int tile, const KArgs &a)
 {
+    if (amode == A_KM) {
+        if (bmode == B_NN) return launch_tile<B_NN, A_KM>(tile, a);
+        if (bmode == B_NT) return launch_tile<B_NT, A_KM>(tile, a);
+        return GEMMF32_EINVAL;          // no packed B with A stored K x M
+    }
     switch (bmode) {
-    case B_NN: return launch_tile<B_NN>(tile, a);
-    case B_NT: return launch_tile<B_NT>(tile, a);
-    default: return launch_tile<B_PACKED>(tile, a);
+    case B_NN: return launch_tile<B_NN, A_MK>(tile, a);
+    case B_NT: return launch_tile<B_NT, A_MK>(tile, a);
+    default: return launch_tile<B_PACKED, A_MK>(tile, a);
     }
 }
 
@@ -184,7 +189,8 @@ int choose_group_m(int tiles_m, int tiles_n, int64_t total)
 struct Plan {
     int status;
     bool launch;
-    int bmode, tile;
+    int bmode, amode, tile;
+    float alpha, beta;   // the caller's; args carries (1, 0) when a second pass applies them
     int split;           // K ranges (1: no split)
     int tail_tiles;      // tiles of the last round that are split along K (0: none)
     int64_t user_ldc;    // leading dimension of the caller's C (args.ldc is the workspace's when split)
@@ -217,13 +223,14 @@ int ensure_workspace(size_t bytes)
     return GEMMF32_OK;
 }
 
-int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, int amode,
                  const float *B, const float *C, int64_t ldc)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0) return GEMMF32_EINVAL;
     if (M > kMaxDim || N > kMaxDim || K > kMaxDim || batch > kMaxDim) return GEMMF32_EINVAL;
-    if (lda < (K > 1 ? K : 1) || ldc < (N > 1 ? N : 1)) return GEMMF32_EINVAL;
-    if (M * lda > kMaxElems || M * ldc > kMaxElems) return GEMMF32_EINVAL;
+    const int64_t a_rows = (amode == A_KM) ? K : M, a_cols = (amode == A_KM) ? M : K;
+    if (lda < (a_cols > 1 ? a_cols : 1) || ldc < (N > 1 ? N : 1)) return GEMMF32_EINVAL;
+    if (a_rows * lda > kMaxElems || M * ldc > kMaxElems) return GEMMF32_EINVAL;
     const bool has_out = batch > 0 && M > 0 && N > 0;
     if (has_out && C == nullptr) return GEMMF32_ENULL;
     if (has_out && K > 0 && (A == nullptr || B == nullptr)) return GEMMF32_ENULL;
@@ -232,13 +239,18 @@ int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A,
 }
 
 Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, int64_t sA,
-               const float *B, int64_t ldb, int64_t sB, float *C, int64_t ldc, int64_t sC, int bmode)
+               const float *B, int64_t ldb, int64_t sB, float *C, int64_t ldc, int64_t sC, int bmode,
+               int amode = A_MK, float alpha = 1.f, float beta = 0.f)
 {
     Plan pl;
     std::memset(&pl, 0, sizeof(pl));
     pl.bmode = bmode;
-    pl.status = check_common(batch, M, N, K, A, lda, B, C, ldc);
+    pl.amode = amode;
+    pl.alpha = alpha;
+    pl.beta = beta;
+    pl.status = check_common(batch, M, N, K, A, lda, amode, B, C, ldc);
     if (pl.status != GEMMF32_OK) return pl;
+    if (amode == A_KM && bmode == B_PACKED) { pl.status = GEMMF32_EINVAL; return pl; }
     if (bmode == B_NN && ldb < (N > 1 ? N : 1)) { pl.status = GEMMF32_EINVAL; return pl; }
     if (bmode == B_NT && ldb < (K > 1 ? K : 1)) { pl.status = GEMMF32_EINVAL; return pl; }
     if (bmode != B_PACKED && (bmode == B_NN ? K : N) * ldb > kMaxElems) { pl.status = GEMMF32_EINVAL; return pl; }
@@ -275,6 +287,8 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.tail_split = 1;
     a.tail_k = 0;
     a.tail_slots = nullptr;
+    a.alpha = alpha;
+    a.beta = beta;
     pl.tail_tiles = 0;
     // Split tail: when the last round of tiles would leave most compute units idle, its tiles are
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
@@ -305,12 +319,16 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
         pl.split = (int)cdiv(K, k_range);           // ranges that are not empty
         a.K = (int)k_range;
         a.k_total = (int)K;
-        a.sA = k_range;
+        a.sA = (amode == A_KM) ? k_range * lda : k_range;
         a.sB = (bmode == B_NN) ? k_range * ldb : (bmode == B_NT ? k_range : k_range * kPanel);
         a.sC = M * N;
         a.ldc = N;
         a.total_tiles = (int)(pl.split * tiles_m * tiles_n);
-        if (pl.split == 1) { a.K = (int)K; a.k_total = 0; a.sA = a.sB = a.sC = 0; a.ldc = ldc; }
+        a.alpha = 1.f;                  // raw partial sums; the second pass applies alpha and beta
+        a.beta = 0.f;
+        if (pl.split == 1) {
+            a.K = (int)K; a.k_total = 0; a.sA = a.sB = a.sC = 0; a.ldc = ldc; a.alpha = alpha; a.beta = beta;
+        }
     }
     pl.launch = true;
     return pl;
@@ -326,7 +344,7 @@ int run_plan(const Plan &pl)
         int rc = ensure_workspace((size_t)pl.tail_tiles * a.tail_split * sh.bm * sh.bn * sizeof(float));
         if (rc != GEMMF32_OK) return rc;
         a.tail_slots = g_workspace;
-        rc = launch_variant(pl.bmode, pl.tile, a);
+        rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
         if (rc != GEMMF32_OK) return rc;
         hipLaunchKernelGGL(tail_reduce_kernel, dim3((unsigned)(pl.tail_tiles * (sh.bm * sh.bn / 1024))), dim3(256), 0,
                            g_stream, a, sh.bm, sh.bn);
@@ -334,7 +352,7 @@ int run_plan(const Plan &pl)
         if (e != hipSuccess) return fail_hip(e);
         return GEMMF32_OK;
     }
-    if (pl.split <= 1) return launch_variant(pl.bmode, pl.tile, pl.args);
+    if (pl.split <= 1) return launch_variant(pl.bmode, pl.amode, pl.tile, pl.args);
     // split K: partial products into the workspace, then one pass that sums them in order
     KArgs a = pl.args;
     const int64_t mn = (int64_t)a.M * a.N;
@@ -343,11 +361,11 @@ int run_plan(const Plan &pl)
     float *C = a.C;
     const int64_t ldc = pl.user_ldc;
     a.C = g_workspace;
-    rc = launch_variant(pl.bmode, pl.tile, a);
+    rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
     if (rc != GEMMF32_OK) return rc;
     const int64_t chunks = (int64_t)a.M * ((a.N + 3) / 4);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv(chunks, 256)), dim3(256), 0, g_stream, g_workspace, C,
-                       a.M, a.N, ldc, pl.split);
+                       a.M, a.N, ldc, pl.split, pl.alpha, pl.beta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e);
     return GEMMF32_OK;
@@ -380,6 +398,25 @@ int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K, const float
     }
     return run_plan(make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
                               transB ? B_NT : B_NN));
+}
+
+int gemm_f32_ex(int64_t M, int64_t N, int64_t K, float alpha, const float *A, int64_t lda, int transA,
+                const float *B, int64_t ldb, int transB, float beta, float *C, int64_t ldc)
+{
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return GEMMF32_EINVAL;
+    return run_plan(make_plan(1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, transB ? B_NT : B_NN,
+                              transA ? A_KM : A_MK, alpha, beta));
+}
+
+int gemm_f32_ex_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float alpha, const float *A, int64_t lda,
+                        int64_t strideA, int transA, const float *B, int64_t ldb, int64_t strideB, int transB,
+                        float beta, float *C, int64_t ldc, int64_t strideC)
+{
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return GEMMF32_EINVAL;
+    if (!transA && alpha == 1.f && beta == 0.f)
+        return gemm_f32_batched(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, transB);
+    return run_plan(make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
+                              transB ? B_NT : B_NN, transA ? A_KM : A_MK, alpha, beta));
 }
 
 int64_t pack_b_panel_width(void) { return kPanel; }

@@ -43,6 +43,10 @@ typedef v2f v2f_g __attribute__((aligned(4)));
 typedef v4f v4f_g __attribute__((aligned(4)));
 
 enum BMode : int { B_NN = 0, B_NT = 1, B_PACKED = 2 };
+// A stored M x K (rows of k), or K x M (the transposed view of Section 6.3 applied to a): its slab
+// then sits in LDS as [k][m] exactly like B stored K x N, a lane reads MB adjacent rows of the tile
+// at once, and row r of MFMA block i is tile row MB*r + i.
+enum AMode : int { A_MK = 0, A_KM = 1 };
 
 constexpr int kPanel = 128;  // panel width P of the packed-B layout, in elements
 
@@ -66,6 +70,9 @@ struct KArgs {
     // pieces go to dense BM x BN slots and tail_reduce_kernel sums them.  tail_split <= 1: off.
     int tail_first, tail_split, tail_k;
     float *tail_slots;
+    // Epilogue: C = alpha * (A*B) + beta * C_old.  beta == 0: C_old is never read.  The paper's
+    // product is alpha = 1, beta = 0.
+    float alpha, beta;
 };
 
 template <int N> struct VecOf;
@@ -76,30 +83,32 @@ template <> struct VecOf<4> { typedef v4f type; typedef v4f_g gtype; };
 template <int N> __device__ __forceinline__ float vget(const typename VecOf<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1, int PF_ = 1>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1, int PF_ = 1, int AMODE_ = A_MK>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
-    static constexpr int BMODE = BMODE_, OCC = OCC_;
+    static constexpr int BMODE = BMODE_, OCC = OCC_, AMODE = AMODE_;
     static constexpr int PF = PF_;                             // slabs held in registers ahead of the LDS write (1 or 2)
     static_assert(PF_ == 1 || PF_ == 2, "prefetch depth");
     static constexpr int THREADS = 64 * WGM * WGN;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
     static constexpr int G = BK / 8;                           // 8-column groups per slab
-    static constexpr int SA = BK + 4;                          // A rows in LDS: [BM][SA]
+    static constexpr int SA = (AMODE == A_KM) ? BM : BK + 4;   // A in LDS: [BM][SA], or [BK][BM] when stored K x M
     static constexpr int SB = (BMODE == B_NT) ? (BK + 4) : BN; // B in LDS: [BN][SB] (NT) or [BK][BN]
-    static constexpr int A_TILE = BM * SA;
+    static constexpr int A_TILE = (AMODE == A_KM) ? BK * BM : BM * SA;
     static constexpr int B_TILE = (BMODE == B_NT) ? BN * SB : BK * BN;
     static constexpr int STAGE_FLOATS = A_TILE + B_TILE;
     static constexpr int LDS_BYTES = 2 * STAGE_FLOATS * 4;
     static constexpr int A_F4 = BM * BK / 4, A_ITERS = A_F4 / THREADS;
     static constexpr int B_F4 = BN * BK / 4, B_ITERS = B_F4 / THREADS;
-    static constexpr int A_F4_ROW = BK / 4;                               // 16-byte chunks per A row
+    static constexpr int A_F4_ROW = (AMODE == A_KM) ? BM / 4 : BK / 4;    // 16-byte chunks per A row in the slab
     static constexpr int B_F4_ROW = (BMODE == B_NT) ? BK / 4 : BN / 4;    // per B row in the slab
     static_assert(BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0, "wave tiles are multiples of 32");
     static_assert(BK % 16 == 0, "a slab holds an even number of 8-column groups");
     static_assert(A_F4 % THREADS == 0 && B_F4 % THREADS == 0, "loads divide evenly over threads");
     static_assert(NB == 1 || NB == 2 || NB == 4, "NB columns are read as one LDS vector");
+    static_assert(AMODE == A_MK || MB == 1 || MB == 2 || MB == 4, "MB rows are read as one LDS vector");
+    static_assert(AMODE == A_MK || BMODE != B_PACKED, "no packed B together with A stored K x M");
     static_assert(BMODE != B_PACKED || BN % kPanel == 0 || kPanel % BN == 0, "tile vs panel");
     static_assert(LDS_BYTES <= 160 * 1024, "fits the 160 KB of LDS per compute unit");
 };
@@ -195,8 +204,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr bool B_KMAJOR = (T::BMODE == B_NT);           // B fragments are 4 consecutive k of one column
     constexpr int NBV = B_KMAJOR ? NB : 4;   // B fragment vectors per 8-column group
     constexpr bool B_ELEMENTWISE = (T::BMODE == B_NN && EDGE == 2);
+    constexpr bool A_KMAJOR = (T::AMODE == A_MK);           // A fragments are 4 consecutive k of one row
+    constexpr int NAV = A_KMAJOR ? MB : 4;                  // A fragment vectors per 8-column group
+    constexpr bool A_ELEMENTWISE = (!A_KMAJOR && EDGE != 0);
     typedef typename VecOf<NB>::type vnb;
     typedef typename std::conditional<B_KMAJOR, v4f, vnb>::type bfrag_t;
+    typedef typename VecOf<A_KMAJOR ? 4 : MB>::type afrag_t;
 
     const int m_own = tm * BM, n_own = tn * BN;               // first row / column this tile stores
     const int m0 = (SHIFTED && m_own + BM > p.M) ? p.M - BM : m_own;
@@ -217,7 +230,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const float *pa[A_ITERS];
     const float *pb[B_ITERS];
     int sa_off[A_ITERS], sb_off[B_ITERS];
-    bool a_ok[A_ITERS];         // row of A in range
+    bool a_ok[A_ITERS];         // row of A in range (A stored K x M: first row of the chunk)
+    int a_col[A_ITERS];         // A stored K x M: first tile row of the chunk (global index)
+    int a_d[A_ITERS][4];        // A stored K x M at an edge: clamped offsets of the four elements
     bool b_ok[B_ITERS];         // NT: row of B in range; packed: chunk present; NN: first column in range
     int b_col[B_ITERS];         // NN / packed: first global column of the chunk
     int b_d[B_ITERS][4];        // NN, EDGE 2: clamped offsets of the four elements from pb[r]
@@ -226,10 +241,23 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         const int f = tid + r * NTHR;
         const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
         sa_off[r] = row * SA + c;
-        a_ok[r] = (m0 + row < M);
-        const int gi = (m0 + row < M) ? (m0 + row) : (M - 1);
-        pa[r] = A + (int64_t)gi * p.lda + c;
+        if constexpr (A_KMAJOR) {
+            a_ok[r] = (m0 + row < M);
+            a_col[r] = 0;
+            const int gi = (m0 + row < M) ? (m0 + row) : (M - 1);
+            pa[r] = A + (int64_t)gi * p.lda + c;
+        } else {
+            const int gi = m0 + c;
+            a_col[r] = gi;
+            a_ok[r] = (gi < M);
+            const int gic = (gi < M) ? gi : (M - 1);
+            pa[r] = A + (int64_t)row * p.lda + gic;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a_d[r][e] = ((gi + e < M) ? (gi + e) : (M - 1)) - gic;
+        }
     }
+    auto a_slot_row = [&](int r) { return (tid + r * NTHR) / A_F4_ROW; };
+    const int64_t a_step = A_KMAJOR ? BK : (int64_t)BK * p.lda;
     auto b_slot_row = [&](int r) {          // row of the B slab (k, or n for N x K storage) of slot r
         return (tid + r * NTHR) / B_F4_ROW;
     };
@@ -272,10 +300,19 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         constexpr int S = decltype(slot_tag)::value, SET = decltype(set_tag)::value;
         if constexpr (S < A_ITERS) {
             constexpr int r = S;
-            v4f v = load4(pa[r] + a_off);
-            if constexpr (EDGE != 0) {
+            v4f v;
+            if constexpr (A_ELEMENTWISE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
+                for (int e = 0; e < 4; ++e) {
+                    const float x = (pa[r] + a_off)[a_d[r][e]];
+                    v[e] = (a_col[r] + e < M) ? x : 0.f;
+                }
+            } else {
+                v = load4(pa[r] + a_off);
+                if constexpr (EDGE != 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
+                }
             }
             ra[SET][r] = v;
         } else {
@@ -298,20 +335,28 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         }
     };
     auto load_slab = [&](auto set_tag, int slab) {
-        const int64_t a_off = (int64_t)slab * BK, b_off = (int64_t)slab * b_step;
+        const int64_t a_off = (int64_t)slab * a_step, b_off = (int64_t)slab * b_step;
         static_for<A_ITERS + B_ITERS>([&](auto slot_tag) { load_slot(slot_tag, set_tag, a_off, b_off); });
     };
     // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain
     auto load_tail = [&](int slab, int kleft) {
-        const int64_t a_off = (int64_t)slab * BK, b_off = (int64_t)slab * b_step;
+        const int64_t a_off = (int64_t)slab * a_step, b_off = (int64_t)slab * b_step;
 #pragma unroll
         for (int r = 0; r < A_ITERS; ++r) {
             const int c = ((tid + r * NTHR) % A_F4_ROW) * 4;
             v4f v = zero4;
-            if (a_ok[r]) {
+            if constexpr (A_KMAJOR) {
+                if (a_ok[r]) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < kleft) v[e] = (pa[r] + a_off)[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < kleft) v[e] = (pa[r] + a_off)[e];
+                }
+            } else {
+                if (a_slot_row(r) < kleft && a_ok[r]) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (a_col[r] + e < M) v[e] = (pa[r] + a_off)[e];   // pa[r] is unclamped when a_ok
+                }
             }
             ra[0][r] = v;
         }
@@ -360,17 +405,23 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
 
     // ---- LDS -> fragments -> MFMA -----------------------------------------------------------
     struct Frag {
-        v4f a[MB];
+        afrag_t a[NAV];
         bfrag_t b[NBV];
     };
-    const int a_frag_off = (wm0 + l32) * SA + 4 * half;
+    const int a_frag_off = A_KMAJOR ? ((wm0 + l32) * SA + 4 * half) : (4 * half * SA + wm0 + MB * l32);
     const int b_frag_off = (T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + 4 * half)
                                               : (T::A_TILE + 4 * half * SB + wn0 + NB * l32);
     auto read_frag = [&](Frag &fr, int stage, int g) {
         const float *base = lds + stage * T::STAGE_FLOATS;
+        if constexpr (A_KMAJOR) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i)
-            fr.a[i] = *reinterpret_cast<const v4f *>(base + a_frag_off + 32 * i * SA + 8 * g);
+            for (int i = 0; i < MB; ++i)   // row of block i: wm0 + 32*i + l32
+                fr.a[i] = *reinterpret_cast<const v4f *>(base + a_frag_off + 32 * i * SA + 8 * g);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)    // row of block i: wm0 + MB*l32 + i
+                fr.a[e] = *reinterpret_cast<const afrag_t *>(base + a_frag_off + (8 * g + e) * SA);
+        }
         if constexpr (T::BMODE == B_NT) {
 #pragma unroll
             for (int j = 0; j < NB; ++j)   // column of block j: wn0 + 32*j + l32
@@ -397,10 +448,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             for (int i = 0; i < MB; ++i)
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
-                    float bv;
+                    float av, bv;
+                    if constexpr (A_KMAJOR) av = fr.a[i][e];
+                    else av = vget<MB>(fr.a[e], i);
                     if constexpr (B_KMAJOR) bv = fr.b[j][e];
                     else bv = vget<NB>(fr.b[e], j);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fr.a[i][e], bv, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
                 }
     };
 
@@ -412,7 +465,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int kleft = K - nkf * BK;
     Frag f0, f1;
     constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
-    constexpr int N_READ = MB + NBV;               // LDS reads of one fragment set
+    constexpr int N_READ = NAV + NBV;              // LDS reads of one fragment set
     // The actions of a slab run in the groups that precede the barrier (all but the last one),
     // the same number in each, in order.
     constexpr int MOVE_GROUPS = (G > 1) ? G - 1 : 1;
@@ -426,7 +479,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         const int cur = t & 1;
         typedef std::integral_constant<int, (PAR + 1) % PF> set_t;
         const int req = (t + 1 + PF < nkf) ? (t + 1 + PF) : (nkf - 1);
-        const int64_t a_off = (int64_t)req * BK, b_off = (int64_t)req * b_step;
+        const int64_t a_off = (int64_t)req * a_step, b_off = (int64_t)req * b_step;
         static_for<G>([&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
             Frag &now = (g & 1) ? f1 : f0;
@@ -500,16 +553,24 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // ---- epilogue: accumulators -> C (overwrite; predicated at the M / N edges) ---------------
     auto row_ok = [&](int gi) { return SHIFTED ? gi >= m_own : (EDGE == 0 || gi < M); };
     auto cols_ok = [&](int gj, int n) { return SHIFTED ? gj >= n_own : (EDGE == 0 || gj + n <= N); };
+    const float alpha = p.alpha, beta = p.beta;
+    const bool add_old = (beta != 0.f);                      // uniform over the grid
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int gi = m0 + wm0 + 32 * i + 8 * (v / 4) + 4 * half + (v % 4);
+            const int mrow = 8 * (v / 4) + 4 * half + (v % 4);          // row of the MFMA block
+            const int gi = m0 + wm0 + (A_KMAJOR ? 32 * i + mrow : MB * mrow + i);
             if constexpr (T::BMODE == B_NT) {
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int gj = n0 + wn0 + 32 * j + l32;
-                    if (row_ok(gi) && cols_ok(gj, 1)) C[(int64_t)gi * p.ldc + gj] = acc[i][j][v];
+                    if (row_ok(gi) && cols_ok(gj, 1)) {
+                        float *dst = C + (int64_t)gi * p.ldc + gj;
+                        float r = alpha * acc[i][j][v];
+                        if (add_old) r += beta * *dst;
+                        *dst = r;
+                    }
                 }
             } else {
                 const int gj = n0 + wn0 + NB * l32;
@@ -517,17 +578,26 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 bool done = false;
                 if constexpr (NB > 1) {
                     if (row_ok(gi) && cols_ok(gj, NB)) {
+                        typedef typename VecOf<NB>::gtype gvec;
                         vnb o;
 #pragma unroll
-                        for (int j = 0; j < NB; ++j) o[j] = acc[i][j][v];
-                        *reinterpret_cast<typename VecOf<NB>::gtype *>(dst) = o;
+                        for (int j = 0; j < NB; ++j) o[j] = alpha * acc[i][j][v];
+                        if (add_old) {
+                            const vnb old = *reinterpret_cast<const gvec *>(dst);
+                            o += beta * old;
+                        }
+                        *reinterpret_cast<gvec *>(dst) = o;
                         done = true;
                     }
                 }
                 if (!done) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        if (row_ok(gi) && cols_ok(gj + j, 1)) dst[j] = acc[i][j][v];
+                        if (row_ok(gi) && cols_ok(gj + j, 1)) {
+                            float r = alpha * acc[i][j][v];
+                            if (add_old) r += beta * dst[j];
+                            dst[j] = r;
+                        }
                 }
             }
         }
@@ -551,12 +621,14 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         batch = 0;
         const int k0 = s * p.tail_k;
         q.K = (p.K - k0 < p.tail_k) ? (p.K - k0) : p.tail_k;
-        q.A = p.A + k0;
+        q.A = p.A + (T::AMODE == A_KM ? (int64_t)k0 * p.lda : (int64_t)k0);
         q.B = p.B + (T::BMODE == B_NN ? (int64_t)k0 * p.ldb : (T::BMODE == B_NT ? (int64_t)k0 : (int64_t)k0 * kPanel));
         // dense BM x BN slot, addressed so that element (m0 + r, n0 + c) lands at r*BN + c
         float *slot = p.tail_slots + (int64_t)piece * (T::BM * T::BN);
         q.C = slot - ((int64_t)tm * T::BM * T::BN + (int64_t)tn * T::BN);
         q.ldc = T::BN;
+        q.alpha = 1.f;                 // raw partial sums; the second pass scales
+        q.beta = 0.f;
     } else {
         batch = logical / p.tiles_per_batch;
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
@@ -585,15 +657,20 @@ __global__ void __launch_bounds__(256) tail_reduce_kernel(const KArgs p, int BM,
     if (gi >= p.M || gj >= p.N) return;
     const float *slot = p.tail_slots + (int64_t)t * p.tail_split * (BM * BN) + e;
     float *dst = p.C + (int64_t)gi * p.ldc + gj;
+    const float alpha = p.alpha, beta = p.beta;
     if (gj + 3 < p.N) {
         v4f acc = *reinterpret_cast<const v4f *>(slot);
 #pragma unroll 8
         for (int s = 1; s < p.tail_split; ++s) acc += *reinterpret_cast<const v4f *>(slot + (int64_t)s * (BM * BN));
+        acc *= alpha;
+        if (beta != 0.f) acc += beta * *reinterpret_cast<const v4f_g *>(dst);
         *reinterpret_cast<v4f_g *>(dst) = acc;
     } else {
         for (int j = 0; gj + j < p.N; ++j) {
             float acc = slot[j];
             for (int s = 1; s < p.tail_split; ++s) acc += slot[(int64_t)s * (BM * BN) + j];
+            acc *= alpha;
+            if (beta != 0.f) acc += beta * dst[j];
             dst[j] = acc;
         }
     }
@@ -701,10 +778,11 @@ __global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
     }
 }
 
-// Split-K second pass: C[i][j] = sum over the S partial products W[s][i][j] (dense M x N each), s
-// ascending, so the result does not depend on how the first pass was scheduled.
+// Split-K second pass: C[i][j] = alpha * (sum over the S partial products W[s][i][j], dense M x N
+// each, s ascending) + beta * C[i][j], so the result does not depend on how the first pass was
+// scheduled.  beta == 0: C is not read.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ W, float *__restrict__ C,
-                                                             int M, int N, int64_t ldc, int S)
+                                                             int M, int N, int64_t ldc, int S, float alpha, float beta)
 {
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;      // first of 4 elements of a row
     const int64_t mn = (int64_t)M * N;
@@ -718,11 +796,15 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
     if (j + 3 < N) {
         v4f acc = load4(src);
         for (int s = 1; s < S; ++s) acc += load4(src + s * mn);
+        acc *= alpha;
+        if (beta != 0.f) acc += beta * load4(dst);
         *reinterpret_cast<v4f_g *>(dst) = acc;
     } else {
         for (int c = 0; j + c < N; ++c) {
             float acc = src[c];
             for (int s = 1; s < S; ++s) acc += src[s * mn + c];
+            acc *= alpha;
+            if (beta != 0.f) acc += beta * dst[c];
             dst[c] = acc;
         }
     }

@@ -1,0 +1,228 @@
+"""GPU parity of the general form  C = alpha*op(A)*op(B) + beta*C  (gemm_f32_ex, gemm_f32_ex_batched,
+through the C ABI) against the general-form CPU oracle on the same seeded inputs.
+
+Tolerance.  The product part carries the plain product's bound scaled by |alpha|
+(|alpha| * 1e-3 * sqrt(K/1024) for U(-1,1) operands); the epilogue adds two fp32 multiplications
+and one addition (or one fused multiply-add), each rounding relative 2^-24 of values bounded by
+|alpha|*|sum| + |beta|*|C_old|, i.e. at most 3 * 2^-24 * (|alpha|*K + |beta|*max|C_old|) -- far
+below the first term for the sizes here; the tests allow the sum of both.  Integer-valued operands
+with integer alpha, beta are exact and compared bit for bit."""
+from __future__ import annotations
+
+import math
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2002_02268_amd import binding, synth  # noqa: E402
+
+from test_gpu_parity import NTHREADS, TILES, TILE_DIMS, dev, padded_dev  # noqa: E402
+
+FLAGS = [(False, False), (False, True), (True, False), (True, True)]
+TENSOR_C = 2
+
+
+def stored(X, trans):
+    return np.ascontiguousarray(X.T) if trans else X
+
+
+def tolerance(K, alpha, beta, c_max):
+    return abs(alpha) * 1e-3 * math.sqrt(max(K, 1) / 1024.0) + 3 * 2.0 ** -24 * (abs(alpha) * K + abs(beta) * c_max)
+
+
+@pytest.fixture
+def force_tile():
+    def _set(name):
+        os.environ["GEMMF32_FORCE_TILE"] = TILES[name]
+    yield _set
+    os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+SHAPES = [(1, 1, 1), (33, 65, 17), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33), (700, 5, 40)]
+
+
+@pytest.mark.parametrize("tile", list(TILES))
+@pytest.mark.parametrize("tA,tB", FLAGS)
+def test_ex_small_shapes_every_tile(force_tile, tile, tA, tB):
+    """Ragged shapes, all four transpose combinations, padded rows everywhere (NaN in the padding),
+    alpha and beta both non-trivial: within tolerance, and the ld padding of C survives."""
+    force_tile(tile)
+    alpha, beta = 1.25, -0.5
+    for idx, (M, N, K) in enumerate(SHAPES):
+        print(f"case tile={tile} tA={tA} tB={tB} M={M} N={N} K={K}", flush=True)
+        A = synth.uniform((M, K), 800 + idx, synth.TENSOR_A)
+        B = synth.uniform((K, N), 800 + idx, synth.TENSOR_B)
+        C0 = synth.uniform((M, N), 800 + idx, TENSOR_C)
+        ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, alpha, beta, tA, tB, nthreads=NTHREADS)
+        dA, _ = padded_dev(stored(A, tA), 3)
+        dB, _ = padded_dev(stored(B, tB), 5)
+        dC, bufC = padded_dev(C0, 2)
+        binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
+        whole = bufC.cpu().numpy()
+        err = np.abs(whole[:, :N].astype(np.float64) - ref).max(initial=0.0)
+        assert err <= tolerance(K, alpha, beta, 1.0), err
+        assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+
+
+@pytest.mark.parametrize("tile", list(TILES))
+@pytest.mark.parametrize("tB", [False, True])
+def test_ex_transposed_a_boundary_sweep_bit_exact(force_tile, tile, tB):
+    """A stored K x M with M and N around tile multiples: edge tiles shorter than a tile (clamped
+    element loads along the contiguous dimension of A) and edge tiles moved back inside.  Integer
+    operands, integer alpha and beta: exact."""
+    force_tile(tile)
+    BM, BN = TILE_DIMS[tile]
+    K = 37
+    for M in (BM - 1, BM, BM + 1, 2 * BM + 7):
+        for N in (BN - 3, BN + 2):
+            print(f"case tile={tile} tB={tB} M={M} N={N}", flush=True)
+            A = synth.small_ints((M, K), 820 + M, synth.TENSOR_A)
+            B = synth.small_ints((K, N), 820 + N, synth.TENSOR_B)
+            C0 = synth.small_ints((M, N), 820, TENSOR_C, -9, 9)
+            ref = oracle.gemm_f32_ex(stored(A, True), stored(B, tB), C0, 2.0, -3.0, True, tB, nthreads=NTHREADS)
+            dA, _ = padded_dev(stored(A, True), 1)
+            dC, bufC = padded_dev(C0, 3)
+            binding.gemm_f32_ex(dA, dev(stored(B, tB)), dC, 2.0, -3.0, True, tB)
+            whole = bufC.cpu().numpy()
+            assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+            assert np.isnan(whole[:, N:]).all()
+
+
+def test_ex_default_scalars_equal_plain_entry_point_bit_for_bit():
+    for tB in (False, True):
+        M, N, K = 300, 260, 150
+        A = synth.uniform((M, K), 840, synth.TENSOR_A)
+        B = synth.uniform((K, N), 840, synth.TENSOR_B)
+        dA, dB = dev(A), dev(stored(B, tB))
+        C1 = torch.full((M, N), float("nan"), device="cuda")
+        C2 = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(dA, dB, C1, transB=tB)
+        binding.gemm_f32_ex(dA, dB, C2, 1.0, 0.0, False, tB)
+        assert torch.equal(C1, C2)
+        # A stored K x M holds the same values: same k order per element, same bits
+        C3 = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32_ex(dev(stored(A, True)), dB, C3, 1.0, 0.0, True, tB)
+        assert torch.equal(C1, C3)
+
+
+def test_ex_beta_zero_never_reads_c_and_alpha_zero_keeps_beta_c():
+    M, N, K = 200, 180, 64
+    A = synth.uniform((M, K), 850, synth.TENSOR_A)
+    B = synth.uniform((K, N), 850, synth.TENSOR_B)
+    C0 = synth.uniform((M, N), 850, TENSOR_C)
+    dC = torch.full((M, N), float("nan"), device="cuda")
+    binding.gemm_f32_ex(dev(A), dev(B), dC, 0.75, 0.0)
+    got = dC.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - oracle.gemm_f32_ex(A, B, None, 0.75, 0.0)).max() <= tolerance(K, 0.75, 0, 0)
+    dC = dev(C0)
+    binding.gemm_f32_ex(dev(A), dev(B), dC, 0.0, 2.0)          # power of two: exact
+    assert np.array_equal(dC.cpu().numpy(), 2.0 * C0)
+    # K == 0: C = beta * C
+    dC = dev(C0)
+    binding.gemm_f32_ex(torch.empty((M, 0), device="cuda"), torch.empty((0, N), device="cuda"), dC, 3.0, 0.5)
+    assert np.array_equal(dC.cpu().numpy(), 0.5 * C0)
+    dC = torch.full((M, N), float("nan"), device="cuda")
+    binding.gemm_f32_ex(torch.empty((M, 0), device="cuda"), torch.empty((0, N), device="cuda"), dC, 3.0, 0.0)
+    assert np.array_equal(dC.cpu().numpy(), np.zeros((M, N), np.float32))
+
+
+@pytest.mark.parametrize("tA,tB", FLAGS)
+def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
+    """Shapes that take the K-split path (small output, long K) and the split last round
+    (272 tiles): the second pass applies alpha and beta; integer operands, exact."""
+    for (M, N, K) in [(96, 80, 4000), (1000, 1030, 999)]:
+        name = binding.variant_name(M, N, K, transB=tB)
+        print(f"case tA={tA} tB={tB} M={M} N={N} K={K} variant={name}", flush=True)
+        assert ("splitk" in name) or ("tail" in name)
+        A = synth.small_ints((M, K), 860, synth.TENSOR_A)
+        B = synth.small_ints((K, N), 860, synth.TENSOR_B)
+        C0 = synth.small_ints((M, N), 860, TENSOR_C, -9, 9)
+        ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, -2.0, 3.0, tA, tB, nthreads=NTHREADS)
+        dC = dev(C0)
+        binding.gemm_f32_ex(dev(stored(A, tA)), dev(stored(B, tB)), dC, -2.0, 3.0, tA, tB)
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+
+
+def test_ex_ragged_workload_transposed_a_within_tolerance():
+    w = synth.WORKLOADS["ragged"]
+    M, N, K = w["M"], w["N"], w["K"]
+    A = synth.uniform((M, K), 870, synth.TENSOR_A)
+    B = synth.uniform((K, N), 870, synth.TENSOR_B)
+    C0 = synth.uniform((M, N), 870, TENSOR_C)
+    ref = oracle.gemm_f32_ex(stored(A, True), B, C0, 1.5, 0.25, True, False, nthreads=NTHREADS)
+    dC = dev(C0)
+    binding.gemm_f32_ex(dev(stored(A, True)), dev(B), dC, 1.5, 0.25, True, False)
+    got = dC.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= tolerance(K, 1.5, 0.25, 1.0)
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
+
+
+@pytest.mark.parametrize("tA,tB", FLAGS)
+def test_ex_batched_non_contiguous_strides(tA, tB):
+    """Batches taken as every second product of a larger buffer with padded rows (batch stride
+    larger than one product, leading dimensions larger than the rows); the skipped products hold
+    NaN (inputs) or a sentinel (outputs) that must survive."""
+    batch, M, N, K = 5, 70, 90, 50
+    alpha, beta = 2.0, -1.0
+    A = synth.small_ints((batch, M, K), 880, synth.TENSOR_A)
+    B = synth.small_ints((batch, K, N), 880, synth.TENSOR_B)
+    C0 = synth.small_ints((batch, M, N), 880, TENSOR_C, -9, 9)
+    As = np.ascontiguousarray(A.transpose(0, 2, 1)) if tA else A
+    Bs = np.ascontiguousarray(B.transpose(0, 2, 1)) if tB else B
+
+    def spaced(x, fill):
+        buf = torch.full((2 * x.shape[0], x.shape[1], x.shape[2] + 3), fill, dtype=torch.float32, device="cuda")
+        view = buf[::2, :, : x.shape[2]]
+        view.copy_(torch.from_numpy(x))
+        return view, buf
+
+    dA, _ = spaced(As, float("nan"))
+    dB, _ = spaced(Bs, float("nan"))
+    dC, bufC = spaced(C0, 777.0)
+    binding.gemm_f32_ex_batched(dA, dB, dC, alpha, beta, tA, tB)
+    whole = bufC.cpu().numpy()
+    for b in range(batch):
+        ref = oracle.gemm_f32_ex(As[b], Bs[b], C0[b], alpha, beta, tA, tB)
+        assert np.array_equal(whole[2 * b, :, :N].astype(np.float64), ref), b
+    assert (whole[1::2] == 777.0).all() and (whole[:, :, N:] == 777.0).all()
+
+
+def test_ex_batched_default_scalars_take_the_streaming_path_and_match():
+    batch = 64
+    A = synth.uniform((batch, 64, 64), 890, synth.TENSOR_A)
+    B = synth.uniform((batch, 64, 64), 890, synth.TENSOR_B)
+    C1 = torch.empty((batch, 64, 64), device="cuda")
+    C2 = torch.empty((batch, 64, 64), device="cuda")
+    binding.gemm_f32_batched(dev(A), dev(B), C1)
+    binding.gemm_f32_ex_batched(dev(A), dev(B), C2)
+    assert torch.equal(C1, C2)
+    C3 = dev(np.ones((batch, 64, 64), np.float32))
+    binding.gemm_f32_ex_batched(dev(A), dev(B), C3, 1.0, 1.0)
+    ref = oracle.gemm_f32_batched(A, B, nthreads=NTHREADS) + 1.0
+    assert np.abs(C3.cpu().numpy().astype(np.float64) - ref).max() <= tolerance(64, 1.0, 1.0, 1.0)
+
+
+def test_ex_error_codes():
+    lib = binding.lib()
+    a = torch.zeros(4096, device="cuda")
+    b = torch.zeros(4096, device="cuda")
+    c = torch.zeros(4096, device="cuda")
+    ap, bp, cp = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    ok = lambda *args: lib.gemm_f32_ex(*args)
+    assert ok(8, 16, 4, 1.0, ap, 4, 0, bp, 16, 0, 0.0, cp, 16) == 0
+    assert ok(8, 16, 4, 1.0, ap, 8, 1, bp, 16, 0, 0.0, cp, 16) == 0
+    assert ok(8, 16, 4, 1.0, ap, 7, 1, bp, 16, 0, 0.0, cp, 16) == -1      # A stored K x M needs lda >= M
+    assert ok(8, 16, 4, 1.0, ap, 3, 0, bp, 16, 0, 0.0, cp, 16) == -1
+    assert ok(8, 16, 4, 1.0, ap, 4, 2, bp, 16, 0, 0.0, cp, 16) == -1      # flags are 0 or 1
+    assert ok(8, 16, 4, 1.0, ap, 4, 0, bp, 16, 3, 0.0, cp, 16) == -1
+    assert ok(8, 16, 4, 1.0, None, 4, 0, bp, 16, 0, 0.0, cp, 16) == -2
+    assert ok(8, 16, 4, 1.0, ap, 4, 0, bp, 16, 0, 1.0, ap, 16) == -3
+    assert ok(0, 16, 4, 1.0, None, 4, 0, None, 16, 0, 1.0, None, 16) == 0
+    torch.cuda.synchronize()
