@@ -42,6 +42,12 @@ SYMBOLS = {
     "binomial3x3_f32_variant": (ctypes.c_int, [ctypes.c_int, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]),
     "binomial3x3_f32_variants": (ctypes.c_int, []),
     "binomial3x3_f32_variant_name": (ctypes.c_char_p, [ctypes.c_int]),
+    "elevate_rewrite": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.c_char_p, ctypes.c_size_t,
+                                       ctypes.POINTER(ctypes.c_int), ctypes.c_char_p, ctypes.c_size_t]),
+    "elevate_alpha_equal": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p]),
+    "elevate_schedule_gemm": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_char_p, _ptr, ctypes.c_char_p, ctypes.c_size_t]),
+    "elevate_default_strategy": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_char_p, ctypes.c_size_t]),
+    "gemm_f32_scheduled": (ctypes.c_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
 }
 
 _lib = None
@@ -262,3 +268,65 @@ def binomial3x3_f32_variant(variant: int, img, out, tmp=None) -> None:
     _check(lib().binomial3x3_f32_variant(int(variant), H, W, img.data_ptr(), _ld(img), out.data_ptr(), _ld(out),
                                          tmp.data_ptr() if tmp is not None else None,
                                          _ld(tmp) if tmp is not None else max(W, 1)))
+
+
+# ---- strategy layer (include/elevate.h) -------------------------------------------------------------
+
+class Schedule(ctypes.Structure):
+    """gemmf32_schedule"""
+    _fields_ = [("bm", ctypes.c_int32), ("bn", ctypes.c_int32), ("bk", ctypes.c_int32),
+                ("waves_m", ctypes.c_int32), ("waves_n", ctypes.c_int32),
+                ("wave_m", ctypes.c_int32), ("wave_n", ctypes.c_int32), ("split_k", ctypes.c_int32),
+                ("tiles_m", ctypes.c_int64), ("tiles_n", ctypes.c_int64), ("k_range", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
+
+
+ELEVATE_OK, ELEVATE_FAILED, ELEVATE_EPARSE, ELEVATE_ENULL = 0, 1, -1, -2
+ELEVATE_ELIMIT, ELEVATE_ELOWER, ELEVATE_ENOKERNEL = -6, -7, -8
+
+
+def elevate_rewrite(strategy: str, program: str, trace: bool = False):
+    """Applies a strategy to a program (both s-expressions).  Returns (code, text, steps[, trace])."""
+    out = ctypes.create_string_buffer(1 << 16)
+    steps = ctypes.c_int(0)
+    tbuf = ctypes.create_string_buffer(1 << 20) if trace else None
+    rc = lib().elevate_rewrite(strategy.encode(), program.encode(), out, len(out), ctypes.byref(steps), tbuf,
+                               len(tbuf) if trace else 0)
+    res = (rc, out.value.decode(), steps.value)
+    return res + (tbuf.value.decode(),) if trace else res
+
+
+def elevate_alpha_equal(a: str, b: str) -> int:
+    return int(lib().elevate_alpha_equal(a.encode(), b.encode()))
+
+
+def elevate_schedule_gemm(M: int, N: int, K: int, strategy: str):
+    """Schedules the product's loop nest with a strategy and lowers it.  Returns (code, Schedule, nest text)."""
+    sched = Schedule()
+    nest = ctypes.create_string_buffer(1 << 14)
+    rc = lib().elevate_schedule_gemm(M, N, K, strategy.encode(), ctypes.byref(sched), nest, len(nest))
+    return rc, sched, nest.value.decode()
+
+
+def elevate_default_strategy(M: int, N: int, K: int) -> str:
+    buf = ctypes.create_string_buffer(1 << 12)
+    rc = lib().elevate_default_strategy(M, N, K, buf, len(buf))
+    if rc != 0:
+        raise ValueError(f"elevate_default_strategy: code {rc}")
+    return buf.value.decode()
+
+
+def gemm_f32_scheduled(sched: Schedule, A, B, C, transB: bool = False) -> None:
+    """C[:] = A @ op(B) with the kernel shape and K split of a schedule."""
+    A = _dev_f32(A, "A", 2)
+    B = _dev_f32(B, "B", 2)
+    C = _dev_f32(C, "C", 2)
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    if (B.shape[1] if transB else B.shape[0]) != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_scheduled(ctypes.byref(sched), M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B),
+                                    C.data_ptr(), _ld(C), int(bool(transB))))

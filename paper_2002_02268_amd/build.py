@@ -7,17 +7,23 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libgemmf32.so")
-SOURCES = ["gemm_f32.hip", "ladder.hip", "binomial.hip"]
+OBJ = os.path.join(_HERE, "_build")
+# device code; the kernels of the product are spread over one file per operand layout
+SOURCES = ["gemm_f32.hip", "gemm_inst_nn.hip", "gemm_inst_nt.hip", "gemm_inst_packed.hip", "gemm_inst_tn.hip",
+           "gemm_inst_tt.hip", "ladder.hip", "binomial.hip"]
+# host-only code (the strategy layer)
+HOST_SOURCES = ["elevate.cpp", "elevate_api.cpp"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 VALU forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC"]
 
 
 def sources():
-    return [os.path.join(CSRC, s) for s in SOURCES]
+    return [os.path.join(CSRC, s) for s in SOURCES + HOST_SOURCES]
 
 
 def stale() -> bool:
@@ -33,7 +39,18 @@ def stale() -> bool:
 def build(force: bool = True, extra_flags=()) -> str:
     """Compile csrc/ into libgemmf32.so.  Raises CalledProcessError on failure."""
     if force or stale():
+        from concurrent.futures import ThreadPoolExecutor
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *sources()]
-        subprocess.run(cmd, check=True)
+        os.makedirs(OBJ, exist_ok=True)
+
+        def compile_one(name):
+            obj = os.path.join(OBJ, name + ".o")
+            flags = HOST_FLAGS if name in HOST_SOURCES else [*HIPCC_FLAGS, *extra_flags]
+            subprocess.run([hipcc, *flags, "-c", os.path.join(CSRC, name), "-o", obj], check=True)
+            return obj
+
+        workers = max(1, min(8, os.cpu_count() or 1))
+        with ThreadPoolExecutor(workers) as pool:
+            objs = list(pool.map(compile_one, SOURCES + HOST_SOURCES))
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB

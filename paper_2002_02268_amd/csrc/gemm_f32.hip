@@ -4,7 +4,8 @@
 
 #include <type_traits>
 
-#include "gemm_kernels.hpp"
+#include "dispatch.hpp"
+#include "gemm_launch.hpp"
 
 #include <cstdio>
 #include <cstdlib>
@@ -28,51 +29,21 @@ int fail_hip(hipError_t e)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// ---- variants -------------------------------------------------------------------------------
-enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, NUM_TILES = 6 };
+}  // namespace
 
-struct TileShape { int bm, bn, bk; const char *name; };
-const TileShape kShapes[NUM_TILES] = {
-    {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
-    {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"}};
+using namespace gemmf32_host;
 
-template <int ID, int BMODE, int AMODE> struct Variant;
-template <int BMODE, int AMODE> struct Variant<T256, BMODE, AMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1, 1, AMODE> type; };
-template <int BMODE, int AMODE> struct Variant<T128, BMODE, AMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2, 2, AMODE> type; };
-template <int BMODE, int AMODE> struct Variant<T64, BMODE, AMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2, 2, AMODE> type; };
-template <int BMODE, int AMODE> struct Variant<TB64, BMODE, AMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2, 2, AMODE> type; };
-template <int BMODE, int AMODE> struct Variant<T256x128, BMODE, AMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
-template <int BMODE, int AMODE> struct Variant<T128x256, BMODE, AMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
+namespace gemmf32_host {
+hipStream_t current_stream() { return g_stream; }
+int record_hip_error(hipError_t e) { return fail_hip(e); }
+extern template int launch_tile<B_NN, A_MK>(int, const KArgs &);
+extern template int launch_tile<B_NT, A_MK>(int, const KArgs &);
+extern template int launch_tile<B_PACKED, A_MK>(int, const KArgs &);
+extern template int launch_tile<B_NN, A_KM>(int, const KArgs &);
+extern template int launch_tile<B_NT, A_KM>(int, const KArgs &);
+}  // namespace gemmf32_host
 
-template <class T> int launch(const KArgs &a)
-{
-    static bool attr_set = false;  // per instantiation; benign if set twice
-    auto kern = gemm_kernel<T>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-        if (e != hipSuccess) return fail_hip(e);
-        attr_set = true;
-    }
-    // a product whose K fits one slab never touches a second LDS buffer
-    const int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
-    hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), lds_bytes, g_stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail_hip(e);
-    return GEMMF32_OK;
-}
-
-template <int BMODE, int AMODE> int launch_tile(int tile, const KArgs &a)
-{
-    switch (tile) {
-    case T256: return launch<typename Variant<T256, BMODE, AMODE>::type>(a);
-    case T128: return launch<typename Variant<T128, BMODE, AMODE>::type>(a);
-    case T64: return launch<typename Variant<T64, BMODE, AMODE>::type>(a);
-    case T256x128: return launch<typename Variant<T256x128, BMODE, AMODE>::type>(a);
-    case T128x256: return launch<typename Variant<T128x256, BMODE, AMODE>::type>(a);
-    default: return launch<typename Variant<TB64, BMODE, AMODE>::type>(a);
-    }
-}
+namespace {
 
 int launch_variant(int bmode, int amode, int tile, const KArgs &a)
 {
@@ -136,9 +107,12 @@ constexpr int64_t kMaxWorkspaceBytes = 256LL << 20;
 
 struct Choice { int tile; int split; };
 
+// set around one call by run_forced: tile and split given by the caller instead of the cost model
+thread_local int g_forced_tile = -1, g_forced_split = -1;
+
 Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
 {
-    int forced_tile = -1, forced_split = -1;
+    int forced_tile = g_forced_tile, forced_split = g_forced_split;
     if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
         int t = std::atoi(f);
         if (t >= 0 && t < NUM_TILES) forced_tile = t;
@@ -374,6 +348,46 @@ int run_plan(const Plan &pl)
 thread_local char g_variant_buf[64];
 
 }  // namespace
+
+namespace gemmf32_host {
+
+TileChoice choose(int64_t M, int64_t N, int64_t K)
+{
+    const Choice c = choose_tile(1, M, N, K);
+    const TileShape &sh = kShapes[c.tile];
+    int split = c.split;
+    if (split > 1) {   // the ranges that are not empty, as make_plan counts them
+        const int64_t k_range = cdiv(cdiv(K, split), sh.bk) * sh.bk;
+        split = (int)cdiv(K, k_range);
+    }
+    return TileChoice{sh.bm, sh.bn, sh.bk, split};
+}
+
+bool has_kernel(int bm, int bn, int bk)
+{
+    for (const TileShape &sh : kShapes)
+        if (sh.bm == bm && sh.bn == bn && sh.bk == bk) return true;
+    return false;
+}
+
+int run_forced(int bm, int bn, int bk, int split, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+               const float *B, int64_t ldb, float *C, int64_t ldc, int transB)
+{
+    int tile = -1;
+    for (int t = 0; t < NUM_TILES; ++t)
+        if (kShapes[t].bm == bm && kShapes[t].bn == bn && kShapes[t].bk == bk) tile = t;
+    if (tile < 0 || split < 1 || split > 256) return GEMMF32_EINVAL;
+    // a split must leave every range at least two slabs and fit the workspace (what choose_tile requires)
+    if (split > 1 && (K < (int64_t)split * 2 * bk || (int64_t)split * M * N * 4 > kMaxWorkspaceBytes)) return GEMMF32_EINVAL;
+    if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    g_forced_tile = tile;
+    g_forced_split = split;
+    const Plan pl = make_plan(1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, transB ? B_NT : B_NN);
+    g_forced_tile = g_forced_split = -1;
+    return run_plan(pl);
+}
+
+}  // namespace gemmf32_host
 
 extern "C" {
 

@@ -1,0 +1,6 @@
+// Kernels of the product for one operand layout (B_NN, A_KM), all tile shapes.
+#include "gemm_launch.hpp"
+
+namespace gemmf32_host {
+template int launch_tile<B_NN, A_KM>(int, const KArgs &);
+}

@@ -645,7 +645,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 
 // Sums the K ranges of the split tail tiles in ascending k and stores them into C.
 // One workgroup per (tail tile, 1024-element chunk of the tile).
-__global__ void __launch_bounds__(256) tail_reduce_kernel(const KArgs p, int BM, int BN)
+static __global__ void __launch_bounds__(256) tail_reduce_kernel(const KArgs p, int BM, int BN)
 {
     const int chunks_per_tile = BM * BN / 1024;
     const int t = blockIdx.x / chunks_per_tile, chunk = blockIdx.x % chunks_per_tile;
@@ -781,7 +781,7 @@ __global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
 // Split-K second pass: C[i][j] = alpha * (sum over the S partial products W[s][i][j], dense M x N
 // each, s ascending) + beta * C[i][j], so the result does not depend on how the first pass was
 // scheduled.  beta == 0: C is not read.
-__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ W, float *__restrict__ C,
+static __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ W, float *__restrict__ C,
                                                              int M, int N, int64_t ldc, int S, float alpha, float beta)
 {
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;      // first of 4 elements of a row
@@ -813,7 +813,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
 // Array packing (Section 6.1): Bp[x][y][z] = opB[y][x*kPanel + z], zero beyond column N.
 // B stored K x N: a re-laid-out copy.  One thread moves four 16-byte pieces (all four loads are
 // issued before the first store); a piece never straddles a panel because kPanel % 4 == 0.
-__global__ void __launch_bounds__(256) pack_b_kernel(const float *__restrict__ B, float *__restrict__ Bp,
+static __global__ void __launch_bounds__(256) pack_b_kernel(const float *__restrict__ B, float *__restrict__ Bp,
                                                       int N, int K, int64_t ldb, int64_t total_f4)
 {
     constexpr int F4_ROW = kPanel / 4;
@@ -846,7 +846,7 @@ __global__ void __launch_bounds__(256) pack_b_kernel(const float *__restrict__ B
 // B stored N x K: the packing is a transpose.  A workgroup moves a 64 (columns of B) x 64 (k)
 // block through LDS: 16-byte global reads along k, 16-byte global writes along z, 4-byte LDS
 // accesses on an odd row stride (at most 2-way bank conflicts either way).
-__global__ void __launch_bounds__(256) pack_b_transposed_kernel(const float *__restrict__ B, float *__restrict__ Bp,
+static __global__ void __launch_bounds__(256) pack_b_transposed_kernel(const float *__restrict__ B, float *__restrict__ Bp,
                                                                  int N, int K, int64_t ldb, int k_blocks)
 {
     constexpr int S = 65;

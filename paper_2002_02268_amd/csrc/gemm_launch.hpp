@@ -1,0 +1,63 @@
+// Tile variants of the product kernel and their launch.  The instantiations are spread over
+// several translation units (gemm_inst_*.hip), one per operand layout, so that they compile in
+// parallel; gemm_f32.hip only declares them.
+#pragma once
+
+#include "../../include/gemm_f32.h"
+#include "gemm_kernels.hpp"
+
+namespace gemmf32_host {
+
+using namespace gemmf32;
+
+hipStream_t current_stream();              // the stream set by gemm_f32_set_stream
+int record_hip_error(hipError_t e);        // remembers e for gemm_f32_last_hip_error; returns GEMMF32_ELAUNCH
+
+// ---- variants -------------------------------------------------------------------------------
+enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, NUM_TILES = 6 };
+
+struct TileShape { int bm, bn, bk; const char *name; };
+const TileShape kShapes[NUM_TILES] = {
+    {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
+    {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"}};
+
+template <int ID, int BMODE, int AMODE> struct Variant;
+template <int BMODE, int AMODE> struct Variant<T256, BMODE, AMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1, 1, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T128, BMODE, AMODE> { typedef Tile<128, 128, 16, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T64, BMODE, AMODE> { typedef Tile<64, 64, 32, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<TB64, BMODE, AMODE> { typedef Tile<64, 64, 64, 2, 2, BMODE, 2, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T256x128, BMODE, AMODE> { typedef Tile<256, 128, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T128x256, BMODE, AMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
+
+template <class T> int launch(const KArgs &a)
+{
+    static bool attr_set = false;  // per instantiation; benign if set twice
+    auto kern = gemm_kernel<T>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return record_hip_error(e);
+        attr_set = true;
+    }
+    // a product whose K fits one slab never touches a second LDS buffer
+    const int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), lds_bytes, current_stream(), a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return record_hip_error(e);
+    return GEMMF32_OK;
+}
+
+template <int BMODE, int AMODE> int launch_tile(int tile, const KArgs &a)
+{
+    switch (tile) {
+    case T256: return launch<typename Variant<T256, BMODE, AMODE>::type>(a);
+    case T128: return launch<typename Variant<T128, BMODE, AMODE>::type>(a);
+    case T64: return launch<typename Variant<T64, BMODE, AMODE>::type>(a);
+    case T256x128: return launch<typename Variant<T256x128, BMODE, AMODE>::type>(a);
+    case T128x256: return launch<typename Variant<T128x256, BMODE, AMODE>::type>(a);
+    default: return launch<typename Variant<TB64, BMODE, AMODE>::type>(a);
+    }
+}
+
+
+}  // namespace gemmf32_host
