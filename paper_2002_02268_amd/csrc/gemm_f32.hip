@@ -272,6 +272,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
         const int bk = kShapes[pl.tile].bk;
         const int64_t tail = total % 256, units = cdiv(K, bk);
         int64_t S = 256 / tail;
+        if (S > 8) S = 8;     // shorter pieces than an eighth of K cost more in the second pass than they save
         if (S > units) S = units;
         const int64_t units_per_piece = cdiv(units, S);
         S = cdiv(units, units_per_piece);                    // no empty pieces
@@ -320,7 +321,7 @@ int run_plan(const Plan &pl)
         a.tail_slots = g_workspace;
         rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
         if (rc != GEMMF32_OK) return rc;
-        hipLaunchKernelGGL(tail_reduce_kernel, dim3((unsigned)(pl.tail_tiles * (sh.bm * sh.bn / 1024))), dim3(256), 0,
+        hipLaunchKernelGGL(tail_reduce_kernel, dim3((unsigned)(pl.tail_tiles * (sh.bm * sh.bn / 256))), dim3(64), 0,
                            g_stream, a, sh.bm, sh.bn);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail_hip(e);

@@ -644,14 +644,14 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 }
 
 // Sums the K ranges of the split tail tiles in ascending k and stores them into C.
-// One workgroup per (tail tile, 1024-element chunk of the tile).
-static __global__ void __launch_bounds__(256) tail_reduce_kernel(const KArgs p, int BM, int BN)
+// One wave per (tail tile, 256-element chunk of the tile), so that even a few tiles spread over the chip.
+static __global__ void __launch_bounds__(64) tail_reduce_kernel(const KArgs p, int BM, int BN)
 {
-    const int chunks_per_tile = BM * BN / 1024;
+    const int chunks_per_tile = BM * BN / 256;
     const int t = blockIdx.x / chunks_per_tile, chunk = blockIdx.x % chunks_per_tile;
     int tm, tn;
     tile_coords(p, p.tail_first + t, tm, tn);
-    const int e = chunk * 1024 + threadIdx.x * 4;            // element of the tile: row e / BN, 4 columns
+    const int e = chunk * 256 + threadIdx.x * 4;             // element of the tile: row e / BN, 4 columns
     const int r = e / BN, c = e % BN;
     const int gi = tm * BM + r, gj = tn * BN + c;
     if (gi >= p.M || gj >= p.N) return;
