@@ -226,3 +226,33 @@ def test_ex_error_codes():
     assert ok(8, 16, 4, 1.0, ap, 4, 0, bp, 16, 0, 1.0, ap, 16) == -3
     assert ok(0, 16, 4, 1.0, None, 4, 0, None, 16, 0, 1.0, None, 16) == 0
     torch.cuda.synchronize()
+
+
+def test_ex_many_seeded_shapes_bit_exact():
+    """120 products whose shapes, strides, transpose flags and integer scalars are drawn from the
+    counter-based generator (so the list is the same on every run): the dispatch picks tile, K split
+    and split last round by itself; integer operands make every result exact."""
+    draws = synth.small_ints((120, 12), 4242, 7, 0, 1 << 20).astype(np.int64)
+    for case, d in enumerate(draws):
+        d = [int(x) for x in d]
+        M = 1 + d[0] % 700
+        N = 1 + d[1] % 700
+        K = 1 + (d[2] % 400 if d[3] % 4 else d[2] % 6000)        # every fourth case: long K
+        if d[3] % 16 == 0:
+            M, N = 1 + d[0] % 90, 1 + d[1] % 90                   # small outputs: K split
+        tA, tB = bool(d[4] & 1), bool(d[4] & 2)
+        alpha, beta = float(d[5] % 5 - 2), float(d[6] % 4 - 1)
+        pads = (d[7] % 5, d[8] % 5, d[9] % 5)
+        print(f"case {case}: M={M} N={N} K={K} tA={tA} tB={tB} alpha={alpha} beta={beta} pads={pads} "
+              f"variant={binding.variant_name(M, N, K, transB=tB)}", flush=True)
+        A = synth.small_ints((M, K), 3000 + case, synth.TENSOR_A)
+        B = synth.small_ints((K, N), 3000 + case, synth.TENSOR_B)
+        C0 = synth.small_ints((M, N), 3000 + case, TENSOR_C, -9, 9)
+        ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, alpha, beta, tA, tB, nthreads=NTHREADS)
+        dA, _ = padded_dev(stored(A, tA), pads[0])
+        dB, _ = padded_dev(stored(B, tB), pads[1])
+        dC, bufC = padded_dev(C0, pads[2])
+        binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
+        whole = bufC.cpu().numpy()
+        assert np.array_equal(whole[:, :N].astype(np.float64), ref), case
+        assert np.isnan(whole[:, N:]).all(), case
