@@ -147,9 +147,17 @@ int gemm_f32_last_hip_error(void);
 void gemm_f32_shutdown(void);
 
 /*
- * Which kernel variant the dispatcher would run for a shape, as a static
- * string such as "t256x256x16/nn/a16" or "t64x64x64/nn/a16/splitk32" (diagnostics for benchmarks; the
- * pointers are only inspected for alignment and may be NULL for "aligned").
+ * Which kernel variant the dispatcher would run for a shape, as a string such as
+ * "t256x256x16/nn/a16", "t64x64x64/nn/a16/splitk32" (K split into 32 ranges) or
+ * "t64x64x64/nn/a4/tail16x8" (the 16 tiles of the last round split into 8 K ranges each); for
+ * diagnostics and benchmarks.  The pointers are only inspected for alignment and may be NULL for
+ * "aligned".  The string lives in a per-thread buffer that the next call on the thread overwrites.
+ *
+ * Test hooks read from the environment at every call (not meant for production use):
+ *   GEMMF32_FORCE_TILE=0..5    tile 256x256x16, 128x128x16, 64x64x32, 64x64x64, 256x128x16, 128x256x16
+ *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
+ *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
+ * gemm_f32_scheduled (elevate.h) is the interface for choosing tile and split per call.
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,
                                   const float *A, int64_t lda,

@@ -338,9 +338,19 @@ int run_plan(const Plan &pl)
     a.C = g_workspace;
     rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
     if (rc != GEMMF32_OK) return rc;
+    // lanes per group of 4 columns: enough to put about 64K threads on the chip, at most 16, at most S
     const int64_t chunks = (int64_t)a.M * ((a.N + 3) / 4);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv(chunks, 256)), dim3(256), 0, g_stream, g_workspace, C,
-                       a.M, a.N, ldc, pl.split, pl.alpha, pl.beta);
+    int sl = 1;
+    while (sl < 16 && sl * 2 <= pl.split && chunks * sl < 65536) sl *= 2;
+    const dim3 grid((unsigned)cdiv(chunks * sl, 256)), block(256);
+    float *W = g_workspace;
+    switch (sl) {
+    case 1: hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
+    case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
+    case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
+    case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
+    default: hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e);
     return GEMMF32_OK;

@@ -778,35 +778,47 @@ __global__ void __launch_bounds__(256, 2) batched64_kernel(const BatchArgs p)
     }
 }
 
-// Split-K second pass: C[i][j] = alpha * (sum over the S partial products W[s][i][j], dense M x N
-// each, s ascending) + beta * C[i][j], so the result does not depend on how the first pass was
-// scheduled.  beta == 0: C is not read.
+// Split-K second pass: C[i][j] = alpha * (sum of the S partial products W[s][i][j], dense M x N
+// each) + beta * C[i][j].  SL lanes share one group of 4 adjacent columns: lane p adds the partials
+// p, p + SL, p + 2*SL, ... in ascending order, then the SL lane sums are combined by a fixed
+// butterfly, so the order of the additions depends on (S, SL) only, never on how the first pass
+// was scheduled; with many partials and a small output the loads of one element are in flight
+// together instead of one after the other.  beta == 0: C is not read.
+template <int SL>
 static __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ W, float *__restrict__ C,
-                                                             int M, int N, int64_t ldc, int S, float alpha, float beta)
+                                                                    int M, int N, int64_t ldc, int S, float alpha,
+                                                                    float beta)
 {
-    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;      // first of 4 elements of a row
     const int64_t mn = (int64_t)M * N;
     const int n4 = (N + 3) / 4;
-    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (chunk >= (int64_t)M * n4) return;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t chunk = gid / SL;
+    const int part = (int)(gid % SL);
+    if (chunk >= (int64_t)M * n4) return;              // whole groups of SL lanes leave together
     const int i = (int)(chunk / n4), j = (int)(chunk % n4) * 4;
-    (void)e;
     const float *src = W + (int64_t)i * N + j;
     float *dst = C + (int64_t)i * ldc + j;
-    if (j + 3 < N) {
-        v4f acc = load4(src);
-        for (int s = 1; s < S; ++s) acc += load4(src + s * mn);
-        acc *= alpha;
+    const bool whole = (j + 3 < N);
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    if (whole) {
+#pragma unroll 4
+        for (int s = part; s < S; s += SL) acc += load4(src + s * mn);
+    } else {
+        for (int s = part; s < S; s += SL)
+            for (int c = 0; j + c < N; ++c) acc[c] += src[s * mn + c];
+    }
+#pragma unroll
+    for (int off = SL / 2; off >= 1; off /= 2) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += __shfl_xor(acc[c], off, 64);
+    }
+    if (part != 0) return;
+    acc *= alpha;
+    if (whole) {
         if (beta != 0.f) acc += beta * load4(dst);
         *reinterpret_cast<v4f_g *>(dst) = acc;
     } else {
-        for (int c = 0; j + c < N; ++c) {
-            float acc = src[c];
-            for (int s = 1; s < S; ++s) acc += src[s * mn + c];
-            acc *= alpha;
-            if (beta != 0.f) acc += beta * dst[c];
-            dst[c] = acc;
-        }
+        for (int c = 0; j + c < N; ++c) dst[c] = (beta != 0.f) ? acc[c] + beta * dst[c] : acc[c];
     }
 }
 
