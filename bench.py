@@ -179,6 +179,84 @@ def ladder(torch, binding, synth):
     return out
 
 
+def protocol(torch, binding, synth):
+    """Every workload timed the long way: 10 warm-up launches, then windows of R back-to-back launches
+    between two events on the launch stream (R sized for a window of at least 50 ms, at least 100
+    launches), 20 windows, median and best per-launch time.  Also: the latency of one launch of
+    square1024 with a synchronisation on both sides, and the batched workload "cold": six disjoint
+    operand sets used in rotation (1.2 GB, more than the memory-side cache holds), so that every
+    launch streams its operands from HBM."""
+    def windows(step, min_launches=100):
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        once = max(time.perf_counter() - t0, 2e-6)
+        reps = int(max(min_launches, min(20000, 0.05 / once)))
+        per = []
+        for _ in range(20):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                step()
+            b.record()
+            torch.cuda.synchronize()
+            per.append(a.elapsed_time(b) / reps)
+        per.sort()
+        return {"launches_per_window": reps, "median_ms": round(per[len(per) // 2], 5), "best_ms": round(per[0], 5)}
+
+    out = {"protocol": {}}
+    plan = [("square1024", "plain"), ("ragged", "plain"), ("square4096", "plain"), ("transb2048", "plain"),
+            ("transb2048", "packed"), ("transb2048", "pack_only"), ("batched64", "plain")]
+    for name, mode in plan:
+        r = Runner(name, "packed" if mode == "pack_only" else mode)
+        r.mode = mode
+        res = windows(r.step, 20 if name == "square4096" else 100)
+        w = r.w
+        if mode == "pack_only":
+            res["algorithmic_GBs"] = round(8.0 * w["N"] * w["K"] / (res["median_ms"] * 1e-3) / 1e9, 1)
+        else:
+            res["tflops_median"] = round(flops_of(w) / (res["median_ms"] * 1e-3) / 1e12, 2)
+            res["tflops_best"] = round(flops_of(w) / (res["best_ms"] * 1e-3) / 1e12, 2)
+            res["frac_peak_median"] = round(res["tflops_median"] / PEAK_TFLOPS, 4)
+        if name == "batched64":
+            res["algorithmic_GBs"] = round(bytes_of(w) / (res["median_ms"] * 1e-3) / 1e9, 1)
+            res["note"] = "warm: the same 201 MB every launch"
+        if name == "square1024" and mode == "plain":
+            lat = []
+            for _ in range(200):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                r.step()
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - t0) * 1e3)
+            lat.sort()
+            res["single_launch_latency_ms"] = {"median": round(lat[len(lat) // 2], 5), "best": round(lat[0], 5)}
+        out["protocol"][name + ("" if mode == "plain" else "_" + mode)] = res
+        del r
+        torch.cuda.empty_cache()
+    # batched64, cold
+    w = synth.WORKLOADS["batched64"]
+    sets = []
+    for _ in range(6):
+        sets.append((torch.rand(w["batch"], w["M"], w["K"], device="cuda"), torch.rand(w["batch"], w["K"], w["N"], device="cuda"),
+                     torch.empty(w["batch"], w["M"], w["N"], device="cuda")))
+    state = {"i": 0}
+
+    def cold_step():
+        a, b, c = sets[state["i"] % 6]
+        state["i"] += 1
+        binding.gemm_f32_batched(a, b, c)
+    res = windows(cold_step, 120)
+    res["algorithmic_GBs"] = round(bytes_of(w) / (res["median_ms"] * 1e-3) / 1e9, 1)
+    res["frac_hbm_peak"] = round(res["algorithmic_GBs"] / HBM_GBS, 4)
+    res["note"] = "cold: six disjoint operand sets in rotation"
+    out["protocol"]["batched64_cold"] = res
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +269,9 @@ def main() -> int:
                     help="time the seven ladder levels (baseline ... parallel) on square1024 and square4096 "
                          "and print one JSON object; levels 4-6 include pack_b in every step, as the paper's "
                          "array-packing versions include their packing loop")
+    ap.add_argument("--protocol", action="store_true",
+                    help="time every workload in 20 windows of at least 50 ms (median and best), the latency of one "
+                         "square1024 launch, and the batched workload with operands streamed from HBM; one JSON object")
     ap.add_argument("--sources-sha256", action="store_true", help="print the kernel source hash and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
@@ -223,6 +304,10 @@ def main() -> int:
 
     if args.ladder:
         print(json.dumps(ladder(torch, binding, synth)))
+        return 0
+
+    if args.protocol:
+        print(json.dumps(protocol(torch, binding, synth)))
         return 0
 
     if args.workload.startswith("binomial"):
