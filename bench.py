@@ -281,7 +281,7 @@ def main() -> int:
         print(kernel_sources_sha256())
         return 0
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        print("bench.py: the library runs on one GPU (--gpus 1); there is no multi-GPU path", file=sys.stderr)
         return 2
 
     import torch
