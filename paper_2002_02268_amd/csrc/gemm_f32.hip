@@ -107,6 +107,42 @@ constexpr int64_t kMaxWorkspaceBytes = 256LL << 20;
 
 struct Choice { int tile; int split; };
 
+// fraction of a compute unit's MFMA peak each variant sustains on large square problems (measured)
+const struct { int id; double eff; } kCandidates[] = {
+    {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {TB64, 0.80}, {T64, 0.78}};
+double tile_efficiency(int tile)
+{
+    for (const auto &c : kCandidates)
+        if (c.id == tile) return c.eff;
+    return 0.8;
+}
+
+// Split of the last, partly filled round: `tail` tiles cut into `pieces` K ranges of `piece_k` columns
+// each (pieces <= 1: no split).  benefit_us: modelled time saved against running the tail as a round
+// of whole tiles, the second pass already charged.
+struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; };
+
+TailSplit plan_tail_split(int bm, int bn, int bk, double eff, int64_t batch, int64_t tiles, int64_t K)
+{
+    TailSplit t = {tiles % 256, 1, 0, 0.0};
+    if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || std::getenv("GEMMF32_NO_TAIL_SPLIT")) return t;
+    const int64_t units = cdiv(K, bk);
+    int64_t S = 256 / t.tail;
+    if (S > 8) S = 8;     // shorter pieces than an eighth of K cost more in the second pass than they save
+    if (S > units) S = units;
+    const int64_t units_per_piece = cdiv(units, S);
+    S = cdiv(units, units_per_piece);                    // no empty pieces
+    if (S <= 1 || t.tail * S * bm * bn * 4 > kMaxWorkspaceBytes) return t;
+    const double per_k = 2.0 * bm * bn / (kCuFlopsPerUs * eff);
+    const double t_full = per_k * ((double)K + kOverheadK), t_piece = per_k * ((double)units_per_piece * bk + kOverheadK);
+    const double second_pass = 8.0;                      // launch, and reading the pieces back
+    if (t_full - t_piece <= second_pass) return t;
+    t.pieces = S;
+    t.piece_k = units_per_piece * bk;
+    t.benefit_us = t_full - t_piece - second_pass;
+    return t;
+}
+
 // set around one call by run_forced: tile and split given by the caller instead of the cost model
 thread_local int g_forced_tile = -1, g_forced_split = -1;
 
@@ -121,11 +157,9 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         int t = std::atoi(f);
         if (t >= 1 && t <= 256) forced_split = t;
     }
-    static const struct { int id; double eff; } cand[] = {
-        {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {TB64, 0.80}, {T64, 0.78}};
     Choice best = {TB64, 1};
     double best_cost = -1;
-    for (const auto &c : cand) {
+    for (const auto &c : kCandidates) {
         if (forced_tile >= 0 && c.id != forced_tile) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
@@ -140,6 +174,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             double cost = (double)cdiv(tiles * S, 256) * 2.0 * sh.bm * sh.bn * (k_range + kOverheadK) /
                           (kCuFlopsPerUs * c.eff);
             if (S > 1) cost += 6.0 + (double)(S + 1) * M * N * 4.0 / 3.0e6;   // second pass: launch + traffic at 3 TB/s
+            if (S == 1) cost -= plan_tail_split(sh.bm, sh.bn, sh.bk, c.eff, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
             if (forced_split >= 1) break;
         }
@@ -267,23 +302,14 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     // Split tail: when the last round of tiles would leave most compute units idle, its tiles are
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
     // 16 become 256 pieces that run beside the full round).
-    if (pl.split == 1 && batch == 1 && total > 256 && total % 256 != 0 && total % 256 <= 128 &&
-        !std::getenv("GEMMF32_NO_TAIL_SPLIT")) {
-        const int bk = kShapes[pl.tile].bk;
-        const int64_t tail = total % 256, units = cdiv(K, bk);
-        int64_t S = 256 / tail;
-        if (S > 8) S = 8;     // shorter pieces than an eighth of K cost more in the second pass than they save
-        if (S > units) S = units;
-        const int64_t units_per_piece = cdiv(units, S);
-        S = cdiv(units, units_per_piece);                    // no empty pieces
-        // worth it when a whole tile costs more than a piece plus the second pass
-        const double t_full = 2.0 * bm * bn * ((double)K + kOverheadK), t_piece = 2.0 * bm * bn * ((double)units_per_piece * bk + kOverheadK);
-        if (S > 1 && (t_full - t_piece) / (kCuFlopsPerUs * 0.8) > 8.0 && tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
-            a.tail_first = (int)(total - tail);
-            a.tail_split = (int)S;
-            a.tail_k = (int)(units_per_piece * bk);
-            a.total_tiles = (int)(total - tail + tail * S);
-            pl.tail_tiles = (int)tail;
+    if (pl.split == 1) {
+        const TailSplit ts = plan_tail_split(bm, bn, kShapes[pl.tile].bk, tile_efficiency(pl.tile), batch, total, K);
+        if (ts.pieces > 1) {
+            a.tail_first = (int)(total - ts.tail);
+            a.tail_split = (int)ts.pieces;
+            a.tail_k = (int)ts.piece_k;
+            a.total_tiles = (int)(total - ts.tail + ts.tail * ts.pieces);
+            pl.tail_tiles = (int)ts.tail;
         }
     }
     if (pl.split > 1) {
