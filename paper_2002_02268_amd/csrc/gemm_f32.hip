@@ -95,26 +95,36 @@ int launch_batched64(int64_t batch, const float *A, int64_t lda, int64_t sA, con
 
 // Tile and split choice.  Workgroups spread over 256 compute units, so a launch costs
 // ceil(workgroups / 256) rounds of one tile each.  A tile over a K range of length k costs
-// 2*BM*BN*(k + kOverheadK) flops at the fraction of one compute unit's MFMA peak (0.6144 Tflop/s)
-// that the variant sustains (measured on square problems); kOverheadK stands for the first-slab
-// latency and the epilogue.  Splitting K into S ranges multiplies the workgroups by S and adds a
+// 2*BM*BN*(k + overhead) flops at the fraction of one compute unit's MFMA peak (0.6144 Tflop/s)
+// that the variant sustains (VariantModel below).  Splitting K into S ranges multiplies the workgroups by S and adds a
 // second pass that sums S partial products.  The cheapest (variant, S) wins: big tiles when they
 // fill the chip evenly, smaller ones when the last round would be mostly empty, a K split when
 // the output alone cannot occupy the chip.
 constexpr double kCuFlopsPerUs = 157.3e6 / 256.0;
-constexpr double kOverheadK = 256.0;
 constexpr int64_t kMaxWorkspaceBytes = 256LL << 20;
 
 struct Choice { int tile; int split; };
 
-// fraction of a compute unit's MFMA peak each variant sustains on large square problems (measured)
-const struct { int id; double eff; } kCandidates[] = {
-    {T256, 0.93}, {T256x128, 0.915}, {T128x256, 0.92}, {T128, 0.90}, {TB64, 0.80}, {T64, 0.78}};
-double tile_efficiency(int tile)
+// What each variant sustains, fitted to measurements: the fraction of a compute unit's MFMA peak when
+// the launch is a single round of workgroups (`single`) and when several workgroups per compute unit
+// follow or overlap each other (`multi`: the small tiles hide their load latency behind a co-resident
+// neighbour), and the fixed cost of a tile (first-slab latency, epilogue) in both regimes,
+// expressed as extra columns of K.
+struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
+const VariantModel kCandidates[] = {
+    {T256, 0.95, 0.95, 100, 100}, {T256x128, 0.935, 0.935, 100, 100}, {T128x256, 0.935, 0.935, 100, 100},
+    {T128, 0.92, 0.92, 100, 100}, {TB64, 0.68, 0.83, 60, 150},        {T64, 0.68, 0.80, 50, 120}};
+const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
-        if (c.id == tile) return c.eff;
-    return 0.8;
+        if (c.id == tile) return c;
+    return kCandidates[4];
+}
+// modelled microseconds of one tile of the variant over a K range of length k
+double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
+{
+    return 2.0 * bm * bn * (k + (multi ? v.overhead_multi : v.overhead_single)) /
+           (kCuFlopsPerUs * (multi ? v.multi : v.single));
 }
 
 // Split of the last, partly filled round: `tail` tiles cut into `pieces` K ranges of `piece_k` columns
@@ -122,8 +132,10 @@ double tile_efficiency(int tile)
 // of whole tiles, the second pass already charged.
 struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; };
 
-TailSplit plan_tail_split(int bm, int bn, int bk, double eff, int64_t batch, int64_t tiles, int64_t K)
+TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
 {
+    const VariantModel &vm = variant_model(tile);
+    const int bm = kShapes[tile].bm, bn = kShapes[tile].bn, bk = kShapes[tile].bk;
     TailSplit t = {tiles % 256, 1, 0, 0.0};
     if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || std::getenv("GEMMF32_NO_TAIL_SPLIT")) return t;
     const int64_t units = cdiv(K, bk);
@@ -133,8 +145,7 @@ TailSplit plan_tail_split(int bm, int bn, int bk, double eff, int64_t batch, int
     const int64_t units_per_piece = cdiv(units, S);
     S = cdiv(units, units_per_piece);                    // no empty pieces
     if (S <= 1 || t.tail * S * bm * bn * 4 > kMaxWorkspaceBytes) return t;
-    const double per_k = 2.0 * bm * bn / (kCuFlopsPerUs * eff);
-    const double t_full = per_k * ((double)K + kOverheadK), t_piece = per_k * ((double)units_per_piece * bk + kOverheadK);
+    const double t_full = tile_us(vm, bm, bn, (double)K, true), t_piece = tile_us(vm, bm, bn, (double)units_per_piece * bk, true);
     const double second_pass = 8.0;                      // launch, and reading the pieces back
     if (t_full - t_piece <= second_pass) return t;
     t.pieces = S;
@@ -163,7 +174,8 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         if (forced_tile >= 0 && c.id != forced_tile) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
-        for (int S = 1; S <= 64; S *= 2) {
+        static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64};
+        for (int S : kSplits) {
             if (forced_split >= 1) S = forced_split;
             if (S > 1) {
                 // every range holds whole slabs and at least two of them; one product only
@@ -171,10 +183,10 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
                 if ((int64_t)S * M * N * 4 > kMaxWorkspaceBytes) break;
             }
             const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
-            double cost = (double)cdiv(tiles * S, 256) * 2.0 * sh.bm * sh.bn * (k_range + kOverheadK) /
-                          (kCuFlopsPerUs * c.eff);
-            if (S > 1) cost += 6.0 + (double)(S + 1) * M * N * 4.0 / 3.0e6;   // second pass: launch + traffic at 3 TB/s
-            if (S == 1) cost -= plan_tail_split(sh.bm, sh.bn, sh.bk, c.eff, batch, tiles, K).benefit_us;
+            const int64_t wgs = tiles * S;
+            double cost = (double)cdiv(wgs, 256) * tile_us(c, sh.bm, sh.bn, k_range, wgs > 256);
+            if (S > 1) cost += 4.0 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
+            if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
             if (forced_split >= 1) break;
         }
@@ -303,7 +315,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
     // 16 become 256 pieces that run beside the full round).
     if (pl.split == 1) {
-        const TailSplit ts = plan_tail_split(bm, bn, kShapes[pl.tile].bk, tile_efficiency(pl.tile), batch, total, K);
+        const TailSplit ts = plan_tail_split(pl.tile, batch, total, K);
         if (ts.pieces > 1) {
             a.tail_first = (int)(total - ts.tail);
             a.tail_split = (int)ts.pieces;
