@@ -469,7 +469,6 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // The actions of a slab run in the groups that precede the barrier (all but the last one),
     // the same number in each, in order.
     constexpr int MOVE_GROUPS = (G > 1) ? G - 1 : 1;
-    constexpr int PER_GROUP = (N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
     // Slab t: multiply it out of LDS buffer t % 2 while
     // slab t+1 goes from register set (t+1) % PF into the other buffer and slab t+1+PF is requested
     // into the same registers (past the end: a harmless re-request of the last full slab).
@@ -491,8 +490,10 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 lds_barrier();                 // slab t+1 is complete in the other buffer
                 read_frag(next, cur ^ 1, 0);
             }
-            constexpr int FIRST = g * PER_GROUP;
-            constexpr int COUNT = !MORE ? 0 : (FIRST >= N_ACTIONS ? 0 : (FIRST + PER_GROUP > N_ACTIONS ? N_ACTIONS - FIRST : PER_GROUP));
+            // action i runs in group i * MOVE_GROUPS / N_ACTIONS: spread as evenly as the counts allow
+            constexpr int FIRST = (g * N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
+            constexpr int END = ((g + 1) * N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
+            constexpr int COUNT = (!MORE || g >= MOVE_GROUPS) ? 0 : END - FIRST;
             constexpr int MOVE_MEM = 2 * COUNT;    // one LDS write and one global load per action
             if constexpr (COUNT > 0) {
                 static_for<COUNT>([&](auto i_tag) {
