@@ -63,3 +63,33 @@ def test_ladder_host_queries():
     assert lib.gemm_f32_ladder(9, 4, 4, 4, None, 4, None, 4, None, None, 4) == -1
     assert lib.gemm_f32_ladder(0, 4, 4, 4, None, 4, None, 4, None, None, 4) == -2
     assert lib.gemm_f32_ladder(0, 0, 4, 4, None, 4, None, 4, None, None, 4) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(INCLUDE)
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_traffic_figures_are_dropped_when_the_kernel_sources_change():
+    """bench.py reports HBM traffic only while the hash of the kernel sources matches the one the
+    counters were taken with."""
+    import importlib.util
+    root = os.path.dirname(INCLUDE)
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    current = bench.kernel_sources_sha256()
+    saved = bench.TRAFFIC["sources_sha256"]
+    try:
+        bench.TRAFFIC["sources_sha256"] = current
+        t = bench.traffic_bytes("square4096")
+        assert t is not None and 4 * 3 * 4096 * 4096 <= t < 4 * 4 * 3 * 4096 * 4096   # between 1x and 4x the compulsory bytes
+        bench.TRAFFIC["sources_sha256"] = "0" * 64
+        assert bench.traffic_bytes("square4096") is None
+    finally:
+        bench.TRAFFIC["sources_sha256"] = saved
