@@ -113,12 +113,13 @@ struct Choice { int tile; int split; };
 struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
 const VariantModel kCandidates[] = {
     {T256, 0.95, 0.95, 100, 100}, {T256x128, 0.935, 0.935, 100, 100}, {T128x256, 0.935, 0.935, 100, 100},
-    {T128, 0.92, 0.92, 100, 100}, {TB64, 0.68, 0.83, 60, 150},        {T64, 0.68, 0.80, 50, 120}};
+    {T128, 0.92, 0.92, 100, 100}, {T128x64, 0.90, 0.90, 154, 100},    {T64x128, 0.87, 0.875, 130, 100},
+    {TB64, 0.79, 0.83, 200, 150}, {T64, 0.79, 0.80, 190, 120}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
         if (c.id == tile) return c;
-    return kCandidates[4];
+    return kCandidates[6];
 }
 // modelled microseconds of one tile of the variant over a K range of length k
 double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
@@ -185,7 +186,10 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
             const int64_t wgs = tiles * S;
             double cost = (double)cdiv(wgs, 256) * tile_us(c, sh.bm, sh.bn, k_range, wgs > 256);
-            if (S > 1) cost += 4.0 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
+            // a matrix shorter than the tile cannot move its edge tiles inside: every tile then runs
+            // the masked loads, which cost about a quarter more
+            if (M < sh.bm || N < sh.bn) cost *= 1.25;
+            if (S > 1) cost += 5.0 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
             if (forced_split >= 1) break;
