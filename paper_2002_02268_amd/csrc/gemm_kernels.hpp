@@ -87,8 +87,8 @@ template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
     static constexpr int BMODE = BMODE_, OCC = OCC_, AMODE = AMODE_;
-    static constexpr int PF = PF_;                             // slabs held in registers ahead of the LDS write (1 or 2)
-    static_assert(PF_ == 1 || PF_ == 2, "prefetch depth");
+    static constexpr int PF = PF_;                             // slabs held in registers ahead of the LDS write
+    static_assert(PF_ >= 1 && PF_ <= 4, "prefetch depth");
     static constexpr int THREADS = 64 * WGM * WGN;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
@@ -473,7 +473,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // slab t+1 goes from register set (t+1) % PF into the other buffer and slab t+1+PF is requested
     // into the same registers (past the end: a harmless re-request of the last full slab).
     auto slab_body = [&](const int t, auto par_tag, auto more_tag) {
-        constexpr int PAR = decltype(par_tag)::value;      // t % 2 when PF == 2 (register set choice)
+        constexpr int PAR = decltype(par_tag)::value;      // t % PF (register set choice)
         constexpr bool MORE = decltype(more_tag)::value;
         const int cur = t & 1;
         typedef std::integral_constant<int, (PAR + 1) % PF> set_t;
@@ -511,30 +511,26 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         load_slab(i0{}, 0);
         store_slab(0, i0{});
         // slab j (1 <= j <= PF) waits in register set j % PF
-        if constexpr (PF == 1) {
-            load_slab(i0{}, last < 1 ? last : 1);
-        } else {
-            load_slab(i1{}, last < 1 ? last : 1);
-            load_slab(i0{}, last < 2 ? last : 2);
-        }
+        static_for<PF>([&](auto j_tag) {
+            constexpr int j = decltype(j_tag)::value + 1;
+            load_slab(std::integral_constant<int, j % PF>{}, last < j ? last : j);
+        });
         lds_barrier();
         read_frag(f0, 0, 0);
-        if constexpr (PF == 1) {
-            for (int t = 0; t + 1 < nkf; ++t) slab_body(t, i0{}, std::true_type{});
-            slab_body(nkf - 1, i0{}, std::false_type{});
-        } else {
-            int t = 0;
-            for (; t + 2 < nkf; t += 2) {
-                slab_body(t, i0{}, std::true_type{});
-                slab_body(t + 1, i1{}, std::true_type{});
-            }
-            if (t + 2 == nkf) {
-                slab_body(t, i0{}, std::true_type{});
-                slab_body(t + 1, i1{}, std::false_type{});
+        // the loop is unrolled PF times so that the register set of every slab is a compile-time choice
+        int t = 0;
+        for (; t + PF < nkf; t += PF)
+            static_for<PF>([&](auto i_tag) { slab_body(t + decltype(i_tag)::value, i_tag, std::true_type{}); });
+        const int rest = nkf - t;                  // 1 .. PF slabs left; the last one requests nothing
+        static_for<PF>([&](auto i_tag) {
+            constexpr int i = decltype(i_tag)::value;
+            if constexpr (i + 1 < PF) {
+                if (i + 1 < rest) slab_body(t + i, i_tag, std::true_type{});
+                else if (i + 1 == rest) slab_body(t + i, i_tag, std::false_type{});
             } else {
-                slab_body(t, i0{}, std::false_type{});
+                if (PF == 1 || i + 1 == rest) slab_body(t + i, i_tag, std::false_type{});
             }
-        }
+        });
     }
     // ---- ragged last slab (K % BK columns), not pipelined -------------------------------------
     if (kleft > 0) {
