@@ -400,6 +400,25 @@ def main() -> int:
             del img, res
             torch.cuda.empty_cache()
 
+    # clock sustained under full matrix load, from a kernel of matrix instructions only; it depends on
+    # the operand values (the chip is power-limited), so it is taken on zeros and on U(-1,1) numbers
+    def mfma_clock_ghz(operands):
+        sink = torch.zeros(4, device="cuda")
+        per_wave = 1 << 16                          # 65536 MFMAs per wave, about 1.8 ms
+        binding.gemm_f32_mfma_rate_probe(per_wave, operands, sink)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(5):
+            binding.gemm_f32_mfma_rate_probe(per_wave, operands, sink)
+        c1.record()
+        torch.cuda.synchronize()
+        return 64.0 * per_wave / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
+
+    clock_zeros = mfma_clock_ghz(torch.zeros(512, device="cuda"))
+    clock_ghz = mfma_clock_ghz(torch.from_numpy(synth.uniform((512,), 99, synth.TENSOR_A)).cuda())
+    peak_at_clock = 256 * 256 * clock_ghz / 1e3     # TFLOP/s
+
     out = {
         "metric": "fp32 GEMM GFLOP/s", "value": round(gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
@@ -409,7 +428,10 @@ def main() -> int:
                    "transB": w["transB"], "dist": w["dist"], "seed": w["seed"],
                    "variant": binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"])},
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": traffic_bytes(args.workload)},
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": traffic_bytes(args.workload),
+                     "mfma_clock_ghz": round(clock_ghz, 3), "mfma_clock_ghz_zero_operands": round(clock_zeros, 3),
+                     "peak_at_mfma_clock": round(peak_at_clock, 1),
+                     "frac_of_peak_at_mfma_clock": round(achieved_tflops / peak_at_clock, 4)},
         "extra": extra,
     }
     if not args.no_cpu_baseline:

@@ -143,6 +143,21 @@ const char *gemm_f32_strerror(int status);
 /* hipError_t (as int) of the most recent GEMMF32_ELAUNCH / GEMMF32_ENOMEM on this thread, else 0. */
 int gemm_f32_last_hip_error(void);
 
+/*
+ * Measurement aid: launches 256 workgroups of 4 waves (one wave per SIMD of every compute unit) that
+ * issue mfma_per_wave (a multiple of 16) fp32 32x32x2 matrix instructions each on register operands
+ * and touch no memory.  One such instruction occupies the matrix pipe for 64 cycles, so
+ *     64 * mfma_per_wave / (run time)
+ * is the clock the chip sustains under full matrix load, and 256 CUs * 256 flop/cycle times that
+ * clock is the matrix peak actually available (the nominal 157.3 TFLOP/s assumes 2.4 GHz).
+ * operands: DEVICE pointer to 512 floats; thread t of every workgroup multiplies operands[2t] by
+ * operands[2t+1] throughout (the sustained clock depends on the values: zeros draw less power than
+ * random numbers, and the chip is power-limited under matrix load).
+ * sink: DEVICE pointer to at least one float (never written in practice).  Asynchronous on the
+ * library's stream; the caller times it.
+ */
+int gemm_f32_mfma_rate_probe(int64_t mfma_per_wave, const float *operands, float *sink);
+
 /* Releases the split-K workspace (waits for the device).  The library stays usable. */
 void gemm_f32_shutdown(void);
 

@@ -31,6 +31,7 @@ SYMBOLS = {
     "gemm_f32_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "gemm_f32_last_hip_error": (ctypes.c_int, []),
     "gemm_f32_shutdown": (None, []),
+    "gemm_f32_mfma_rate_probe": (ctypes.c_int, [_i64, _ptr, _ptr]),
     "gemm_f32_variant_name": (ctypes.c_char_p, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64,
                                                 ctypes.c_int]),
     "gemm_f32_ladder_levels": (ctypes.c_int, []),
@@ -163,6 +164,15 @@ def gemm_f32_ex_batched(A, B, C, alpha: float = 1.0, beta: float = 0.0, transA: 
     _check(lib().gemm_f32_ex_batched(batch, M, N, K, float(alpha), A.data_ptr(), _ld(A), int(A.stride(0)),
                                      int(bool(transA)), B.data_ptr(), _ld(B), int(B.stride(0)), int(bool(transB)),
                                      float(beta), C.data_ptr(), _ld(C), int(C.stride(0))))
+
+
+def gemm_f32_mfma_rate_probe(mfma_per_wave: int, operands, sink) -> None:
+    """Launches the matrix-instruction-only kernel (see gemm_f32.h) on the current torch stream."""
+    if operands.numel() < 512 or not operands.is_contiguous():
+        raise ValueError("operands must hold 512 contiguous floats")
+    _dev_f32(operands, "operands", 1)
+    _use_current_stream(sink)
+    _check(lib().gemm_f32_mfma_rate_probe(int(mfma_per_wave), operands.data_ptr(), sink.data_ptr()))
 
 
 def pack_b_panel_width() -> int:

@@ -400,6 +400,33 @@ int run_plan(const Plan &pl)
 
 thread_local char g_variant_buf[64];
 
+// Nothing but matrix instructions: every wave issues `steps` rounds of 16 MFMAs on four independent
+// accumulators from registers.  One MFMA 32x32x2 occupies a SIMD's matrix pipe for 64 cycles, so the
+// run time gives the clock the chip sustains under full matrix load.  The operands come from
+// operands[2*lane], operands[2*lane + 1]: the sustained clock depends on their values (zeros draw
+// less power than random numbers).
+__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(int steps, const float *operands, float *sink)
+{
+    v16f acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const float a = operands[2 * threadIdx.x], b = operands[2 * threadIdx.x + 1];
+    for (int s = 0; s < steps; ++s) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += acc[i][v];
+    if (t == -1.f) sink[0] = t;          // never true; keeps the accumulators alive
+}
+
 }  // namespace
 
 namespace gemmf32_host {
@@ -527,6 +554,16 @@ int gemm_f32_packed(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda
 {
     if (Bp != nullptr && !aligned16(Bp)) return GEMMF32_EINVAL;
     return run_plan(make_plan(1, M, N, K, A, lda, 0, Bp, kPanel, 0, C, ldc, 0, B_PACKED));
+}
+
+int gemm_f32_mfma_rate_probe(int64_t mfma_per_wave, const float *operands, float *sink)
+{
+    if (mfma_per_wave < 16 || mfma_per_wave > (1LL << 30) || mfma_per_wave % 16 != 0) return GEMMF32_EINVAL;
+    if (sink == nullptr || operands == nullptr) return GEMMF32_ENULL;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, g_stream, (int)(mfma_per_wave / 16), operands, sink);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
 }
 
 int gemm_f32_set_stream(void *hip_stream)

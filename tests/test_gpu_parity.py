@@ -564,3 +564,16 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
         os.environ.pop("GEMMF32_NO_TAIL_SPLIT", None)
+
+
+def test_mfma_rate_probe_runs_and_validates_its_arguments():
+    lib = binding.lib()
+    ops = torch.zeros(512, device="cuda")
+    sink = torch.full((4,), 7.0, device="cuda")
+    binding.gemm_f32_mfma_rate_probe(1024, ops, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(sink, torch.full((4,), 7.0, device="cuda"))       # the sink is never written
+    assert lib.gemm_f32_mfma_rate_probe(1000, ops.data_ptr(), sink.data_ptr()) == -1    # not a multiple of 16
+    assert lib.gemm_f32_mfma_rate_probe(0, ops.data_ptr(), sink.data_ptr()) == -1
+    assert lib.gemm_f32_mfma_rate_probe(1024, None, sink.data_ptr()) == -2
+    assert lib.gemm_f32_mfma_rate_probe(1024, ops.data_ptr(), None) == -2
