@@ -256,3 +256,48 @@ def test_ex_many_seeded_shapes_bit_exact():
         whole = bufC.cpu().numpy()
         assert np.array_equal(whole[:, :N].astype(np.float64), ref), case
         assert np.isnan(whole[:, N:]).all(), case
+
+
+def test_ex_batched_many_seeded_shapes_bit_exact():
+    """40 batched products with seeded shapes, batch counts, transpose flags, integer scalars, padded rows
+    and batch strides larger than one product: exact on integer operands, padding and gaps untouched."""
+    draws = synth.small_ints((40, 12), 5151, 7, 0, 1 << 20).astype(np.int64)
+    for case, d in enumerate(draws):
+        d = [int(x) for x in d]
+        batch = 1 + d[0] % 9
+        M, N, K = 1 + d[1] % 300, 1 + d[2] % 300, 1 + d[3] % 200
+        if d[4] % 5 == 0:
+            M = N = K = 64                                  # the streaming path when the scalars are (1, 0)
+        tA, tB = bool(d[5] & 1), bool(d[5] & 2)
+        alpha, beta = float(d[6] % 4 - 1), float(d[7] % 3 - 1)
+        if d[4] % 10 == 0:
+            tA, alpha, beta = False, 1.0, 0.0
+        pad, gap = d[8] % 4, d[9] % 3
+        print(f"case {case}: batch={batch} M={M} N={N} K={K} tA={tA} tB={tB} alpha={alpha} beta={beta} pad={pad} gap={gap}",
+              flush=True)
+        A = synth.small_ints((batch, M, K), 5200 + case, synth.TENSOR_A)
+        B = synth.small_ints((batch, K, N), 5200 + case, synth.TENSOR_B)
+        C0 = synth.small_ints((batch, M, N), 5200 + case, TENSOR_C, -9, 9)
+        As = np.ascontiguousarray(A.transpose(0, 2, 1)) if tA else A
+        Bs = np.ascontiguousarray(B.transpose(0, 2, 1)) if tB else B
+
+        def spaced(x, fill):
+            buf = torch.full(((1 + gap) * x.shape[0], x.shape[1], x.shape[2] + pad), fill, dtype=torch.float32,
+                             device="cuda")
+            view = buf[:: 1 + gap, :, : x.shape[2]]
+            view.copy_(torch.from_numpy(x))
+            return view, buf
+
+        dA, _ = spaced(As, float("nan"))
+        dB, _ = spaced(Bs, float("nan"))
+        dC, bufC = spaced(C0, 555.0)
+        binding.gemm_f32_ex_batched(dA, dB, dC, alpha, beta, tA, tB)
+        whole = bufC.cpu().numpy()
+        for b in range(batch):
+            ref = oracle.gemm_f32_ex(As[b], Bs[b], C0[b], alpha, beta, tA, tB)
+            assert np.array_equal(whole[(1 + gap) * b, :, :N].astype(np.float64), ref), (case, b)
+        assert (whole[:, :, N:] == 555.0).all(), case
+        if gap:
+            keep = np.ones(whole.shape[0], bool)
+            keep[:: 1 + gap] = False
+            assert (whole[keep] == 555.0).all(), case
