@@ -9,6 +9,9 @@
  * Programs (terms):  atom | (head arg ...)
  *   functional array language (Section 4):
  *     (let x e0 e1) (fun x e) (app f a) (build n f) (get a i) (length a), variables, integers
+ *   image language (Section 5): the binomial filter
+ *     (fun img (map2D (fun nbh (reduce add 0 (map mult (zip (join weights2d) (join nbh)))))
+ *                     (slide2D 3 1 (pad2D 1 img))))
  *   loop nests over the product's axes (stand-in for the RISE program of Section 6.3):
  *     (loop AXIS EXTENT KIND body), AXIS in M N K, KIND in seq grid wave unroll slab,
  *     leaves mac (one multiply-accumulate) and mfma32x32x2 (one matrix instruction)
@@ -18,6 +21,7 @@
  *   (body s) (function s) (argument s) (bodyN n s)                               Section 3.6
  *   (topDown s) (bottomUp s) (allTopDown s) (allBottomUp s) (tryAll s) (normalize s)   3.7, 3.8
  *   rules, Section 4:   buildGet lenBuild letPartialEval letApp funToLet
+ *   rules, Section 5:   (separateDot w2d wh wv) (storeRows image|line)
  *   rules, Section 6:   (split AXIS n) (cover AXIS n) interchange (mark KIND) mfma,
  *                       and built from them (tile bm bn) (reorder p0 p1 ...)
  * `one` picks the leftmost sub-term on which its strategy succeeds, so every rewrite is
@@ -79,6 +83,14 @@ typedef struct {
  */
 int elevate_schedule_gemm(int64_t M, int64_t N, int64_t K, const char *strategy, gemmf32_schedule *out,
                           char *nest, size_t nest_cap);
+
+/*
+ * Starts from the 3x3 binomial filter in its naive form (above), applies `strategy`, and reads off
+ * which of the three kernels of binomial_f32.h computes the result: *form = 0 naive; 1 separated
+ * (after separateDot, row sums stored as a whole image); 2 scanline (row sums stored per line).
+ * program (may be NULL): the rewritten program (or the failing strategy / why it has no kernel).
+ */
+int elevate_schedule_filter(const char *strategy, int *form, char *program, size_t program_cap);
 
 /* The strategy that expresses what the library's own dispatch does for this shape (tile and K
  * split from its cost model), as text that elevate_schedule_gemm accepts. */

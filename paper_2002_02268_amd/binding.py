@@ -47,6 +47,8 @@ SYMBOLS = {
                                        ctypes.POINTER(ctypes.c_int), ctypes.c_char_p, ctypes.c_size_t]),
     "elevate_alpha_equal": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p]),
     "elevate_schedule_gemm": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_char_p, _ptr, ctypes.c_char_p, ctypes.c_size_t]),
+    "elevate_schedule_filter": (ctypes.c_int, [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int), ctypes.c_char_p,
+                                               ctypes.c_size_t]),
     "elevate_default_strategy": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_char_p, ctypes.c_size_t]),
     "gemm_f32_scheduled": (ctypes.c_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
 }
@@ -318,6 +320,14 @@ def elevate_schedule_gemm(M: int, N: int, K: int, strategy: str):
     nest = ctypes.create_string_buffer(1 << 14)
     rc = lib().elevate_schedule_gemm(M, N, K, strategy.encode(), ctypes.byref(sched), nest, len(nest))
     return rc, sched, nest.value.decode()
+
+
+def elevate_schedule_filter(strategy: str):
+    """Rewrites the naive binomial filter with a strategy.  Returns (code, form, program text)."""
+    form = ctypes.c_int(-1)
+    buf = ctypes.create_string_buffer(1 << 12)
+    rc = lib().elevate_schedule_filter(strategy.encode(), ctypes.byref(form), buf, len(buf))
+    return rc, form.value, buf.value.decode()
 
 
 def elevate_default_strategy(M: int, N: int, K: int) -> str:

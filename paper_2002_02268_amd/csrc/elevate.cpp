@@ -375,6 +375,40 @@ Strategy<TermP> mfma()
     });
 }
 
+// ---- the image-processing language of Section 5 --------------------------------------------------------
+// The binomial filter as the paper writes it, with dot spelled out:
+//   (fun img (map2D (fun nbh (reduce add 0 (map mult (zip (join weights2d) (join nbh)))))
+//                   (slide2D 3 1 (pad2D 1 img))))
+//
+// separateDot(w2d, wh, wv), Section 5.2: the dot product of the joined 2-D weights with the joined
+// neighbourhood becomes  nbh |> map(dot(wh)) |> dot(wv), written (dot wv (map (dot wh) nbh)).
+// Nothing checks that wh and wv separate w2d: that is left to the author of the strategy, as in
+// the paper.
+Strategy<TermP> separateDot(const TermP &w2d, const TermP &wh, const TermP &wv)
+{
+    return rule("separateDot", [w2d, wh, wv](const TermP &p) -> TermP {
+        if (!is_node(p, "reduce", 3) || !is_atom(p->args[0]) || p->args[0]->head != "add" || !is_atom(p->args[1]) ||
+            p->args[1]->head != "0")
+            return nullptr;
+        const TermP &m = p->args[2];
+        if (!is_node(m, "map", 2) || !is_atom(m->args[0]) || m->args[0]->head != "mult") return nullptr;
+        const TermP &z = m->args[1];
+        if (!is_node(z, "zip", 2) || !is_node(z->args[0], "join", 1) || !is_node(z->args[1], "join", 1)) return nullptr;
+        if (!equal(z->args[0]->args[0], w2d)) return nullptr;
+        return node("dot", {wv, node("map", {node("dot", {wh}), z->args[1]->args[0]})});
+    });
+}
+// Where the row sums of the separated filter live, the counterpart of Halide's compute_root /
+// compute_at for the vertical stage (Section 5.1): (map (dot wh) nbh) under the outer dot becomes
+// (stored image ...) -- a whole temporary image -- or (stored line ...) -- the scanline form.
+Strategy<TermP> storeRows(const std::string &where)
+{
+    return rule("storeRows(" + where + ")", [where](const TermP &p) -> TermP {
+        if (!is_node(p, "dot", 2) || !is_node(p->args[1], "map", 2) || !is_node(p->args[1]->args[0], "dot", 1)) return nullptr;
+        return node("dot", {p->args[0], node("stored", {atom(where), p->args[1]})});
+    });
+}
+
 // ---- language-specific traversals (Section 3.6) -------------------------------------------------------
 Strategy<TermP> child(const std::string &name, const char *head, size_t nargs, size_t index, Strategy<TermP> s,
                       const char *head2 = nullptr, size_t nargs2 = 0, size_t index2 = 0)
@@ -514,6 +548,17 @@ Strategy<TermP> compile_strategy(const TermP &e, std::string &err)
         if (k != "grid" && k != "wave" && k != "unroll" && k != "slab") { err = "mark: the kind is grid, wave, unroll or slab"; return S(); }
         return mark(k);
     }
+    if (h == "separateDot") {
+        if (e->args.size() != 3) { err = "separateDot takes the 2-D weights and the horizontal and vertical weights"; return S(); }
+        return separateDot(e->args[0], e->args[1], e->args[2]);
+    }
+    if (h == "storeRows") {
+        if (e->args.size() != 1 || !is_atom(e->args[0]) || (e->args[0]->head != "image" && e->args[0]->head != "line")) {
+            err = "storeRows takes image or line";
+            return S();
+        }
+        return storeRows(e->args[0]->head);
+    }
     if (h == "tile") {
         std::vector<long long> v;
         if (e->args.size() != 2 || !ints_from(e, 0, v) || v[0] < 1 || v[1] < 1) { err = "tile takes two positive block sizes"; return S(); }
@@ -531,6 +576,41 @@ Strategy<TermP> compile_strategy(const TermP &e, std::string &err)
     }
     err = "unknown strategy '" + h + "'";
     return S();
+}
+
+TermP binomial_filter_program()
+{
+    std::string err;
+    return parse("(fun img (map2D (fun nbh (reduce add 0 (map mult (zip (join weights2d) (join nbh))))) "
+                 "(slide2D 3 1 (pad2D 1 img))))", err);
+}
+
+namespace {
+// counts sub-terms of t (t included) for which pred holds
+template <class F> int count_if(const TermP &t, F pred)
+{
+    int n = pred(t) ? 1 : 0;
+    for (const auto &a : t->args) n += count_if(a, pred);
+    return n;
+}
+}  // namespace
+
+int lower_filter(const TermP &program, std::string &err)
+{
+    const int naive = count_if(program, [](const TermP &t) {
+        return is_node(t, "reduce", 3) && is_node(t->args[2], "map", 2) && is_node(t->args[2]->args[1], "zip", 2) &&
+               is_node(t->args[2]->args[1]->args[0], "join", 1);
+    });
+    const int separated = count_if(program, [](const TermP &t) {
+        return is_node(t, "dot", 2) && (is_node(t->args[1], "map", 2) || is_node(t->args[1], "stored", 2));
+    });
+    const int image = count_if(program, [](const TermP &t) { return is_node(t, "stored", 2) && t->args[0]->head == "image"; });
+    const int line = count_if(program, [](const TermP &t) { return is_node(t, "stored", 2) && t->args[0]->head == "line"; });
+    const int window = count_if(program, [](const TermP &t) { return is_node(t, "slide2D", 3); });
+    if (window != 1 || naive + separated != 1) { err = "not a 3x3 filter over one sliding window"; return -1; }
+    if (naive == 1) return 0;
+    if (image + line != 1) { err = "the separated filter does not say where its row sums are stored"; return -1; }
+    return image == 1 ? 1 : 2;
 }
 
 TermP product_nest(long long M, long long N, long long K)

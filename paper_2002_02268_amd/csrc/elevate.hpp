@@ -221,6 +221,12 @@ Strategy<TermP> compile_strategy(const TermP &expr, std::string &err);
 TermP substitute(const TermP &e, const std::string &x, const TermP &v);
 bool alpha_equal(const TermP &a, const TermP &b);
 
+// The 3x3 binomial filter of Section 5 in its naive form, and what a rewritten form says about the
+// kernel that runs it: 0 naive (nine taps per pixel), 1 separated with the row sums in a temporary
+// image, 2 scanline (row sums kept per line); -1 (and err) if the program is none of these.
+TermP binomial_filter_program();
+int lower_filter(const TermP &program, std::string &err);
+
 // The loop nest of the plain product: (loop M m seq (loop N n seq (loop K k seq mac))).
 TermP product_nest(long long M, long long N, long long K);
 

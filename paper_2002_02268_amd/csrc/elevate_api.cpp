@@ -191,6 +191,27 @@ int elevate_schedule_gemm(int64_t M, int64_t N, int64_t K, const char *strategy,
     return built ? ELEVATE_OK : ELEVATE_ENOKERNEL;
 }
 
+int elevate_schedule_filter(const char *strategy, int *form, char *program_buf, size_t program_cap)
+{
+    put(program_buf, program_cap, "");
+    if (strategy == nullptr || form == nullptr) return ELEVATE_ENULL;
+    *form = -1;
+    Trace trace;
+    TermP program;
+    std::string text;
+    const int rc = apply(strategy, binomial_filter_program(), program, text, trace);
+    put(program_buf, program_cap, text);
+    if (rc != ELEVATE_OK) return rc;
+    std::string err;
+    const int f = lower_filter(program, err);
+    if (f < 0) {
+        put(program_buf, program_cap, err);
+        return ELEVATE_ELOWER;
+    }
+    *form = f;
+    return ELEVATE_OK;
+}
+
 int elevate_default_strategy(int64_t M, int64_t N, int64_t K, char *strategy, size_t cap)
 {
     put(strategy, cap, "");

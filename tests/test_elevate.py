@@ -319,3 +319,40 @@ def test_scheduled_entry_point_validates_on_the_host():
     bad.bm = 512
     assert lib.gemm_f32_scheduled(ctypes.byref(bad), 4096, 4096, 4096, None, 4096, None, 4096, None, 4096, 0) == -1
     assert lib.gemm_f32_scheduled(ref, 4096, 4096, 4096, None, 4096, None, 4096, None, 4096, 0) == -2      # null operands
+
+
+# ---------------------------------------------------------------- Section 5: the binomial filter
+
+BF = ("(fun img (map2D (fun nbh (reduce add 0 (map mult (zip (join weights2d) (join nbh))))) "
+      "(slide2D 3 1 (pad2D 1 img))))")
+SEPARATE = "(topDown (separateDot weights2d weightsH weightsV))"
+
+
+def test_separate_dot_rewrites_the_naive_filter_as_section_5_2_prints_it():
+    code, out, steps = rw(SEPARATE, BF)
+    # nbh |> map(dot(weightsH)) |> dot(weightsV), inside the unchanged pad / slide / map2D pipeline
+    assert (code, steps) == (0, 1)
+    assert out == ("(fun img (map2D (fun nbh (dot weightsV (map (dot weightsH) nbh))) "
+                   "(slide2D 3 1 (pad2D 1 img))))")
+    # the underlined parts of the pattern must match: other weights, another operator, no match
+    assert rw("(topDown (separateDot otherWeights weightsH weightsV))", BF)[0] == b.ELEVATE_FAILED
+    assert rw(SEPARATE, BF.replace("add", "max"))[0] == b.ELEVATE_FAILED
+    assert rw(SEPARATE, BF.replace("mult", "add"))[0] == b.ELEVATE_FAILED
+    assert rw(SEPARATE, out)[0] == b.ELEVATE_FAILED                     # already separated
+    assert rw("(separateDot weights2d weightsH weightsV)", BF)[0] == b.ELEVATE_FAILED   # not at the root
+
+
+def test_filter_strategies_select_the_three_kernels():
+    assert b.elevate_schedule_filter("id")[:2] == (0, 0)                                 # naive
+    code, form, prog = b.elevate_schedule_filter(f"(seq {SEPARATE} (topDown (storeRows image)))")
+    assert (code, form) == (0, 1) and "(stored image (map (dot weightsH) nbh))" in prog   # separated
+    code, form, prog = b.elevate_schedule_filter(f"(seq {SEPARATE} (topDown (storeRows line)))")
+    assert (code, form) == (0, 2) and "(stored line " in prog                             # scanline
+    # separated but nobody said where the row sums live: no kernel
+    code, form, why = b.elevate_schedule_filter(SEPARATE)
+    assert code == b.ELEVATE_ELOWER and form == -1 and "stored" in why
+    # the storage choice is only valid on the separated form
+    assert b.elevate_schedule_filter("(topDown (storeRows line))")[0] == b.ELEVATE_FAILED
+    twice = f"(seq {SEPARATE} (topDown (storeRows line)) (topDown (storeRows image)))"
+    assert b.elevate_schedule_filter(twice)[0] == b.ELEVATE_FAILED
+    assert b.elevate_schedule_filter("(storeRows nowhere)")[0] == b.ELEVATE_EPARSE

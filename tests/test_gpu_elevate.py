@@ -93,3 +93,23 @@ def test_default_schedule_runs_the_same_kernel_as_the_plain_entry_point():
         b.gemm_f32(A, B, C1)
         b.gemm_f32_scheduled(sched, A, B, C2)
         assert torch.equal(C1, C2)
+
+
+def test_filter_scheduled_by_a_strategy_matches_the_oracle():
+    """Section 5 end to end: the naive filter, rewritten by topDown(separateDot) and a storage choice,
+    selects one of the three kernels; each result is checked against the nine-tap oracle."""
+    separate = "(topDown (separateDot weights2d weightsH weightsV))"
+    strategies = {"id": 0, f"(seq {separate} (topDown (storeRows image)))": 1,
+                  f"(seq {separate} (topDown (storeRows line)))": 2}
+    img = synth.uniform((300, 517), 950, synth.TENSOR_A)
+    ints = synth.small_ints((300, 517), 951, synth.TENSOR_A, -50, 50)
+    for text, want in strategies.items():
+        code, form, prog = b.elevate_schedule_filter(text)
+        assert (code, form) == (0, want), prog
+        for image, exact in ((img, False), (ints, True)):
+            out = torch.full((300, 517), float("nan"), device="cuda")
+            tmp = torch.empty((300, 517), device="cuda")
+            b.binomial3x3_f32_variant(form, dev(image), out, tmp)
+            got = out.cpu().numpy().astype(np.float64)
+            ref = oracle.binomial3x3_f32(image)
+            assert np.array_equal(got, ref) if exact else np.max(np.abs(got - ref)) <= 1e-6
