@@ -221,3 +221,12 @@ def test_generator_is_counter_based_and_in_range():
     i = synth.small_ints((5000,), 8, synth.TENSOR_A)
     assert set(np.unique(i)) == {-2.0, -1.0, 0.0, 1.0, 2.0}
     assert set(np.unique(synth.signs(100, 9))) == {-1.0, 1.0}
+
+
+def test_generator_output_function_is_the_published_splitmix64():
+    """The first three outputs of SplitMix64 seeded with 0 (state advanced by the golden-ratio
+    increment, then the two multiply-xorshift rounds), as the published reference prints them."""
+    with np.errstate(over="ignore"):
+        state = np.arange(1, 4, dtype=np.uint64) * synth._GOLDEN
+        got = [int(v) for v in synth._mix(state)]
+    assert got == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
