@@ -356,3 +356,29 @@ def test_filter_strategies_select_the_three_kernels():
     twice = f"(seq {SEPARATE} (topDown (storeRows line)) (topDown (storeRows image)))"
     assert b.elevate_schedule_filter(twice)[0] == b.ELEVATE_FAILED
     assert b.elevate_schedule_filter("(storeRows nowhere)")[0] == b.ELEVATE_EPARSE
+
+
+# ---------------------------------------------------------------- Section 6.1: the tutorial's loop orders
+
+def test_blocking_and_loop_permutation_schedules_give_the_loop_orders_of_section_6_1():
+    """blocking: tile(32,32) on the two outer loops, split k by 4, reorder (xo, yo, ko, ki, xi, yi);
+    loop permutation: the same with ki and xi switched: (xo, yo, ko, xi, ki, yi)."""
+    nest = "(loop M 1024 seq (loop N 1024 seq (loop K 1024 seq mac)))"
+
+    def order(text):
+        out, axes = [], text
+        import re
+        return re.findall(r"\\(loop ([MNK]) (\\d+)", text)
+
+    blocking = "(seq (tile 32 32) (bodyN 4 (split K 4)) (reorder 0 1 4 5 2 3))"
+    code, out, _ = rw(blocking, nest)
+    assert code == 0
+    assert order(out) == [("M", "32"), ("N", "32"), ("K", "256"), ("K", "4"), ("M", "32"), ("N", "32")]
+    permuted = "(seq (tile 32 32) (bodyN 4 (split K 4)) (reorder 0 1 4 2 5 3))"
+    code, out, _ = rw(permuted, nest)
+    assert code == 0
+    assert order(out) == [("M", "32"), ("N", "32"), ("K", "256"), ("M", "32"), ("K", "4"), ("N", "32")]
+    # from the blocking order, switching ki and xi is one interchange at depth 3
+    assert rw(f"(seq {blocking} (bodyN 3 interchange))", nest)[1] == out
+    # parallelising the outermost loop (the tutorial's last version) is topDown(mark grid)
+    assert rw(f"(seq {permuted} (topDown (mark grid)))", nest)[1].startswith("(loop M 32 grid (loop N 32 seq")
