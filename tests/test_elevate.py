@@ -366,9 +366,8 @@ def test_blocking_and_loop_permutation_schedules_give_the_loop_orders_of_section
     nest = "(loop M 1024 seq (loop N 1024 seq (loop K 1024 seq mac)))"
 
     def order(text):
-        out, axes = [], text
         import re
-        return re.findall(r"\\(loop ([MNK]) (\\d+)", text)
+        return re.findall(r"[(]loop ([MNK]) ([0-9]+)", text)
 
     blocking = "(seq (tile 32 32) (bodyN 4 (split K 4)) (reorder 0 1 4 5 2 3))"
     code, out, _ = rw(blocking, nest)
