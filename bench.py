@@ -26,10 +26,10 @@ HBM_GBS = 8000.0
 # of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
 # one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "f02cd02eb84d558888a2cd3615e47cb4ba6447e4e2235d476eea72dcc6186d99",
-    "square4096": {"fetch_kib": 196795.8, "write_kib": 65792.0, "copy_fetch_kib": 32815.5, "copy_write_kib": 65536.0},
-    "square1024": {"fetch_kib": 14403.3, "write_kib": 4096.0, "copy_fetch_kib": 32815.5, "copy_write_kib": 65536.0},
-    "batched64": {"fetch_kib": 65571.7, "write_kib": 65536.0, "copy_fetch_kib": 32815.5, "copy_write_kib": 65536.0},
+    "sources_sha256": "66f6c7d16c63347f7bdc608bd0ff6bc0035d9286205346460b7198c9511d1043",
+    "square4096": {"fetch_kib": 196795.0, "write_kib": 65792.0, "copy_fetch_kib": 32816.2, "copy_write_kib": 65536.0},
+    "square1024": {"fetch_kib": 14403.1, "write_kib": 4096.0, "copy_fetch_kib": 32816.2, "copy_write_kib": 65536.0},
+    "batched64": {"fetch_kib": 65571.7, "write_kib": 65536.0, "copy_fetch_kib": 32816.2, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 

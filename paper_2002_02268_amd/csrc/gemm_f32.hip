@@ -113,7 +113,7 @@ struct Choice { int tile; int split; };
 struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
 const VariantModel kCandidates[] = {
     {T256, 0.95, 0.95, 100, 100}, {T256x128, 0.935, 0.935, 100, 100}, {T128x256, 0.935, 0.935, 100, 100},
-    {T128, 0.92, 0.92, 100, 100}, {T128x64, 0.90, 0.90, 154, 100},    {T64x128, 0.87, 0.875, 130, 100},
+    {T128, 0.92, 0.93, 100, 100}, {T128x64, 0.90, 0.90, 154, 100},    {T64x128, 0.87, 0.875, 130, 100},
     {TB64, 0.79, 0.83, 200, 150}, {T64, 0.79, 0.80, 190, 120}};
 const VariantModel &variant_model(int tile)
 {
