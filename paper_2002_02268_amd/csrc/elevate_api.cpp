@@ -49,7 +49,7 @@ struct NestLoop { char axis; long long extent; const char *kind; };   // kind: t
 // every loop its implementation, and turn the innermost block into the matrix instruction.
 std::string default_strategy(long long M, long long N, long long K, const gemmf32_host::TileChoice &c)
 {
-    const long long wave_m = c.bm / 2, wave_n = c.bn / 2;          // all kernels: 2 x 2 waves
+    const long long wave_m = c.bm / c.waves_m, wave_n = c.bn / c.waves_n;
     const long long k_range = c.split > 1 ? ((K + c.split - 1) / c.split + c.bk - 1) / c.bk * c.bk
                                           : (K + c.bk - 1) / c.bk * c.bk;
     std::vector<NestLoop> nest = {{'M', M, "seq"}, {'N', N, "seq"}, {'K', K, "seq"}};
@@ -186,8 +186,8 @@ int elevate_schedule_gemm(int64_t M, int64_t N, int64_t K, const char *strategy,
     out->split_k = (int32_t)ls.split_k;
     out->tiles_m = ls.tiles_m; out->tiles_n = ls.tiles_n;
     out->k_range = ls.k_range;
-    const bool built = gemmf32_host::has_kernel(out->bm, out->bn, out->bk) && out->waves_m == 2 && out->waves_n == 2 &&
-                       out->wave_m * 2 == out->bm && out->wave_n * 2 == out->bn;
+    const bool built = gemmf32_host::has_kernel(out->bm, out->bn, out->bk, out->waves_m, out->waves_n) &&
+                       (int64_t)out->wave_m * out->waves_m == out->bm && (int64_t)out->wave_n * out->waves_n == out->bn;
     return built ? ELEVATE_OK : ELEVATE_ENOKERNEL;
 }
 
@@ -227,7 +227,7 @@ int gemm_f32_scheduled(const gemmf32_schedule *s, int64_t M, int64_t N, int64_t 
                        const float *B, int64_t ldb, float *C, int64_t ldc, int transB)
 {
     if (s == nullptr) return GEMMF32_ENULL;
-    if (!gemmf32_host::has_kernel(s->bm, s->bn, s->bk) || s->waves_m != 2 || s->waves_n != 2) return GEMMF32_EINVAL;
+    if (!gemmf32_host::has_kernel(s->bm, s->bn, s->bk, s->waves_m, s->waves_n)) return GEMMF32_EINVAL;
     if (s->split_k < 1) return GEMMF32_EINVAL;
     if (M > 0 && N > 0 && K > 0) {
         // the schedule must be one for this problem: its blocks cover it with no idle workgroup

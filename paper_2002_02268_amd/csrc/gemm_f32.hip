@@ -114,7 +114,8 @@ struct VariantModel { int id; double single, multi, overhead_single, overhead_mu
 const VariantModel kCandidates[] = {
     {T256, 0.95, 0.95, 100, 100}, {T256x128, 0.935, 0.935, 100, 100}, {T128x256, 0.935, 0.935, 100, 100},
     {T128, 0.92, 0.93, 100, 100}, {T128x64, 0.90, 0.90, 154, 100},    {T64x128, 0.87, 0.875, 130, 100},
-    {TB64, 0.79, 0.83, 200, 150}, {T64, 0.79, 0.80, 190, 120}};
+    {TB64, 0.79, 0.83, 200, 150}, {T64, 0.79, 0.80, 190, 120},
+    {T128x32, 0.70, 0.70, 150, 120}, {T32x128, 0.70, 0.70, 150, 120}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -189,6 +190,10 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             // a matrix shorter than the tile cannot move its edge tiles inside: every tile then runs
             // the masked loads, which cost about a quarter more
             if (M < sh.bm || N < sh.bn) cost *= 1.25;
+            // both operands cross the memory interface at least once, at 5.2 TB/s at best: what
+            // bounds products with one short dimension
+            const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / 5.2e6;
+            if (cost < hbm_us) cost = hbm_us;
             if (S > 1) cost += 5.0 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
@@ -282,6 +287,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (batch > 1 && (sA < 0 || sB < 0 || sC < 0)) { pl.status = GEMMF32_EINVAL; return pl; }
     if (batch == 0 || M == 0 || N == 0) return pl;  // nothing to do
 
+
     const Choice ch = choose_tile(batch, M, N, K);
     pl.tile = ch.tile;
     pl.split = ch.split;
@@ -351,6 +357,26 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     return pl;
 }
 
+// second pass of a K split: sums `split` dense M x N partial products from W into C
+int launch_splitk_reduce(const float *W, float *C, int M, int N, int64_t ldc, int split, float alpha, float beta)
+{
+    // lanes per group of 4 columns: enough to put about 64K threads on the chip, at most 16, at most S
+    const int64_t chunks = (int64_t)M * ((N + 3) / 4);
+    int sl = 1;
+    while (sl < 16 && sl * 2 <= split && chunks * sl < 65536) sl *= 2;
+    const dim3 grid((unsigned)cdiv(chunks * sl, 256)), block(256);
+    switch (sl) {
+    case 1: hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    default: hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
+}
+
 int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
@@ -380,22 +406,7 @@ int run_plan(const Plan &pl)
     a.C = g_workspace;
     rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
     if (rc != GEMMF32_OK) return rc;
-    // lanes per group of 4 columns: enough to put about 64K threads on the chip, at most 16, at most S
-    const int64_t chunks = (int64_t)a.M * ((a.N + 3) / 4);
-    int sl = 1;
-    while (sl < 16 && sl * 2 <= pl.split && chunks * sl < 65536) sl *= 2;
-    const dim3 grid((unsigned)cdiv(chunks * sl, 256)), block(256);
-    float *W = g_workspace;
-    switch (sl) {
-    case 1: hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
-    case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
-    case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
-    case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
-    default: hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, g_stream, W, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta); break;
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail_hip(e);
-    return GEMMF32_OK;
+    return launch_splitk_reduce(g_workspace, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta);
 }
 
 thread_local char g_variant_buf[64];
@@ -440,13 +451,13 @@ TileChoice choose(int64_t M, int64_t N, int64_t K)
         const int64_t k_range = cdiv(cdiv(K, split), sh.bk) * sh.bk;
         split = (int)cdiv(K, k_range);
     }
-    return TileChoice{sh.bm, sh.bn, sh.bk, split};
+    return TileChoice{sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, split};
 }
 
-bool has_kernel(int bm, int bn, int bk)
+bool has_kernel(int bm, int bn, int bk, int waves_m, int waves_n)
 {
     for (const TileShape &sh : kShapes)
-        if (sh.bm == bm && sh.bn == bn && sh.bk == bk) return true;
+        if (sh.bm == bm && sh.bn == bn && sh.bk == bk && sh.waves_m == waves_m && sh.waves_n == waves_n) return true;
     return false;
 }
 

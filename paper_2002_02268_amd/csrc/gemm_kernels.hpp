@@ -295,7 +295,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B) of the slab that
-    // starts a_off / b_off elements after slab 0; the slab is in range along k
+    // starts a_off / b_off elements after slab 0; the slab is in range along k.  Out-of-range rows and
+    // columns come from a clamped address; they are zeroed when the slot is written to LDS
+    // (masked_slot), not here, so that nothing has to wait for the load before then.
     auto load_slot = [&](auto slot_tag, auto set_tag, int64_t a_off, int64_t b_off) {
         constexpr int S = decltype(slot_tag)::value, SET = decltype(set_tag)::value;
         if constexpr (S < A_ITERS) {
@@ -303,16 +305,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             v4f v;
             if constexpr (A_ELEMENTWISE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = (pa[r] + a_off)[a_d[r][e]];
-                    v[e] = (a_col[r] + e < M) ? x : 0.f;
-                }
+                for (int e = 0; e < 4; ++e) v[e] = (pa[r] + a_off)[a_d[r][e]];
             } else {
                 v = load4(pa[r] + a_off);
-                if constexpr (EDGE != 0) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = a_ok[r] ? v[e] : 0.f;
-                }
             }
             ra[SET][r] = v;
         } else {
@@ -320,19 +315,32 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             v4f v;
             if constexpr (B_ELEMENTWISE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = (pb[r] + b_off)[b_d[r][e]];
-                    v[e] = (b_col[r] + e < N) ? x : 0.f;
-                }
+                for (int e = 0; e < 4; ++e) v[e] = (pb[r] + b_off)[b_d[r][e]];
             } else {
                 v = load4(pb[r] + b_off);
-                if constexpr (EDGE != 0 && T::BMODE != B_NN) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = b_ok[r] ? v[e] : 0.f;
-                }
             }
             rb[SET][r] = v;
         }
+    };
+    auto masked_slot = [&](auto slot_tag, v4f v) {
+        constexpr int S = decltype(slot_tag)::value;
+        if constexpr (EDGE != 0) {
+            if constexpr (S < A_ITERS) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool ok = A_ELEMENTWISE ? (a_col[S] + e < M) : a_ok[S];
+                    v[e] = ok ? v[e] : 0.f;
+                }
+            } else if constexpr (B_ELEMENTWISE || T::BMODE != B_NN) {
+                constexpr int r = S - A_ITERS;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool ok = B_ELEMENTWISE ? (b_col[r] + e < N) : b_ok[r];
+                    v[e] = ok ? v[e] : 0.f;
+                }
+            }
+        }
+        return v;
     };
     auto load_slab = [&](auto set_tag, int slab) {
         const int64_t a_off = (int64_t)slab * a_step, b_off = (int64_t)slab * b_step;
@@ -387,10 +395,14 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         constexpr int SET = decltype(set_tag)::value;
         float *As = lds + stage * T::STAGE_FLOATS;
         float *Bs = As + T::A_TILE;
-#pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) *reinterpret_cast<v4f *>(&As[sa_off[r]]) = ra[SET][r];
-#pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = rb[SET][r];
+        static_for<A_ITERS>([&](auto r_tag) {
+            constexpr int r = decltype(r_tag)::value;
+            *reinterpret_cast<v4f *>(&As[sa_off[r]]) = masked_slot(r_tag, ra[SET][r]);
+        });
+        static_for<B_ITERS>([&](auto r_tag) {
+            constexpr int r = decltype(r_tag)::value;
+            *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = masked_slot(std::integral_constant<int, A_ITERS + r>{}, rb[SET][r]);
+        });
     };
     // Moving a staged slab into LDS and requesting a later slab into the same registers is a list of
     // actions executed in order, one per slot: write the slot to LDS, reload it.
@@ -398,8 +410,8 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     auto do_action = [&](auto a_tag, int stage, auto set_tag, int64_t a_off, int64_t b_off) {
         constexpr int a = decltype(a_tag)::value, SET = decltype(set_tag)::value;
         float *As = lds + stage * T::STAGE_FLOATS;
-        if constexpr (a < A_ITERS) *reinterpret_cast<v4f *>(&As[sa_off[a]]) = ra[SET][a];
-        else *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[a - A_ITERS]]) = rb[SET][a - A_ITERS];
+        if constexpr (a < A_ITERS) *reinterpret_cast<v4f *>(&As[sa_off[a]]) = masked_slot(a_tag, ra[SET][a]);
+        else *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[a - A_ITERS]]) = masked_slot(a_tag, rb[SET][a - A_ITERS]);
         load_slot(a_tag, set_tag, a_off, b_off);
     };
 

@@ -14,13 +14,14 @@ hipStream_t current_stream();              // the stream set by gemm_f32_set_str
 int record_hip_error(hipError_t e);        // remembers e for gemm_f32_last_hip_error; returns GEMMF32_ELAUNCH
 
 // ---- variants -------------------------------------------------------------------------------
-enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, T128x64 = 6, T64x128 = 7, NUM_TILES = 8 };
+enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, T128x64 = 6, T64x128 = 7, T128x32 = 8, T32x128 = 9, NUM_TILES = 10 };
 
-struct TileShape { int bm, bn, bk; const char *name; };
+struct TileShape { int bm, bn, bk, waves_m, waves_n; const char *name; };
 const TileShape kShapes[NUM_TILES] = {
-    {256, 256, 16, "t256x256x16"}, {128, 128, 16, "t128x128x16"}, {64, 64, 32, "t64x64x32"},
-    {64, 64, 64, "t64x64x64"},     {256, 128, 16, "t256x128x16"}, {128, 256, 16, "t128x256x16"},
-    {128, 64, 32, "t128x64x32"},   {64, 128, 32, "t64x128x32"}};
+    {256, 256, 16, 2, 2, "t256x256x16"}, {128, 128, 16, 2, 2, "t128x128x16"}, {64, 64, 32, 2, 2, "t64x64x32"},
+    {64, 64, 64, 2, 2, "t64x64x64"},     {256, 128, 16, 2, 2, "t256x128x16"}, {128, 256, 16, 2, 2, "t128x256x16"},
+    {128, 64, 32, 2, 2, "t128x64x32"},   {64, 128, 32, 2, 2, "t64x128x32"},   {128, 32, 32, 4, 1, "t128x32x32"},
+    {32, 128, 32, 1, 4, "t32x128x32"}};
 
 template <int ID, int BMODE, int AMODE> struct Variant;
 template <int BMODE, int AMODE> struct Variant<T256, BMODE, AMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1, 1, AMODE> type; };
@@ -31,6 +32,9 @@ template <int BMODE, int AMODE> struct Variant<T256x128, BMODE, AMODE> { typedef
 template <int BMODE, int AMODE> struct Variant<T128x256, BMODE, AMODE> { typedef Tile<128, 256, 16, 2, 2, BMODE, 2, 1, AMODE> type; };
 template <int BMODE, int AMODE> struct Variant<T128x64, BMODE, AMODE> { typedef Tile<128, 64, 32, 2, 2, BMODE, 2, 2, AMODE> type; };
 template <int BMODE, int AMODE> struct Variant<T64x128, BMODE, AMODE> { typedef Tile<64, 128, 32, 2, 2, BMODE, 2, 2, AMODE> type; };
+// one 32 x 32 block per wave, four waves along the long side: for products with at most 32 columns (rows)
+template <int BMODE, int AMODE> struct Variant<T128x32, BMODE, AMODE> { typedef Tile<128, 32, 32, 4, 1, BMODE, 3, 2, AMODE> type; };
+template <int BMODE, int AMODE> struct Variant<T32x128, BMODE, AMODE> { typedef Tile<32, 128, 32, 1, 4, BMODE, 3, 2, AMODE> type; };
 
 template <class T> int launch(const KArgs &a)
 {
@@ -60,6 +64,8 @@ template <int BMODE, int AMODE> int launch_tile(int tile, const KArgs &a)
     case T128x256: return launch<typename Variant<T128x256, BMODE, AMODE>::type>(a);
     case T128x64: return launch<typename Variant<T128x64, BMODE, AMODE>::type>(a);
     case T64x128: return launch<typename Variant<T64x128, BMODE, AMODE>::type>(a);
+    case T128x32: return launch<typename Variant<T128x32, BMODE, AMODE>::type>(a);
+    case T32x128: return launch<typename Variant<T32x128, BMODE, AMODE>::type>(a);
     default: return launch<typename Variant<TB64, BMODE, AMODE>::type>(a);
     }
 }

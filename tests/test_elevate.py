@@ -283,7 +283,7 @@ def test_lowering_rejects_nests_no_kernel_can_run():
 
 SHAPES = [(4096, 4096, 4096), (1024, 1024, 1024), (1000, 1030, 999), (2048, 2048, 2048), (128, 128, 8192),
           (32, 32, 100000), (4095, 4097, 4099), (1, 1, 1), (64, 64, 64), (300, 70, 5), (1536, 1536, 1536),
-          (384, 384, 16384), (100, 5000, 33)]
+          (384, 384, 16384), (100, 5000, 33), (8192, 32, 8192), (16, 4096, 4096), (5000, 7, 300)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -300,7 +300,8 @@ def test_default_strategy_reproduces_the_dispatch_choice(M, N, K):
     else:
         assert s.split_k == 1
     assert s.tiles_m == -(-M // s.bm) and s.tiles_n == -(-N // s.bn)
-    assert (s.waves_m, s.waves_n, s.wave_m, s.wave_n) == (2, 2, s.bm // 2, s.bn // 2)
+    grid = {(128, 32): (4, 1), (32, 128): (1, 4)}.get((s.bm, s.bn), (2, 2))   # waves per workgroup
+    assert (s.waves_m, s.waves_n, s.wave_m, s.wave_n) == (*grid, s.bm // grid[0], s.bn // grid[1])
     assert s.k_range % s.bk == 0 and s.split_k * s.k_range >= K > (s.split_k - 1) * s.k_range
     # same text, same result
     assert b.elevate_default_strategy(M, N, K) == text

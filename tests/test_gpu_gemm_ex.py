@@ -301,3 +301,44 @@ def test_ex_batched_many_seeded_shapes_bit_exact():
             keep = np.ones(whole.shape[0], bool)
             keep[:: 1 + gap] = False
             assert (whole[keep] == 555.0).all(), case
+
+
+
+SKINNY = [
+    # (M, N, K, transA, transB): at most 32 columns, or at most 32 rows, of C
+    (700, 32, 2000, False, False), (700, 32, 2000, False, True), (1000, 17, 1537, False, False),
+    (1000, 1, 4099, False, True), (257, 31, 513, False, False), (4096, 8, 600, False, True),
+    (32, 900, 2000, False, True), (5, 1111, 3001, False, True), (32, 900, 2000, True, True),
+    (1, 300, 5000, True, True), (16, 257, 512, False, True), (8, 4100, 1030, True, True),
+    (2000, 24, 700, True, False), (3, 2000, 900, False, False),
+]
+
+
+@pytest.mark.parametrize("M,N,K,tA,tB", SKINNY)
+def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
+    """One dimension of C at most 32: the dispatch takes a tile that is 32 wide in that dimension
+    (four waves side by side along the other).  Rows and columns that do not fill the tile, K not a
+    multiple of the slab, K split or not, padded strides, alpha and beta: exact on integers, within
+    tolerance on U(-1,1)."""
+    if not tA and max(M, N) >= 700:
+        name = binding.variant_name(M, N, K, transB=tB)
+        assert name.startswith("t128x32x32" if N <= 32 else "t32x128x32"), name
+    for ints in (True, False):
+        gen = synth.small_ints if ints else synth.uniform
+        A = gen((M, K), 7000 + M, synth.TENSOR_A)
+        B = gen((K, N), 7000 + N, synth.TENSOR_B)
+        C0 = synth.small_ints((M, N), 7000, TENSOR_C, -9, 9)
+        for alpha, beta in ((1.0, 0.0), (2.0, -1.0)):
+            print(f"case M={M} N={N} K={K} tA={tA} tB={tB} ints={ints} alpha={alpha} beta={beta}", flush=True)
+            ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, alpha, beta, tA, tB, nthreads=NTHREADS)
+            dA, _ = padded_dev(stored(A, tA), 3)
+            dB, _ = padded_dev(stored(B, tB), 1)
+            dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
+            binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
+            whole = bufC.cpu().numpy()
+            got = whole[:, :N].astype(np.float64)
+            if ints:
+                assert np.array_equal(got, ref)
+            else:
+                assert np.abs(got - ref).max() <= tolerance(K, alpha, beta, 9.0)
+            assert np.isnan(whole[:, N:]).all(), "ldc padding was written"

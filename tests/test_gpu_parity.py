@@ -20,9 +20,10 @@ from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 NTHREADS = min(16, os.cpu_count() or 1)
 TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3", "t256x128": "4", "t128x256": "5", "t128x64": "6",
-         "t64x128": "7"}
+         "t64x128": "7", "t128x32": "8", "t32x128": "9"}
 TILE_DIMS = {"t256": (256, 256), "t128": (128, 128), "t64": (64, 64), "tb64": (64, 64), "t256x128": (256, 128),
-             "t128x256": (128, 256), "t128x64": (128, 64), "t64x128": (64, 128)}
+             "t128x256": (128, 256), "t128x64": (128, 64), "t64x128": (64, 128),
+             "t128x32": (128, 32), "t32x128": (32, 128)}
 
 
 def dev(x: np.ndarray):
