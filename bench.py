@@ -209,7 +209,8 @@ def protocol(torch, binding, synth):
 
     out = {"protocol": {}}
     plan = [("square1024", "plain"), ("ragged", "plain"), ("square4096", "plain"), ("transb2048", "plain"),
-            ("transb2048", "packed"), ("transb2048", "pack_only"), ("batched64", "plain")]
+            ("transb2048", "packed"), ("transb2048", "pack_only"), ("batched64", "plain"), ("skinny8192", "plain"),
+            ("wide8192", "plain")]
     for name, mode in plan:
         r = Runner(name, "packed" if mode == "pack_only" else mode)
         r.mode = mode
@@ -224,6 +225,10 @@ def protocol(torch, binding, synth):
         if name == "batched64":
             res["algorithmic_GBs"] = round(bytes_of(w) / (res["median_ms"] * 1e-3) / 1e9, 1)
             res["note"] = "warm: the same 201 MB every launch"
+        if name in ("skinny8192", "wide8192"):
+            res["algorithmic_GBs"] = round(bytes_of(w) / (res["median_ms"] * 1e-3) / 1e9, 1)
+            res["frac_hbm_peak"] = round(res["algorithmic_GBs"] / HBM_GBS, 4)
+            res["note"] = "270 MB of operands per launch, more than the memory-side cache holds"
         if name == "square1024" and mode == "plain":
             lat = []
             for _ in range(200):
@@ -363,7 +368,8 @@ def main() -> int:
     extra = {}
     if not args.no_extra:
         plan = [("square1024", "plain", 2000), ("ragged", "plain", 1000), ("transb2048", "plain", 300),
-                ("transb2048", "packed", 300), ("batched64", "plain", 1000)]
+                ("transb2048", "packed", 300), ("batched64", "plain", 1000), ("skinny8192", "plain", 300),
+                ("wide8192", "plain", 300)]
         for name, mode, steps in plan:
             if name == args.workload and mode == "plain":
                 continue
@@ -372,7 +378,7 @@ def main() -> int:
             key = name + ("_packed" if mode == "packed" else "")
             extra[key] = {"gflops": round(flops_of(r.w) / (wl * 1e-3) / 1e9, 1), "ms": round(wl, 5),
                           "frac_peak": round(flops_of(r.w) / (ev * 1e-3) / 1e12 / PEAK_TFLOPS, 4)}
-            if name == "batched64":
+            if name in ("batched64", "skinny8192", "wide8192"):
                 extra[key]["algorithmic_GBs"] = round(bytes_of(r.w) / (ev * 1e-3) / 1e9, 1)
             if mode == "packed":
                 r.mode = "pack_only"
@@ -434,6 +440,11 @@ def main() -> int:
                      "frac_of_peak_at_mfma_clock": round(achieved_tflops / peak_at_clock, 4)},
         "extra": extra,
     }
+    if flops_of(w) / bytes_of(w) < PEAK_TFLOPS * 1e3 / HBM_GBS:
+        # fewer flops per compulsory byte than the machine balance: the memory interface bounds it
+        gbs = bytes_of(w) / (ev_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
+                           "frac": round(gbs / HBM_GBS, 4), "traffic": traffic_bytes(args.workload)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(main_run)
     print(json.dumps(out))

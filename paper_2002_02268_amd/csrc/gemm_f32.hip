@@ -176,7 +176,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         if (forced_tile >= 0 && c.id != forced_tile) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
-        static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64};
+        static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
         for (int S : kSplits) {
             if (forced_split >= 1) S = forced_split;
             if (S > 1) {
@@ -360,17 +360,19 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
 // second pass of a K split: sums `split` dense M x N partial products from W into C
 int launch_splitk_reduce(const float *W, float *C, int M, int N, int64_t ldc, int split, float alpha, float beta)
 {
-    // lanes per group of 4 columns: enough to put about 64K threads on the chip, at most 16, at most S
+    // lanes per group of 4 columns: enough to put about 64K threads on the chip, at most 64, at most S
     const int64_t chunks = (int64_t)M * ((N + 3) / 4);
     int sl = 1;
-    while (sl < 16 && sl * 2 <= split && chunks * sl < 65536) sl *= 2;
+    while (sl < 64 && sl * 2 <= split && chunks * sl < 65536) sl *= 2;
     const dim3 grid((unsigned)cdiv(chunks * sl, 256)), block(256);
     switch (sl) {
     case 1: hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
     case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
     case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
     case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
-    default: hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    case 16: hipLaunchKernelGGL(splitk_reduce_kernel<16>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    case 32: hipLaunchKernelGGL(splitk_reduce_kernel<32>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
+    default: hipLaunchKernelGGL(splitk_reduce_kernel<64>, grid, block, 0, g_stream, W, C, M, N, ldc, split, alpha, beta); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e);

@@ -89,6 +89,9 @@ WORKLOADS = {
     "square4096": dict(batch=0, M=4096, N=4096, K=4096, dist="uniform", seed=2, transB=False),
     "transb2048": dict(batch=0, M=2048, N=2048, K=2048, dist="normal", seed=3, transB=True),
     "batched64": dict(batch=4096, M=64, N=64, K=64, dist="uniform", seed=4, transB=False),
+    # one short dimension: 16 flop per byte of the long operand, bound by streaming it (268 MB) once
+    "skinny8192": dict(batch=0, M=8192, N=32, K=8192, dist="uniform", seed=5, transB=False),
+    "wide8192": dict(batch=0, M=32, N=8192, K=8192, dist="uniform", seed=6, transB=True),
 }
 
 

@@ -307,6 +307,25 @@ def test_workload_square4096_sampled_rows_and_vector_check():
     _sampled_rows_and_freivalds(A, B, C, False, 4096, seed=2)
 
 
+@pytest.mark.parametrize("name", ["skinny8192", "wide8192"])
+def test_workload_one_short_dimension_full_oracle(name):
+    """8192 x 32 x 8192 and 32 x 8192 x 8192 (B stored N x K) as the benchmark launches them: every
+    element against the oracle, on U(-1,1) and exactly on integer-valued operands."""
+    w = synth.WORKLOADS[name]
+    assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]).startswith(
+        "t128x32x32" if w["N"] == 32 else "t32x128x32")
+    for dist in (None, "ints"):
+        A, B = synth.make_operands(name, dist=dist)
+        dC = torch.full((w["M"], w["N"]), float("nan"), device="cuda")
+        binding.gemm_f32(dev(A), dev(B), dC, transB=w["transB"])
+        C = dC.cpu().numpy()
+        ref = oracle.gemm_f32(A, B, transB=w["transB"], nthreads=NTHREADS)
+        if dist == "ints":
+            assert np.array_equal(C.astype(np.float64), ref)
+        else:
+            check_close(C, ref, w["K"])
+
+
 def test_workload_square4096_integer_bit_exact_vs_library_int_product():
     """Whole 4096^2 output, exact: integer-valued operands against an int64 product of a row
     sample by the oracle, and the +-1 vector check (exact in fp64) over everything."""
@@ -455,7 +474,8 @@ def test_batched64_uniform_values_and_two_products():
 def test_split_k_small_outputs_long_k(transB):
     """Outputs too small to occupy the chip: the dispatcher splits K; the second pass sums the
     partial products in a fixed order.  Ragged M, N and K, padded C with NaN guards."""
-    for idx, (M, N, K) in enumerate([(128, 128, 8192), (100, 70, 5003), (64, 64, 4096), (33, 257, 3000)]):
+    for idx, (M, N, K) in enumerate([(128, 128, 8192), (100, 70, 5003), (64, 64, 4096), (33, 257, 3000),
+                                      (1, 1, 1000003), (3, 5, 300001), (40, 2, 150000)]):
         name = binding.variant_name(M, N, K, transB=transB)
         assert "splitk" in name, name
         print(f"split-K {name} M={M} N={N} K={K} transB={transB}", flush=True)
