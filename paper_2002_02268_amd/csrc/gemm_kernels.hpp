@@ -290,8 +290,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
 
     // Staging registers: PF sets.  Set s holds a slab between its global load and its LDS write.
+    // One more set (index PF) carries slab 0 and is dead after the prologue.
     constexpr int PF = T::PF;
-    v4f ra[PF][A_ITERS], rb[PF][B_ITERS];
+    v4f ra[PF + 1][A_ITERS], rb[PF + 1][B_ITERS];
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B) of the slab that
@@ -520,13 +521,15 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     typedef std::integral_constant<int, 1> i1;
     if (nkf > 0) {
         const int last = nkf - 1;
-        load_slab(i0{}, 0);
-        store_slab(0, i0{});
-        // slab j (1 <= j <= PF) waits in register set j % PF
+        // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
+        // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
+        typedef std::integral_constant<int, PF> first_set;
+        load_slab(first_set{}, 0);
         static_for<PF>([&](auto j_tag) {
             constexpr int j = decltype(j_tag)::value + 1;
             load_slab(std::integral_constant<int, j % PF>{}, last < j ? last : j);
         });
+        store_slab(0, first_set{});
         lds_barrier();
         read_frag(f0, 0, 0);
         // the loop is unrolled PF times so that the register set of every slab is a compile-time choice
