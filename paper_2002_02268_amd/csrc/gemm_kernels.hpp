@@ -182,6 +182,26 @@ template <int N_MFMA, int N_MEM> __device__ __forceinline__ void spread_memory_b
 
 __device__ __forceinline__ v4f load4(const float *src) { return *reinterpret_cast<const v4f_g *>(src); }
 
+// A pointer that is the same in every lane, told to the compiler: it then lives in scalar registers.
+__device__ __forceinline__ const float *uniform_pointer(const float *ptr)
+{
+    const unsigned long long u = reinterpret_cast<unsigned long long>(ptr);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u), hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+    return reinterpret_cast<const float *>(((unsigned long long)hi << 32) | lo);
+}
+// 16 bytes per lane from `origin` (uniform) + `byte_offset` (per lane, 32 bits) with buffer addressing:
+// the origin travels in a scalar descriptor, so moving it from slab to slab is scalar arithmetic and
+// the request needs no vector instruction to form its address.  (Between two matrix instructions of a
+// wave a vector ALU instruction costs the matrix pipe 14 cycles or more and a load through a 64-bit
+// per-lane address about 36; scalar instructions, LDS instructions and buffer loads cost next to nothing.)
+// The range check of the descriptor is opened to the full 4 GB window; callers keep offsets below it.
+__device__ __forceinline__ v4f buffer_load4(const float *origin, unsigned byte_offset)
+{
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(origin), 0, 0xFFFFFFFF, 0x00020000 /* 32-bit data */);
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 0));
+}
+
 // One BM x BN tile.  EDGE = 0: every access is in range.  EDGE = 1: the tile crosses the M
 // boundary (or, for B stored N x K / packed, the N boundary): whole 16-byte chunks are either in
 // range or not.  EDGE = 2 (B stored K x N only): the tile crosses the N boundary, chunks of a
@@ -191,11 +211,14 @@ __device__ __forceinline__ v4f load4(const float *src) { return *reinterpret_cas
 // dimension: its origin is moved back so that it ends at the boundary, every load is in range as
 // for EDGE = 0, and only the rows and columns the tile owns are stored (the others belong to its
 // neighbour, which computes the same values).
+// EDGE = 0 and 3 address the operands through buffer descriptors with 32-bit offsets from the tile's
+// origin (tile_offsets_fit_32 must hold; the masked modes 1 and 2 work for any leading dimension).
 template <class T, int EDGE_MODE>
 __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
 {
     constexpr bool SHIFTED = (EDGE_MODE == 3);
     constexpr int EDGE = SHIFTED ? 0 : EDGE_MODE;            // how the loads treat the boundaries
+    constexpr bool BUF = (EDGE == 0);                        // every access in range: buffer addressing
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
     constexpr int MB = T::MB, NB = T::NB, SA = T::SA, SB = T::SB;
     constexpr int NTHR = T::THREADS;
@@ -226,7 +249,8 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int l32 = lane & 31, half = lane >> 5;
     const int wm0 = (wave / T::WGN) * T::WM, wn0 = (wave % T::WGN) * T::WN;
 
-    // ---- per-thread load slots: global pointer (at slab 0), LDS offset, edge predicates ----
+    // ---- per-thread load slots: global pointer (running: the next slab to request), LDS offset,
+    // edge predicates ----
     const float *pa[A_ITERS];
     const float *pb[B_ITERS];
     int sa_off[A_ITERS], sb_off[B_ITERS];
@@ -288,6 +312,23 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         }
     }
     const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
+    // BUF: the slots as 32-bit byte offsets from the tile's origin in each operand.  The origins are
+    // uniform and, like the pointers of the other modes, stand at the next slab to request.
+    unsigned va[A_ITERS], vb[B_ITERS];
+    const float *org_a = nullptr, *org_b = nullptr;
+    if constexpr (BUF) {
+        org_a = uniform_pointer(A + (A_KMAJOR ? (int64_t)m0 * p.lda : (int64_t)m0));
+        if constexpr (T::BMODE == B_NT) org_b = uniform_pointer(B + (int64_t)n0 * p.ldb);
+        else if constexpr (T::BMODE == B_NN) org_b = uniform_pointer(B + n0);
+        else org_b = uniform_pointer(B + (int64_t)(n0 / kPanel) * p.k_panel * kPanel + (n0 % kPanel));
+#pragma unroll
+        for (int r = 0; r < A_ITERS; ++r) va[r] = (unsigned)((pa[r] - org_a) * 4);
+#pragma unroll
+        for (int r = 0; r < B_ITERS; ++r) vb[r] = (unsigned)((pb[r] - org_b) * 4);
+    }
+    // where slot r stands now, as a pointer (for the ragged last slab)
+    auto a_slot_ptr = [&](int r) { return BUF ? org_a + (va[r] >> 2) : pa[r]; };
+    auto b_slot_ptr = [&](int r) { return BUF ? org_b + (vb[r] >> 2) : pb[r]; };
 
     // Staging registers: PF sets.  Set s holds a slab between its global load and its LDS write.
     // One more set (index PF) carries slab 0 and is dead after the prologue.
@@ -295,32 +336,45 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     v4f ra[PF + 1][A_ITERS], rb[PF + 1][B_ITERS];
     const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B) of the slab that
-    // starts a_off / b_off elements after slab 0; the slab is in range along k.  Out-of-range rows and
+    // global -> registers for one load slot (slots 0..A_ITERS-1 are A, the rest B) of the slab its
+    // pointer stands at (a whole slab, in range along k); the pointer then moves on by a_adv / b_adv
+    // (one slab, or nothing once it stands at the last whole slab: later requests repeat that slab
+    // and are never used).  The pointers live in registers of their own for the whole loop: an
+    // address computed into a temporary per request ties the request to whatever else the
+    // register allocator keeps in that temporary (fragments), and the in-order wave then waits on
+    // chains of false dependencies.  Out-of-range rows and
     // columns come from a clamped address; they are zeroed when the slot is written to LDS
     // (masked_slot), not here, so that nothing has to wait for the load before then.
-    auto load_slot = [&](auto slot_tag, auto set_tag, int64_t a_off, int64_t b_off) {
+    auto load_slot = [&](auto slot_tag, auto set_tag, int64_t a_adv, int64_t b_adv) {
         constexpr int S = decltype(slot_tag)::value, SET = decltype(set_tag)::value;
         if constexpr (S < A_ITERS) {
             constexpr int r = S;
             v4f v;
-            if constexpr (A_ELEMENTWISE) {
+            if constexpr (BUF) {
+                v = buffer_load4(org_a, va[r]);
+            } else if constexpr (A_ELEMENTWISE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (pa[r] + a_off)[a_d[r][e]];
+                for (int e = 0; e < 4; ++e) v[e] = pa[r][a_d[r][e]];
             } else {
-                v = load4(pa[r] + a_off);
+                v = load4(pa[r]);
             }
             ra[SET][r] = v;
+            if constexpr (!BUF) pa[r] += a_adv;
         } else {
             constexpr int r = S - A_ITERS;
             v4f v;
-            if constexpr (B_ELEMENTWISE) {
+            if constexpr (BUF) {
+                v = buffer_load4(org_b, vb[r]);
+            } else if constexpr (B_ELEMENTWISE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (pb[r] + b_off)[b_d[r][e]];
+                for (int e = 0; e < 4; ++e) v[e] = pb[r][b_d[r][e]];
             } else {
-                v = load4(pb[r] + b_off);
+                v = load4(pb[r]);
             }
             rb[SET][r] = v;
+            if constexpr (!BUF) pb[r] += b_adv;
+            // the origins move once per slab, after the last slot's request
+            if constexpr (BUF && r == B_ITERS - 1) { org_a += a_adv; org_b += b_adv; }
         }
     };
     auto masked_slot = [&](auto slot_tag, v4f v) {
@@ -343,13 +397,15 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         }
         return v;
     };
-    auto load_slab = [&](auto set_tag, int slab) {
-        const int64_t a_off = (int64_t)slab * a_step, b_off = (int64_t)slab * b_step;
-        static_for<A_ITERS + B_ITERS>([&](auto slot_tag) { load_slot(slot_tag, set_tag, a_off, b_off); });
+    // requests the slab the pointers stand at; `advance`: a later whole slab exists
+    auto load_slab = [&](auto set_tag, bool advance) {
+        const int64_t a_adv = advance ? a_step : 0, b_adv = advance ? b_step : 0;
+        static_for<A_ITERS + B_ITERS>([&](auto slot_tag) { load_slot(slot_tag, set_tag, a_adv, b_adv); });
     };
-    // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain
-    auto load_tail = [&](int slab, int kleft) {
-        const int64_t a_off = (int64_t)slab * a_step, b_off = (int64_t)slab * b_step;
+    // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain.  After
+    // the main loop the pointers stand at the last whole slab (at slab 0 if there is none).
+    auto load_tail = [&](bool after_whole_slabs, int kleft) {
+        const int64_t a_off = after_whole_slabs ? a_step : 0, b_off = after_whole_slabs ? b_step : 0;
 #pragma unroll
         for (int r = 0; r < A_ITERS; ++r) {
             const int c = ((tid + r * NTHR) % A_F4_ROW) * 4;
@@ -358,20 +414,20 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 if (a_ok[r]) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (c + e < kleft) v[e] = (pa[r] + a_off)[e];
+                        if (c + e < kleft) v[e] = (a_slot_ptr(r) + a_off)[e];
                 }
             } else {
                 if (a_slot_row(r) < kleft && a_ok[r]) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (a_col[r] + e < M) v[e] = (pa[r] + a_off)[e];   // pa[r] is unclamped when a_ok
+                        if (a_col[r] + e < M) v[e] = (a_slot_ptr(r) + a_off)[e];   // the slot's pointer is unclamped when a_ok
                 }
             }
             ra[0][r] = v;
         }
 #pragma unroll
         for (int r = 0; r < B_ITERS; ++r) {
-            const float *src = pb[r] + b_off;
+            const float *src = b_slot_ptr(r) + b_off;
             v4f v = zero4;
             if constexpr (T::BMODE == B_NT) {
                 const int c = ((tid + r * NTHR) % B_F4_ROW) * 4;
@@ -408,12 +464,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // Moving a staged slab into LDS and requesting a later slab into the same registers is a list of
     // actions executed in order, one per slot: write the slot to LDS, reload it.
     constexpr int N_ACTIONS = A_ITERS + B_ITERS;
-    auto do_action = [&](auto a_tag, int stage, auto set_tag, int64_t a_off, int64_t b_off) {
+    auto do_action = [&](auto a_tag, int stage, auto set_tag, int64_t a_adv, int64_t b_adv) {
         constexpr int a = decltype(a_tag)::value, SET = decltype(set_tag)::value;
         float *As = lds + stage * T::STAGE_FLOATS;
         if constexpr (a < A_ITERS) *reinterpret_cast<v4f *>(&As[sa_off[a]]) = masked_slot(a_tag, ra[SET][a]);
         else *reinterpret_cast<v4f *>(&As[T::A_TILE + sb_off[a - A_ITERS]]) = masked_slot(a_tag, rb[SET][a - A_ITERS]);
-        load_slot(a_tag, set_tag, a_off, b_off);
+        load_slot(a_tag, set_tag, a_adv, b_adv);
     };
 
     // ---- LDS -> fragments -> MFMA -----------------------------------------------------------
@@ -490,8 +546,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         constexpr bool MORE = decltype(more_tag)::value;
         const int cur = t & 1;
         typedef std::integral_constant<int, (PAR + 1) % PF> set_t;
-        const int req = (t + 1 + PF < nkf) ? (t + 1 + PF) : (nkf - 1);
-        const int64_t a_off = (int64_t)req * a_step, b_off = (int64_t)req * b_step;
+        // this slab requests slab min(t + 1 + PF, nkf - 1); the pointers move on if the next request is a later one
+        const bool advance = (t + 2 + PF < nkf);
+        const int64_t a_adv = advance ? a_step : 0, b_adv = advance ? b_step : 0;
         static_for<G>([&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
             Frag &now = (g & 1) ? f1 : f0;
@@ -510,7 +567,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             constexpr int MOVE_MEM = 2 * COUNT;    // one LDS write and one global load per action
             if constexpr (COUNT > 0) {
                 static_for<COUNT>([&](auto i_tag) {
-                    do_action(std::integral_constant<int, FIRST + decltype(i_tag)::value>{}, cur ^ 1, set_t{}, a_off, b_off);
+                    do_action(std::integral_constant<int, FIRST + decltype(i_tag)::value>{}, cur ^ 1, set_t{}, a_adv, b_adv);
                 });
             }
             mfma_group(now);
@@ -524,10 +581,10 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
         // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
         typedef std::integral_constant<int, PF> first_set;
-        load_slab(first_set{}, 0);
+        load_slab(first_set{}, 0 < last);                       // slab 0; the pointers move to slab min(1, last)
         static_for<PF>([&](auto j_tag) {
-            constexpr int j = decltype(j_tag)::value + 1;
-            load_slab(std::integral_constant<int, j % PF>{}, last < j ? last : j);
+            constexpr int j = decltype(j_tag)::value + 1;       // slab min(j, last); then on to min(j + 1, last)
+            load_slab(std::integral_constant<int, j % PF>{}, j < last);
         });
         store_slab(0, first_set{});
         lds_barrier();
@@ -549,7 +606,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     }
     // ---- ragged last slab (K % BK columns), not pipelined -------------------------------------
     if (kleft > 0) {
-        load_tail(nkf, kleft);
+        load_tail(nkf > 0, kleft);
         __syncthreads();                           // everyone is done reading both buffers
         store_slab(0, i0{});
         __syncthreads();
@@ -646,11 +703,18 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
     }
     const bool m_edge = (tm + 1) * T::BM > p.M, n_edge = (tn + 1) * T::BN > p.N;
+    // the in-range paths address a tile with 32-bit byte offsets from its origin
+    constexpr int64_t kSpanLimit = (1LL << 30) - 64;                       // elements: 4 GB less a margin
+    const int64_t a_span = (T::AMODE == A_MK) ? (int64_t)(T::BM - 1) * q.lda + T::BK : (int64_t)(T::BK - 1) * q.lda + T::BM;
+    const int64_t b_span = (T::BMODE == B_NT)   ? (int64_t)(T::BN - 1) * q.ldb + T::BK
+                           : (T::BMODE == B_NN) ? (int64_t)(T::BK - 1) * q.ldb + T::BN
+                                                : ((int64_t)((T::BN + kPanel - 1) / kPanel) * q.k_panel + T::BK) * kPanel;
+    const bool offsets_fit_32 = a_span < kSpanLimit && b_span < kSpanLimit;
     // an edge tile can be moved back inside the matrix unless the matrix is shorter than a tile
     // (packed B: columns come in whole panels, so only rows move)
     const bool can_shift = (!m_edge || p.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && p.N >= T::BN));
-    if (!m_edge && !n_edge) gemm_tile<T, 0>(q, lds, batch, tm, tn);
-    else if (can_shift) gemm_tile<T, 3>(q, lds, batch, tm, tn);
+    if (!m_edge && !n_edge && offsets_fit_32) gemm_tile<T, 0>(q, lds, batch, tm, tn);
+    else if (can_shift && (m_edge || n_edge) && offsets_fit_32) gemm_tile<T, 3>(q, lds, batch, tm, tn);
     else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
     else gemm_tile<T, 1>(q, lds, batch, tm, tn);
 }
