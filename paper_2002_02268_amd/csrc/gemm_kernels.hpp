@@ -260,11 +260,16 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     bool b_ok[B_ITERS];         // NT: row of B in range; packed: chunk present; NN: first column in range
     int b_col[B_ITERS];         // NN / packed: first global column of the chunk
     int b_d[B_ITERS][4];        // NN, EDGE 2: clamped offsets of the four elements from pb[r]
+    // slot r of a thread lies a fixed number of rows below its slot 0: the LDS addresses of all slots
+    // are one register plus constants
+    static_assert(NTHR % A_F4_ROW == 0 && NTHR % B_F4_ROW == 0, "slots of a thread share their column");
+    const int sa_base = (tid / A_F4_ROW) * SA + (tid % A_F4_ROW) * 4;
+    const int sb_base = (tid / B_F4_ROW) * SB + (tid % B_F4_ROW) * 4;
 #pragma unroll
     for (int r = 0; r < A_ITERS; ++r) {
         const int f = tid + r * NTHR;
         const int row = f / A_F4_ROW, c = (f % A_F4_ROW) * 4;
-        sa_off[r] = row * SA + c;
+        sa_off[r] = sa_base + r * (NTHR / A_F4_ROW) * SA;
         if constexpr (A_KMAJOR) {
             a_ok[r] = (m0 + row < M);
             a_col[r] = 0;
@@ -289,7 +294,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     for (int r = 0; r < B_ITERS; ++r) {
         const int f = tid + r * NTHR;
         const int row = b_slot_row(r), c = (f % B_F4_ROW) * 4;
-        sb_off[r] = row * SB + c;
+        sb_off[r] = sb_base + r * (NTHR / B_F4_ROW) * SB;
         if constexpr (T::BMODE == B_NT) {
             b_ok[r] = (n0 + row < N);
             b_col[r] = 0;
