@@ -112,10 +112,10 @@ struct Choice { int tile; int split; };
 // expressed as extra columns of K.
 struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
 const VariantModel kCandidates[] = {
-    {T256, 0.95, 0.95, 100, 100}, {T256x128, 0.935, 0.935, 100, 100}, {T128x256, 0.935, 0.935, 100, 100},
-    {T128, 0.92, 0.93, 100, 100}, {T128x64, 0.90, 0.90, 154, 100},    {T64x128, 0.87, 0.875, 130, 100},
-    {TB64, 0.79, 0.83, 200, 150}, {T64, 0.79, 0.80, 190, 120},
-    {T128x32, 0.70, 0.70, 150, 120}, {T32x128, 0.70, 0.70, 150, 120}};
+    {T256, 0.975, 0.975, 70, 70},     {T256x128, 0.965, 0.965, 96, 45}, {T128x256, 0.965, 0.965, 96, 45},
+    {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
+    {TB64, 0.93, 0.93, 515, 98},      {T64, 0.916, 0.916, 392, 40},
+    {T128x32, 0.80, 0.80, 400, 120},  {T32x128, 0.80, 0.80, 400, 120}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -187,6 +187,9 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
             const int64_t wgs = tiles * S;
             double cost = (double)cdiv(wgs, 256) * tile_us(c, sh.bm, sh.bn, k_range, wgs > 256);
+            // what a launch pays once (start-up, first loads, last stores) is part of the single-round
+            // overhead; with several rounds it is still paid once, on top of the per-round overheads
+            if (wgs > 256) cost += 2.0 * sh.bm * sh.bn * (c.overhead_single - c.overhead_multi) / (kCuFlopsPerUs * c.single);
             // a matrix shorter than the tile cannot move its edge tiles inside: every tile then runs
             // the masked loads, which cost about a quarter more
             if (M < sh.bm || N < sh.bn) cost *= 1.25;
@@ -194,7 +197,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             // bounds products with one short dimension
             const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / 5.2e6;
             if (cost < hbm_us) cost = hbm_us;
-            if (S > 1) cost += 5.0 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
+            if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
             if (forced_split >= 1) break;
