@@ -535,7 +535,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // Issue order inside a slab is pinned with scheduling groups: the LDS reads, LDS writes and
     // global loads are spread one at a time between MFMAs instead of being issued in a burst
     // (a burst from all waves at once fills the LDS queue and stalls MFMA issue behind it).
-    const int nkf = K / BK;
+    const int nkf = __builtin_amdgcn_readfirstlane(K / BK);   // uniform; kept in a scalar register (see gemm_kernel)
     const int kleft = K - nkf * BK;
     Frag f0, f1;
     constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
@@ -707,6 +707,12 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         batch = logical / p.tiles_per_batch;
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
     }
+    // The tile's coordinates are the same in every lane; said explicitly, because they come out of
+    // integer divisions (done in the vector unit), and everything derived from them -- origins,
+    // slab counts, buffer descriptors -- has to stay in scalar registers.
+    batch = __builtin_amdgcn_readfirstlane(batch);
+    tm = __builtin_amdgcn_readfirstlane(tm);
+    tn = __builtin_amdgcn_readfirstlane(tn);
     const bool m_edge = (tm + 1) * T::BM > p.M, n_edge = (tn + 1) * T::BN > p.N;
     // the in-range paths address a tile with 32-bit byte offsets from its origin
     constexpr int64_t kSpanLimit = (1LL << 30) - 64;                       // elements: 4 GB less a margin

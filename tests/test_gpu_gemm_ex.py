@@ -316,13 +316,11 @@ SKINNY = [
 
 @pytest.mark.parametrize("M,N,K,tA,tB", SKINNY)
 def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
-    """One dimension of C at most 32: the dispatch takes a tile that is 32 wide in that dimension
-    (four waves side by side along the other).  Rows and columns that do not fill the tile, K not a
+    """One dimension of C at most 32, through the dispatch's choice and through the tile that is 32
+    wide in that dimension (four waves side by side along the other).  Rows and columns that do not fill the tile, K not a
     multiple of the slab, K split or not, padded strides, alpha and beta: exact on integers, within
     tolerance on U(-1,1)."""
-    if not tA and max(M, N) >= 700:
-        name = binding.variant_name(M, N, K, transB=tB)
-        assert name.startswith("t128x32x32" if N <= 32 else "t32x128x32"), name
+    narrow = "8" if N <= 32 else "9"                       # tile 128x32x32 / 32x128x32
     for ints in (True, False):
         gen = synth.small_ints if ints else synth.uniform
         A = gen((M, K), 7000 + M, synth.TENSOR_A)
@@ -334,11 +332,18 @@ def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
             dA, _ = padded_dev(stored(A, tA), 3)
             dB, _ = padded_dev(stored(B, tB), 1)
             dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
-            binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
-            whole = bufC.cpu().numpy()
-            got = whole[:, :N].astype(np.float64)
-            if ints:
-                assert np.array_equal(got, ref)
-            else:
-                assert np.abs(got - ref).max() <= tolerance(K, alpha, beta, 9.0)
-            assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+            for forced in (None, narrow):                  # the dispatch's own choice, then the narrow tile
+                if forced is not None:
+                    os.environ["GEMMF32_FORCE_TILE"] = forced
+                    dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
+                try:
+                    binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
+                finally:
+                    os.environ.pop("GEMMF32_FORCE_TILE", None)
+                whole = bufC.cpu().numpy()
+                got = whole[:, :N].astype(np.float64)
+                if ints:
+                    assert np.array_equal(got, ref)
+                else:
+                    assert np.abs(got - ref).max() <= tolerance(K, alpha, beta, 9.0)
+                assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
