@@ -7,6 +7,7 @@
 #include "dispatch.hpp"
 #include "gemm_launch.hpp"
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -174,6 +175,9 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
     double best_cost = -1;
     for (const auto &c : kCandidates) {
         if (forced_tile >= 0 && c.id != forced_tile) continue;
+        // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
+        // are for outputs that are no wider, where the others would compute padding
+        if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32))) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
@@ -195,7 +199,10 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
             if (M < sh.bm || N < sh.bn) cost *= 1.25;
             // both operands cross the memory interface at least once, at 5.2 TB/s at best: what
             // bounds products with one short dimension
-            const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / 5.2e6;
+            // (a workgroup keeps about 40 KB in flight, which at the memory latency is 22 GB/s: fewer
+            // than 240 workgroups do not reach the full rate)
+            const double bytes_per_us = std::min(5.2e6, (double)wgs * 0.022e6);
+            const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / bytes_per_us;
             if (cost < hbm_us) cost = hbm_us;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;

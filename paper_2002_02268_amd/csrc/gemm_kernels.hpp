@@ -194,11 +194,12 @@ __device__ __forceinline__ const float *uniform_pointer(const float *ptr)
 // the request needs no vector instruction to form its address.  (Between two matrix instructions of a
 // wave a vector ALU instruction costs the matrix pipe 14 cycles or more and a load through a 64-bit
 // per-lane address about 36; scalar instructions, LDS instructions and buffer loads cost next to nothing.)
-// The range check of the descriptor is opened to the full 4 GB window; callers keep offsets below it.
-__device__ __forceinline__ v4f buffer_load4(const float *origin, unsigned byte_offset)
+// By default the range check of the descriptor is opened to the full 4 GB window; callers keep offsets below it.
+// `bytes`: the descriptor's range; a request at or beyond it touches no memory and returns zeros.
+__device__ __forceinline__ v4f buffer_load4(const float *origin, unsigned byte_offset, unsigned bytes = 0xFFFFFFFFu)
 {
     const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(origin), 0, 0xFFFFFFFF, 0x00020000 /* 32-bit data */);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(origin), 0, (int)bytes, 0x00020000 /* 32-bit data */);
     return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 0));
 }
 
@@ -212,13 +213,18 @@ __device__ __forceinline__ v4f buffer_load4(const float *origin, unsigned byte_o
 // for EDGE = 0, and only the rows and columns the tile owns are stored (the others belong to its
 // neighbour, which computes the same values).
 // EDGE = 0 and 3 address the operands through buffer descriptors with 32-bit offsets from the tile's
-// origin (tile_offsets_fit_32 must hold; the masked modes 1 and 2 work for any leading dimension).
+// origin.  So does EDGE = 1 when A is stored M x K: rows past the end of a row-major operand lie past
+// its last byte, so a descriptor whose range ends there masks them in hardware (zeros, no memory
+// access, no select).  These need the tile's offsets to fit 32 bits; EDGE = 4 is EDGE = 1 with
+// per-lane 64-bit pointers and selects, for any leading dimension (as are EDGE = 2, and EDGE = 1
+// when A is stored K x M).
 template <class T, int EDGE_MODE>
 __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
 {
     constexpr bool SHIFTED = (EDGE_MODE == 3);
-    constexpr int EDGE = SHIFTED ? 0 : EDGE_MODE;            // how the loads treat the boundaries
-    constexpr bool BUF = (EDGE == 0);                        // every access in range: buffer addressing
+    constexpr int EDGE = SHIFTED ? 0 : (EDGE_MODE == 4 ? 1 : EDGE_MODE);   // how the loads treat the boundaries
+    constexpr bool RANGED = (EDGE_MODE == 1 && T::AMODE == A_MK);           // boundaries masked by the descriptors' ranges
+    constexpr bool BUF = (EDGE == 0) || RANGED;                            // buffer addressing
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
     constexpr int MB = T::MB, NB = T::NB, SA = T::SA, SB = T::SB;
     constexpr int NTHR = T::THREADS;
@@ -319,18 +325,44 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int64_t b_step = (T::BMODE == B_NT) ? BK : (T::BMODE == B_NN ? (int64_t)BK * p.ldb : (int64_t)BK * kPanel);
     // BUF: the slots as 32-bit byte offsets from the tile's origin in each operand.  The origins are
     // uniform and, like the pointers of the other modes, stand at the next slab to request.
+    // RANGED: end_a / end_b are one past the last element of the operand that this tile's K range may
+    // read (last row, last column of the range); rows past the end start at or beyond them.
     unsigned va[A_ITERS], vb[B_ITERS];
-    const float *org_a = nullptr, *org_b = nullptr;
+    const float *org_a = nullptr, *org_b = nullptr, *end_a = nullptr, *end_b = nullptr;
     if constexpr (BUF) {
         org_a = uniform_pointer(A + (A_KMAJOR ? (int64_t)m0 * p.lda : (int64_t)m0));
-        if constexpr (T::BMODE == B_NT) org_b = uniform_pointer(B + (int64_t)n0 * p.ldb);
-        else if constexpr (T::BMODE == B_NN) org_b = uniform_pointer(B + n0);
-        else org_b = uniform_pointer(B + (int64_t)(n0 / kPanel) * p.k_panel * kPanel + (n0 % kPanel));
+        const int64_t b_origin = (T::BMODE == B_NT)   ? (int64_t)n0 * p.ldb
+                                 : (T::BMODE == B_NN) ? (int64_t)n0
+                                                      : (int64_t)(n0 / kPanel) * p.k_panel * kPanel + (n0 % kPanel);
+        org_b = uniform_pointer(B + b_origin);
 #pragma unroll
-        for (int r = 0; r < A_ITERS; ++r) va[r] = (unsigned)((pa[r] - org_a) * 4);
+        for (int r = 0; r < A_ITERS; ++r) {
+            const int f = tid + r * NTHR;
+            va[r] = (unsigned)(((int64_t)(f / A_F4_ROW) * p.lda + (f % A_F4_ROW) * 4) * 4);
+        }
 #pragma unroll
-        for (int r = 0; r < B_ITERS; ++r) vb[r] = (unsigned)((pb[r] - org_b) * 4);
+        for (int r = 0; r < B_ITERS; ++r) {
+            const int f = tid + r * NTHR;
+            const int row = f / B_F4_ROW, c = (f % B_F4_ROW) * 4;
+            if constexpr (T::BMODE == B_PACKED) {
+                const int gj = n0 + c;
+                vb[r] = (unsigned)((((int64_t)(gj / kPanel) * p.k_panel + row) * kPanel + (gj % kPanel) - b_origin) * 4);
+            } else {
+                vb[r] = (unsigned)(((int64_t)row * p.ldb + c) * 4);
+            }
+        }
+        if constexpr (RANGED) {
+            end_a = uniform_pointer(A + (int64_t)(M - 1) * p.lda + K);
+            if constexpr (T::BMODE == B_NT) end_b = uniform_pointer(B + (int64_t)(N - 1) * p.ldb + K);
+            else if constexpr (T::BMODE == B_PACKED)
+                end_b = uniform_pointer(B + ((int64_t)(p.n_padded / kPanel - 1) * p.k_panel + K) * kPanel);
+        }
     }
+    // bytes from an origin to the end of its operand, as a descriptor range (the window is 4 GB at most)
+    auto range_bytes = [&](const float *org, const float *end) {
+        const int64_t d = (end - org) * 4;
+        return (unsigned)(d > 0xFFFFFFFFLL ? 0xFFFFFFFFLL : d);
+    };
     // where slot r stands now, as a pointer (for the ragged last slab)
     auto a_slot_ptr = [&](int r) { return BUF ? org_a + (va[r] >> 2) : pa[r]; };
     auto b_slot_ptr = [&](int r) { return BUF ? org_b + (vb[r] >> 2) : pb[r]; };
@@ -355,7 +387,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         if constexpr (S < A_ITERS) {
             constexpr int r = S;
             v4f v;
-            if constexpr (BUF) {
+            if constexpr (RANGED) {
+                v = buffer_load4(org_a, va[r], range_bytes(org_a, end_a));
+            } else if constexpr (BUF) {
                 v = buffer_load4(org_a, va[r]);
             } else if constexpr (A_ELEMENTWISE) {
 #pragma unroll
@@ -368,7 +402,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         } else {
             constexpr int r = S - A_ITERS;
             v4f v;
-            if constexpr (BUF) {
+            if constexpr (RANGED && T::BMODE != B_NN) {
+                v = buffer_load4(org_b, vb[r], range_bytes(org_b, end_b));
+            } else if constexpr (BUF) {
                 v = buffer_load4(org_b, vb[r]);
             } else if constexpr (B_ELEMENTWISE) {
 #pragma unroll
@@ -384,7 +420,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     };
     auto masked_slot = [&](auto slot_tag, v4f v) {
         constexpr int S = decltype(slot_tag)::value;
-        if constexpr (EDGE != 0) {
+        if constexpr (EDGE != 0 && !BUF) {
             if constexpr (S < A_ITERS) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -727,7 +763,8 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     if (!m_edge && !n_edge && offsets_fit_32) gemm_tile<T, 0>(q, lds, batch, tm, tn);
     else if (can_shift && (m_edge || n_edge) && offsets_fit_32) gemm_tile<T, 3>(q, lds, batch, tm, tn);
     else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
-    else gemm_tile<T, 1>(q, lds, batch, tm, tn);
+    else if (T::AMODE != A_MK || offsets_fit_32) gemm_tile<T, 1>(q, lds, batch, tm, tn);
+    else if constexpr (T::AMODE == A_MK) gemm_tile<T, 4>(q, lds, batch, tm, tn);
 }
 
 // Sums the K ranges of the split tail tiles in ascending k and stores them into C.
