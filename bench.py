@@ -26,10 +26,10 @@ HBM_GBS = 8000.0
 # of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
 # one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "21d5ab4dcb006b29a6d8490e232c25e878054aad582c469ce82f5124b5cc60be",
-    "square4096": {"fetch_kib": 196787.5, "write_kib": 65792.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "square1024": {"fetch_kib": 14400.1, "write_kib": 4096.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "batched64": {"fetch_kib": 65569.1, "write_kib": 65536.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
+    "sources_sha256": "1b1062d61c923329bb6664385926e3ca349e692d7958cc3781429a38d82b3dfe",
+    "square4096": {"fetch_kib": 196793.7, "write_kib": 65536.0, "copy_fetch_kib": 32818.2, "copy_write_kib": 65536.0},
+    "square1024": {"fetch_kib": 14398.8, "write_kib": 4096.0, "copy_fetch_kib": 32818.2, "copy_write_kib": 65536.0},
+    "batched64": {"fetch_kib": 65569.3, "write_kib": 65536.0, "copy_fetch_kib": 32818.2, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 
