@@ -94,9 +94,11 @@ struct Tile {
     static constexpr int MB = WM / 32, NB = WN / 32;
     static constexpr int G = BK / 8;                           // 8-column groups per slab
     static constexpr int SA = (AMODE == A_KM) ? BM : BK + 4;   // A in LDS: [BM][SA], or [BK][BM] when stored K x M
-    static constexpr int SB = (BMODE == B_NT) ? (BK + 4) : BN; // B in LDS: [BN][SB] (NT) or [BK][BN]
+    // B in LDS: [BN][SB] (NT) or [BK][SB] with SB >= BN; rows at least 64 floats apart keep the
+    // fragment reads (one float from each of several rows) within reach of one address register
+    static constexpr int SB = (BMODE == B_NT) ? (BK + 4) : (BN < 64 ? 64 : BN);
     static constexpr int A_TILE = (AMODE == A_KM) ? BK * BM : BM * SA;
-    static constexpr int B_TILE = (BMODE == B_NT) ? BN * SB : BK * BN;
+    static constexpr int B_TILE = (BMODE == B_NT) ? BN * SB : BK * SB;
     static constexpr int STAGE_FLOATS = A_TILE + B_TILE;
     static constexpr int LDS_BYTES = 2 * STAGE_FLOATS * 4;
     static constexpr int A_F4 = BM * BK / 4, A_ITERS = A_F4 / THREADS;
@@ -360,8 +362,11 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     }
     // bytes from an origin to the end of its operand, as a descriptor range (the window is 4 GB at most)
     auto range_bytes = [&](const float *org, const float *end) {
-        const int64_t d = (end - org) * 4;
-        return (unsigned)(d > 0xFFFFFFFFLL ? 0xFFFFFFFFLL : d);
+        const uint64_t d = (uint64_t)((end - org) * 4);                  // never negative
+        unsigned hi = (unsigned)(d >> 32);
+        asm volatile("" : "+s"(hi));      // keeps the test on the high word: a 32-bit scalar compare (there is no
+                                          // scalar ordered compare of 64-bit values, and a vector one costs the matrix pipe)
+        return hi != 0 ? 0xFFFFFFFFu : (unsigned)d;
     };
     // where slot r stands now, as a pointer (for the ragged last slab)
     auto a_slot_ptr = [&](int r) { return BUF ? org_a + (va[r] >> 2) : pa[r]; };
