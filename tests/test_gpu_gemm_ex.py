@@ -347,3 +347,47 @@ def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
                 else:
                     assert np.abs(got - ref).max() <= tolerance(K, alpha, beta, 9.0)
                 assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+
+
+def _strided_dev(X: np.ndarray, ld: int):
+    """X (rows x cols) on the device inside a buffer whose rows are ld floats apart; the gaps hold NaN."""
+    rows, cols = X.shape
+    buf = torch.full(((rows - 1) * ld + cols,), float("nan"), device="cuda")
+    view = torch.as_strided(buf, (rows, cols), (ld, 1))
+    view.copy_(torch.from_numpy(X).cuda())
+    return view, buf
+
+
+@pytest.mark.parametrize("tile", ["t256", "t64", "t128x32"])
+def test_leading_dimensions_beyond_32_bit_tile_offsets(force_tile, tile):
+    """Leading dimensions so large that the byte offsets inside one tile exceed 32 bits: the kernels
+    then take the per-lane 64-bit pointer path for every tile (interior, edge, ragged K).  A stored
+    M x K with lda = 2^30 / (BM - 1) + 1000, B stored N x K with a matching ldb, then A stored K x M."""
+    BM, BN = TILE_DIMS[tile]
+    M, N, K = BM + 44, 150, 40
+    wide_a = (1 << 30) // (BM - 1) + 1000
+    wide_b = (1 << 30) // (BN - 1) + 1000
+    A = synth.small_ints((M, K), 7300, synth.TENSOR_A)
+    B = synth.small_ints((K, N), 7300, synth.TENSOR_B)
+    ref = oracle.gemm_f32_ex(A, B, np.zeros((M, N), np.float32), 1.0, 0.0, False, False, nthreads=NTHREADS)
+    force_tile(tile)
+    # A (M x K) with a wide lda, B (K x N) tight
+    dA, keepA = _strided_dev(A, wide_a)
+    dC = torch.full((M, N), float("nan"), device="cuda")
+    print(f"case tile={tile} wide lda={wide_a} bytes={keepA.numel() * 4}", flush=True)
+    binding.gemm_f32_ex(dA, dev(B), dC, 1.0, 0.0, False, False)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+    # B stored N x K with a wide ldb
+    dBt, keepB = _strided_dev(np.ascontiguousarray(B.T), wide_b)
+    dC.fill_(float("nan"))
+    print(f"case tile={tile} wide ldb={wide_b} bytes={keepB.numel() * 4}", flush=True)
+    binding.gemm_f32_ex(dA, dBt, dC, 1.0, 0.0, False, True)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+    del dA, keepA
+    # A stored K x M with a wide lda (K rows): offsets (BK - 1) * lda exceed 32 bits
+    wide_k = (1 << 30) // 15 + 1000
+    dAt, keepAt = _strided_dev(np.ascontiguousarray(A.T), wide_k)
+    dC.fill_(float("nan"))
+    print(f"case tile={tile} A^T wide lda={wide_k} bytes={keepAt.numel() * 4}", flush=True)
+    binding.gemm_f32_ex(dAt, dBt, dC, 1.0, 0.0, True, True)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
