@@ -93,3 +93,22 @@ def test_traffic_figures_are_dropped_when_the_kernel_sources_change():
         assert bench.traffic_bytes("square4096") is None
     finally:
         bench.TRAFFIC["sources_sha256"] = saved
+
+
+def test_dispatch_choices_for_the_benchmark_workloads():
+    """The tile and split the cost model takes for the workloads the benchmark times (a host computation;
+    pinned so that a change of the model's constants shows up here and not only as a slower benchmark)."""
+    from paper_2002_02268_amd import synth
+    want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x64x32/nn/a16", "transb2048": "t128x128x16/nt/a16",
+            "ragged": "t64x64x32/nn/a4/tail16x8", "skinny8192": "t128x32x32/nn/a16/splitk4",
+            "wide8192": "t32x128x32/nt/a16/splitk4"}
+    for name, variant in want.items():
+        w = synth.WORKLOADS[name]
+        assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]) == variant, name
+    # wide outputs never take the 32-wide tiles; outputs no wider than 32 always do
+    for M, N, K in [(1024, 1024, 1024), (300, 300, 300), (128, 128, 8192), (2048, 64, 2048), (64, 4096, 512)]:
+        assert not binding.variant_name(M, N, K).startswith(("t128x32x32", "t32x128x32")), (M, N, K)
+    for M, N, K in [(4096, 32, 4096), (8192, 8, 8192), (3000, 17, 1000)]:
+        assert binding.variant_name(M, N, K).startswith("t128x32x32"), (M, N, K)
+    for M, N, K in [(32, 4096, 4096), (1, 8192, 8192), (16, 11008, 4096)]:
+        assert binding.variant_name(M, N, K, transB=True).startswith("t32x128x32"), (M, N, K)
