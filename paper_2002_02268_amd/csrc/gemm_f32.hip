@@ -115,7 +115,7 @@ struct VariantModel { int id; double single, multi, overhead_single, overhead_mu
 const VariantModel kCandidates[] = {
     {T256, 0.975, 0.975, 70, 70},     {T256x128, 0.965, 0.965, 96, 45}, {T128x256, 0.965, 0.965, 96, 45},
     {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
-    {TB64, 0.93, 0.93, 515, 98},      {T64, 0.916, 0.916, 392, 40},
+    {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
     {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120}};
 const VariantModel &variant_model(int tile)
 {
