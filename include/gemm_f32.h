@@ -164,7 +164,8 @@ void gemm_f32_shutdown(void);
 /*
  * Which kernel variant the dispatcher would run for a shape, as a string such as
  * "t256x256x16/nn/a16", "t64x64x64/nn/a16/splitk32" (K split into 32 ranges) or
- * "t64x64x64/nn/a4/tail16x8" (the 16 tiles of the last round split into 8 K ranges each); for
+ * "t64x64x64/nn/a4/tail16x8" (the 16 tiles of the last round split into 8 K ranges each) or
+ * "t64x64x32/nn/a4/quad16" (the 16 tiles of the last round computed as 32 x 32 blocks); for
  * diagnostics and benchmarks.  The pointers are only inspected for alignment and may be NULL for
  * "aligned".  The string lives in a per-thread buffer that the next call on the thread overwrites.
  *
@@ -173,6 +174,7 @@ void gemm_f32_shutdown(void);
  *                              128x64x32, 64x128x32, 128x32x32, 32x128x32
  *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
  *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
+ *   GEMMF32_NO_QUAD=1          split the last round along K only, never into 32 x 32 blocks
  * gemm_f32_scheduled (elevate.h) is the interface for choosing tile and split per call.
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,

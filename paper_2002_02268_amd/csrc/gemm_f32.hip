@@ -133,13 +133,16 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 // Split of the last, partly filled round: `tail` tiles cut into `pieces` K ranges of `piece_k` columns
 // each (pieces <= 1: no split).  benefit_us: modelled time saved against running the tail as a round
 // of whole tiles, the second pass already charged.
-struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; };
+// quad: instead, every tail tile is cut into its 32 x 32 blocks (`pieces` of them), each computed by a
+// whole workgroup whose waves share the slabs along k: a quarter of a tile's time per block, and no
+// second pass.  Better than K ranges when K is short (the second pass costs a fixed 10 us).
+struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; bool quad; };
 
 TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
 {
     const VariantModel &vm = variant_model(tile);
     const int bm = kShapes[tile].bm, bn = kShapes[tile].bn, bk = kShapes[tile].bk;
-    TailSplit t = {tiles % 256, 1, 0, 0.0};
+    TailSplit t = {tiles % 256, 1, 0, 0.0, false};
     if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || std::getenv("GEMMF32_NO_TAIL_SPLIT")) return t;
     const int64_t units = cdiv(K, bk);
     int64_t S = 256 / t.tail;
@@ -147,13 +150,31 @@ TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
     if (S > units) S = units;
     const int64_t units_per_piece = cdiv(units, S);
     S = cdiv(units, units_per_piece);                    // no empty pieces
-    if (S <= 1 || t.tail * S * bm * bn * 4 > kMaxWorkspaceBytes) return t;
-    const double t_full = tile_us(vm, bm, bn, (double)K, true), t_piece = tile_us(vm, bm, bn, (double)units_per_piece * bk, true);
-    const double second_pass = 8.0;                      // launch, and reading the pieces back
-    if (t_full - t_piece <= second_pass) return t;
-    t.pieces = S;
-    t.piece_k = units_per_piece * bk;
-    t.benefit_us = t_full - t_piece - second_pass;
+    const double t_full = tile_us(vm, bm, bn, (double)K, true);
+    // 32 x 32 blocks: measured, a round of them adds 5 us + 1.8 ns per column of K to the launch (they
+    // start on compute units whose whole tiles ended early); in proportion if there are more than 256
+    double quad_benefit = 0.0;
+    const int64_t subs = (int64_t)(bm / 32) * (bn / 32);
+    if (bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !std::getenv("GEMMF32_NO_QUAD")) {
+        const double t_block = 5.0 + 0.0018 * (double)K;
+        quad_benefit = t_full - std::max(1.0, (double)(t.tail * subs) / 256.0) * t_block;
+    }
+    double range_benefit = 0.0;
+    if (S > 1 && t.tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
+        // measured: the pieces and the second pass add 10 us and a quarter of a piece's own time (the
+        // pieces, too, start where whole tiles ended early)
+        const double t_piece = tile_us(vm, bm, bn, (double)units_per_piece * bk, true);
+        range_benefit = t_full - (10.0 + 0.25 * t_piece);
+    }
+    if (quad_benefit > 0.0 && quad_benefit >= range_benefit) {
+        t.pieces = subs;
+        t.benefit_us = quad_benefit;
+        t.quad = true;
+    } else if (range_benefit > 0.0) {
+        t.pieces = S;
+        t.piece_k = units_per_piece * bk;
+        t.benefit_us = range_benefit;
+    }
     return t;
 }
 
@@ -328,6 +349,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.tail_split = 1;
     a.tail_k = 0;
     a.tail_slots = nullptr;
+    a.quad = 0;
     a.alpha = alpha;
     a.beta = beta;
     pl.tail_tiles = 0;
@@ -341,6 +363,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
             a.tail_split = (int)ts.pieces;
             a.tail_k = (int)ts.piece_k;
             a.total_tiles = (int)(total - ts.tail + ts.tail * ts.pieces);
+            a.quad = ts.quad ? 1 : 0;
             pl.tail_tiles = (int)ts.tail;
         }
     }
@@ -393,7 +416,7 @@ int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
-    if (pl.split <= 1 && pl.tail_tiles > 0) {
+    if (pl.split <= 1 && pl.tail_tiles > 0 && pl.args.quad == 0) {
         const TileShape &sh = kShapes[pl.tile];
         KArgs a = pl.args;
         int rc = ensure_workspace((size_t)pl.tail_tiles * a.tail_split * sh.bm * sh.bn * sizeof(float));
@@ -627,7 +650,10 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
-    if (pl.tail_tiles > 0)
+    if (pl.tail_tiles > 0 && pl.args.quad != 0)
+        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/quad%d", kShapes[pl.tile].name,
+                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles);
+    else if (pl.tail_tiles > 0)
         std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/tail%dx%d", kShapes[pl.tile].name,
                       pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles, pl.args.tail_split);
     else if (pl.split > 1)

@@ -70,6 +70,10 @@ struct KArgs {
     // pieces go to dense BM x BN slots and tail_reduce_kernel sums them.  tail_split <= 1: off.
     int tail_first, tail_split, tail_k;
     float *tail_slots;
+    // Or (quad != 0; tiles of at most 128 x 64): each tail tile is cut into its 32 x 32 blocks
+    // (tail_split = their number) and a whole workgroup computes one block, its four waves sharing
+    // every slab along k and adding up through LDS: a quarter of the tile's time, no second pass.
+    int quad;
     // Epilogue: C = alpha * (A*B) + beta * C_old.  beta == 0: C_old is never read.  The paper's
     // product is alpha = 1, beta = 0.
     float alpha, beta;
@@ -83,16 +87,21 @@ template <> struct VecOf<4> { typedef v4f type; typedef v4f_g gtype; };
 template <int N> __device__ __forceinline__ float vget(const typename VecOf<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1, int PF_ = 1, int AMODE_ = A_MK>
+// WGK > 1: the waves of a workgroup also split every slab along k (wave w / (WGM*WGN) takes that
+// share of the slab's 8-column groups) and their accumulators are added through LDS at the end: a
+// 32 x 32 output block is then computed four times as fast as by one wave, with no second pass.
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int BMODE_, int OCC_ = 1, int PF_ = 1, int AMODE_ = A_MK,
+          int WGK_ = 1>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, WGK = WGK_;
     static constexpr int BMODE = BMODE_, OCC = OCC_, AMODE = AMODE_;
     static constexpr int PF = PF_;                             // slabs held in registers ahead of the LDS write
     static_assert(PF_ >= 1 && PF_ <= 4, "prefetch depth");
-    static constexpr int THREADS = 64 * WGM * WGN;
+    static constexpr int THREADS = 64 * WGM * WGN * WGK;
     static constexpr int WM = BM / WGM, WN = BN / WGN;
     static constexpr int MB = WM / 32, NB = WN / 32;
     static constexpr int G = BK / 8;                           // 8-column groups per slab
+    static constexpr int GQ = G / WGK;                         // of which one wave multiplies this many
     static constexpr int SA = (AMODE == A_KM) ? BM : BK + 4;   // A in LDS: [BM][SA], or [BK][BM] when stored K x M
     // B in LDS: [BN][SB] (NT) or [BK][SB] with SB >= BN; rows at least 64 floats apart keep the
     // fragment reads (one float from each of several rows) within reach of one address register
@@ -113,6 +122,9 @@ struct Tile {
     static_assert(AMODE == A_MK || BMODE != B_PACKED, "no packed B together with A stored K x M");
     static_assert(BMODE != B_PACKED || BN % kPanel == 0 || kPanel % BN == 0, "tile vs panel");
     static_assert(LDS_BYTES <= 160 * 1024, "fits the 160 KB of LDS per compute unit");
+    static_assert(G % WGK == 0 && GQ >= 2 && GQ % 2 == 0, "every wave multiplies an even number of groups of a slab");
+    static_assert(WGK == 1 || (MB == 1 && NB == 1 && WGM == 1 && WGN == 1), "k-split waves share one 32 x 32 block");
+    static_assert(WGK == 1 || WGK * 32 * 33 * 4 <= LDS_BYTES, "room for the final sum of the k-split accumulators");
 };
 
 // Maps the hardware workgroup id to a tile.  Workgroups are handed to the 8 XCDs round
@@ -255,7 +267,10 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int wm0 = (wave / T::WGN) * T::WM, wn0 = (wave % T::WGN) * T::WN;
+    const int kq = wave / (T::WGM * T::WGN);                   // which share of every slab's groups (0 unless WGK > 1)
+    const int wv = wave % (T::WGM * T::WGN);
+    const int wm0 = (wv / T::WGN) * T::WM, wn0 = (wv % T::WGN) * T::WN;
+    constexpr int GQ = T::GQ;
 
     // ---- per-thread load slots: global pointer (running: the next slab to request), LDS offset,
     // edge predicates ----
@@ -523,9 +538,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         afrag_t a[NAV];
         bfrag_t b[NBV];
     };
-    const int a_frag_off = A_KMAJOR ? ((wm0 + l32) * SA + 4 * half) : (4 * half * SA + wm0 + MB * l32);
-    const int b_frag_off = (T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + 4 * half)
-                                              : (T::A_TILE + 4 * half * SB + wn0 + NB * l32);
+    // (group g of this wave is group kq * GQ + g of the slab)
+    const int a_frag_off = (A_KMAJOR ? ((wm0 + l32) * SA + 4 * half) : (4 * half * SA + wm0 + MB * l32)) +
+                           8 * GQ * kq * (A_KMAJOR ? 1 : SA);
+    const int b_frag_off = ((T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + 4 * half)
+                                               : (T::A_TILE + 4 * half * SB + wn0 + NB * l32)) +
+                           8 * GQ * kq * (T::BMODE == B_NT ? 1 : SB);
     auto read_frag = [&](Frag &fr, int stage, int g) {
         const float *base = lds + stage * T::STAGE_FLOATS;
         if constexpr (A_KMAJOR) {
@@ -583,7 +601,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr int N_READ = NAV + NBV;              // LDS reads of one fragment set
     // The actions of a slab run in the groups that precede the barrier (all but the last one),
     // the same number in each, in order.
-    constexpr int MOVE_GROUPS = (G > 1) ? G - 1 : 1;
+    constexpr int MOVE_GROUPS = GQ - 1;
     // Slab t: multiply it out of LDS buffer t % 2 while
     // slab t+1 goes from register set (t+1) % PF into the other buffer and slab t+1+PF is requested
     // into the same registers (past the end: a harmless re-request of the last full slab).
@@ -595,12 +613,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         // this slab requests slab min(t + 1 + PF, nkf - 1); the pointers move on if the next request is a later one
         const bool advance = (t + 2 + PF < nkf);
         const int64_t a_adv = advance ? a_step : 0, b_adv = advance ? b_step : 0;
-        static_for<G>([&](auto g_tag) {
+        static_for<GQ>([&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
             Frag &now = (g & 1) ? f1 : f0;
             Frag &next = (g & 1) ? f0 : f1;
-            constexpr bool READS = (g + 1 < G) || MORE;
-            if constexpr (g + 1 < G) {
+            constexpr bool READS = (g + 1 < GQ) || MORE;
+            if constexpr (g + 1 < GQ) {
                 read_frag(next, cur, g + 1);
             } else if constexpr (MORE) {
                 lds_barrier();                 // slab t+1 is complete in the other buffer
@@ -657,8 +675,8 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         store_slab(0, i0{});
         __syncthreads();
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (8 * g < kleft) {
+        for (int g = 0; g < GQ; ++g) {
+            if (8 * (GQ * kq + g) < kleft) {
                 read_frag(f0, 0, g);
                 mfma_group(f0);
             }
@@ -670,6 +688,31 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     auto cols_ok = [&](int gj, int n) { return SHIFTED ? gj >= n_own : (EDGE == 0 || gj + n <= N); };
     const float alpha = p.alpha, beta = p.beta;
     const bool add_old = (beta != 0.f);                      // uniform over the grid
+    if constexpr (T::WGK > 1) {
+        // the waves hold partial sums of the same 32 x 32 block: through LDS (element (i, j) of wave w
+        // at red[w][i * 33 + j]), added in wave order, stored by all threads
+        __syncthreads();                                      // the slab buffers are free
+        float *red = lds;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            red[kq * (32 * 33) + (8 * (v / 4) + 4 * half + (v % 4)) * 33 + l32] = acc[0][0][v];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 32 * 32 / NTHR; ++t) {
+            const int e = tid + NTHR * t, i = e >> 5, j = e & 31;
+            const int gi = m0 + i, gj = n0 + j;
+            float sum = red[i * 33 + j];
+#pragma unroll
+            for (int w = 1; w < T::WGK; ++w) sum += red[w * (32 * 33) + i * 33 + j];
+            if (row_ok(gi) && cols_ok(gj, 1)) {
+                float *dst = C + (int64_t)gi * p.ldc + gj;
+                float r = alpha * sum;
+                if (add_old) r += beta * *dst;
+                *dst = r;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
@@ -719,6 +762,39 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     }
 }
 
+// One tile of shape T at tile coordinates (tm, tn): picks how its boundaries are treated.
+template <class T>
+__device__ __forceinline__ void run_tile(const KArgs &q, float *lds, int batch, int tm, int tn)
+{
+    // The tile's coordinates are the same in every lane; said explicitly, because they come out of
+    // integer divisions (done in the vector unit), and everything derived from them -- origins,
+    // slab counts, buffer descriptors -- has to stay in scalar registers.
+    batch = __builtin_amdgcn_readfirstlane(batch);
+    tm = __builtin_amdgcn_readfirstlane(tm);
+    tn = __builtin_amdgcn_readfirstlane(tn);
+    const bool m_edge = (tm + 1) * T::BM > q.M, n_edge = (tn + 1) * T::BN > q.N;
+    // the in-range paths address a tile with 32-bit byte offsets from its origin
+    constexpr int64_t kSpanLimit = (1LL << 30) - 64;                       // elements: 4 GB less a margin
+    const int64_t a_span = (T::AMODE == A_MK) ? (int64_t)(T::BM - 1) * q.lda + T::BK : (int64_t)(T::BK - 1) * q.lda + T::BM;
+    const int64_t b_span = (T::BMODE == B_NT)   ? (int64_t)(T::BN - 1) * q.ldb + T::BK
+                           : (T::BMODE == B_NN) ? (int64_t)(T::BK - 1) * q.ldb + T::BN
+                                                : ((int64_t)((T::BN + kPanel - 1) / kPanel) * q.k_panel + T::BK) * kPanel;
+    const bool offsets_fit_32 = a_span < kSpanLimit && b_span < kSpanLimit;
+    // an edge tile can be moved back inside the matrix unless the matrix is shorter than a tile
+    // (packed B: columns come in whole panels, so only rows move)
+    const bool can_shift = (!m_edge || q.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && q.N >= T::BN));
+    if (!m_edge && !n_edge && offsets_fit_32) gemm_tile<T, 0>(q, lds, batch, tm, tn);
+    else if (can_shift && (m_edge || n_edge) && offsets_fit_32) gemm_tile<T, 3>(q, lds, batch, tm, tn);
+    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
+    else if (T::AMODE != A_MK || offsets_fit_32) gemm_tile<T, 1>(q, lds, batch, tm, tn);
+    else if constexpr (T::AMODE == A_MK) gemm_tile<T, 4>(q, lds, batch, tm, tn);
+}
+
+// The tile shape that computes one 32 x 32 block of a tail tile of shape T (see KArgs::quad); void
+// for shapes whose tails are split along K only.
+template <class T, bool = (T::BM * T::BN <= 128 * 64 && T::THREADS == 256 && T::WGK == 1)> struct QuadOf { typedef void type; };
+template <class T> struct QuadOf<T, true> { typedef Tile<32, 32, 64, 1, 1, T::BMODE, T::OCC, 2, T::AMODE, 4> type; };
+
 template <class T>
 __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 {
@@ -728,6 +804,20 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     // whole tiles first, then the pieces of the split tail; each kind is spread over the XCDs separately
     const bool is_piece = p.tail_split > 1 && (int)blockIdx.x >= p.tail_first;
     const int logical = is_piece ? 0 : xcd_contiguous_id(blockIdx.x, p.tail_split > 1 ? p.tail_first : p.total_tiles);
+    if constexpr (!std::is_void<typename QuadOf<T>::type>::value) {
+        if (is_piece && p.quad != 0) {
+            // one 32 x 32 block of one tile of the last round, by the whole workgroup
+            typedef typename QuadOf<T>::type QT;
+            constexpr int SUB_N = T::BN / 32;
+            const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.total_tiles - p.tail_first);
+            const int t = piece / p.tail_split, sub = piece - t * p.tail_split;
+            tile_coords(p, p.tail_first + t, tm, tn);
+            const int qm = tm * (T::BM / 32) + sub / SUB_N, qn = tn * SUB_N + sub % SUB_N;
+            if (qm * 32 >= p.M || qn * 32 >= p.N) return;      // a block of an edge tile that lies outside the matrix
+            run_tile<QT>(p, lds, 0, qm, qn);
+            return;
+        }
+    }
     if (is_piece) {
         // one K range of one tile of the last round -> its slot
         const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.total_tiles - p.tail_first);
@@ -748,28 +838,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         batch = logical / p.tiles_per_batch;
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
     }
-    // The tile's coordinates are the same in every lane; said explicitly, because they come out of
-    // integer divisions (done in the vector unit), and everything derived from them -- origins,
-    // slab counts, buffer descriptors -- has to stay in scalar registers.
-    batch = __builtin_amdgcn_readfirstlane(batch);
-    tm = __builtin_amdgcn_readfirstlane(tm);
-    tn = __builtin_amdgcn_readfirstlane(tn);
-    const bool m_edge = (tm + 1) * T::BM > p.M, n_edge = (tn + 1) * T::BN > p.N;
-    // the in-range paths address a tile with 32-bit byte offsets from its origin
-    constexpr int64_t kSpanLimit = (1LL << 30) - 64;                       // elements: 4 GB less a margin
-    const int64_t a_span = (T::AMODE == A_MK) ? (int64_t)(T::BM - 1) * q.lda + T::BK : (int64_t)(T::BK - 1) * q.lda + T::BM;
-    const int64_t b_span = (T::BMODE == B_NT)   ? (int64_t)(T::BN - 1) * q.ldb + T::BK
-                           : (T::BMODE == B_NN) ? (int64_t)(T::BK - 1) * q.ldb + T::BN
-                                                : ((int64_t)((T::BN + kPanel - 1) / kPanel) * q.k_panel + T::BK) * kPanel;
-    const bool offsets_fit_32 = a_span < kSpanLimit && b_span < kSpanLimit;
-    // an edge tile can be moved back inside the matrix unless the matrix is shorter than a tile
-    // (packed B: columns come in whole panels, so only rows move)
-    const bool can_shift = (!m_edge || p.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && p.N >= T::BN));
-    if (!m_edge && !n_edge && offsets_fit_32) gemm_tile<T, 0>(q, lds, batch, tm, tn);
-    else if (can_shift && (m_edge || n_edge) && offsets_fit_32) gemm_tile<T, 3>(q, lds, batch, tm, tn);
-    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
-    else if (T::AMODE != A_MK || offsets_fit_32) gemm_tile<T, 1>(q, lds, batch, tm, tn);
-    else if constexpr (T::AMODE == A_MK) gemm_tile<T, 4>(q, lds, batch, tm, tn);
+    run_tile<T>(q, lds, batch, tm, tn);
 }
 
 // Sums the K ranges of the split tail tiles in ascending k and stores them into C.

@@ -36,18 +36,26 @@ template <int BMODE, int AMODE> struct Variant<T64x128, BMODE, AMODE> { typedef 
 template <int BMODE, int AMODE> struct Variant<T128x32, BMODE, AMODE> { typedef Tile<128, 32, 32, 4, 1, BMODE, 3, 2, AMODE> type; };
 template <int BMODE, int AMODE> struct Variant<T32x128, BMODE, AMODE> { typedef Tile<32, 128, 32, 1, 4, BMODE, 3, 2, AMODE> type; };
 
+// LDS a launch of shape T may need: its own two slab buffers, or those of the tile shape that computes
+// the 32 x 32 blocks of its tail tiles
+template <class T, class Q = typename QuadOf<T>::type> struct LdsNeed {
+    static constexpr int value = T::LDS_BYTES > Q::LDS_BYTES ? T::LDS_BYTES : Q::LDS_BYTES;
+};
+template <class T> struct LdsNeed<T, void> { static constexpr int value = T::LDS_BYTES; };
+
 template <class T> int launch(const KArgs &a)
 {
     static bool attr_set = false;  // per instantiation; benign if set twice
     auto kern = gemm_kernel<T>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LdsNeed<T>::value);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
     // a product whose K fits one slab never touches a second LDS buffer
-    const int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
+    int lds_bytes = (a.K <= T::BK) ? T::LDS_BYTES / 2 : T::LDS_BYTES;
+    if (a.quad != 0) lds_bytes = LdsNeed<T>::value;
     hipLaunchKernelGGL(kern, dim3((unsigned)a.total_tiles), dim3(T::THREADS), lds_bytes, current_stream(), a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return record_hip_error(e);

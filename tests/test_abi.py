@@ -100,7 +100,7 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     pinned so that a change of the model's constants shows up here and not only as a slower benchmark)."""
     from paper_2002_02268_amd import synth
     want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x64x32/nn/a16", "transb2048": "t128x128x16/nt/a16",
-            "ragged": "t64x64x32/nn/a4/tail16x8", "skinny8192": "t128x32x32/nn/a16/splitk4",
+            "ragged": "t64x64x32/nn/a4/quad16", "skinny8192": "t128x32x32/nn/a16/splitk4",
             "wide8192": "t32x128x32/nt/a16/splitk4"}
     for name, variant in want.items():
         w = synth.WORKLOADS[name]

@@ -138,16 +138,22 @@ def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
     """Shapes that take the K-split path (small output, long K) and the split last round
     (272 tiles): the second pass applies alpha and beta; integer operands, exact."""
     for (M, N, K) in [(96, 80, 4000), (1000, 1030, 999)]:
-        name = binding.variant_name(M, N, K, transB=tB)
-        print(f"case tA={tA} tB={tB} M={M} N={N} K={K} variant={name}", flush=True)
-        assert ("splitk" in name) or ("tail" in name)
         A = synth.small_ints((M, K), 860, synth.TENSOR_A)
         B = synth.small_ints((K, N), 860, synth.TENSOR_B)
         C0 = synth.small_ints((M, N), 860, TENSOR_C, -9, 9)
         ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, -2.0, 3.0, tA, tB, nthreads=NTHREADS)
-        dC = dev(C0)
-        binding.gemm_f32_ex(dev(stored(A, tA)), dev(stored(B, tB)), dC, -2.0, 3.0, tA, tB)
-        assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+        for no_quad in (False, True):       # the last round as 32 x 32 blocks (scalars applied in the kernel), then as K ranges
+            if no_quad:
+                os.environ["GEMMF32_NO_QUAD"] = "1"
+            try:
+                name = binding.variant_name(M, N, K, transB=tB)
+                print(f"case tA={tA} tB={tB} M={M} N={N} K={K} variant={name}", flush=True)
+                assert ("splitk" in name) or ("tail" in name) or ("quad" in name and not no_quad)
+                dC = dev(C0)
+                binding.gemm_f32_ex(dev(stored(A, tA)), dev(stored(B, tB)), dC, -2.0, 3.0, tA, tB)
+            finally:
+                os.environ.pop("GEMMF32_NO_QUAD", None)
+            assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
 
 
 def test_ex_ragged_workload_transposed_a_within_tolerance():

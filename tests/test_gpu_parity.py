@@ -538,17 +538,30 @@ def test_shutdown_releases_workspace_and_library_stays_usable():
 
 # --------------------------------------------------------------------- split tail (uneven tile counts)
 
-@pytest.mark.parametrize("tile", ["t128", "t64", "tb64"])
+@pytest.mark.parametrize("tile,how", [("t128", "tail"), ("t64", "tail"), ("tb64", "tail"), ("t64", "quad"), ("tb64", "quad"),
+                                      ("t128x64", "quad"), ("t64x128", "quad")])
 @pytest.mark.parametrize("transB", [False, True])
-def test_split_tail_bit_exact(force_tile, tile, transB):
-    """More tiles than one round of 256, with a small remainder: the remainder's tiles are cut along K
-    and summed by a second pass.  Exact on integer operands; ragged edges, a K tail, padded C."""
+def test_split_tail_bit_exact(force_tile, tile, how, transB):
+    """More tiles than one round of 256, with a small remainder.  "tail": the remainder's tiles are cut
+    along K and summed by a second pass.  "quad": they are cut into 32 x 32 blocks, each computed by a
+    whole workgroup whose waves share the slabs along k and add up through LDS.  Exact on integer
+    operands; ragged edges (blocks of edge tiles that lie outside the matrix), a K tail, padded C."""
     force_tile(tile)
+    if how == "tail":
+        os.environ["GEMMF32_NO_QUAD"] = "1"
     shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
-              "tb64": [(1000, 1030, 999), (1100, 1100, 1100)]}[tile]
+              "tb64": [(1000, 1030, 999), (1100, 1100, 1100)], "t128x64": [(2100, 1090, 700), (2200, 1000, 333)],
+              "t64x128": [(1090, 2100, 700)]}[tile]
+    try:
+        _split_tail_cases(shapes, how, transB)
+    finally:
+        os.environ.pop("GEMMF32_NO_QUAD", None)
+
+
+def _split_tail_cases(shapes, how, transB):
     for idx, (M, N, K) in enumerate(shapes):
         name = binding.variant_name(M, N, K, transB=transB)
-        assert "/tail" in name, name
+        assert "/" + how in name, name
         print(f"split tail {name} M={M} N={N} K={K}", flush=True)
         A = synth.small_ints((M, K), 800 + idx, synth.TENSOR_A)
         B = synth.small_ints((N, K) if transB else (K, N), 800 + idx, synth.TENSOR_B)
@@ -561,8 +574,9 @@ def test_split_tail_bit_exact(force_tile, tile, transB):
 
 
 def test_split_tail_ragged_workload_parity_determinism_and_packed():
-    """The ragged workload (272 tiles of 64x64) takes this path."""
-    assert "/tail" in binding.variant_name(1000, 1030, 999)
+    """The ragged workload (272 tiles of 64x64) takes this path: 32 x 32 blocks by default, K ranges
+    when those are switched off, whole tiles when both are."""
+    assert "/quad16" in binding.variant_name(1000, 1030, 999)
     A, B = synth.make_operands("ragged")
     ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
     dA, dB = dev(A), dev(B)
@@ -578,9 +592,19 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
     dC = torch.full((1000, 1030), float("nan"), device="cuda")
     binding.gemm_f32_packed(dA, dBp, dC)
     check_close(dC.cpu().numpy(), ref, 999)
+    os.environ["GEMMF32_NO_QUAD"] = "1"
+    try:
+        assert "/tail16x8" in binding.variant_name(1000, 1030, 999)
+        dC.fill_(float("nan"))
+        binding.gemm_f32(dA, dB, dC)
+        check_close(dC.cpu().numpy(), ref, 999)
+    finally:
+        os.environ.pop("GEMMF32_NO_QUAD", None)
     os.environ["GEMMF32_NO_TAIL_SPLIT"] = "1"
     try:
-        assert "/tail" not in binding.variant_name(1000, 1030, 999)
+        name = binding.variant_name(1000, 1030, 999)
+        assert "/tail" not in name and "/quad" not in name
+        dC.fill_(float("nan"))
         binding.gemm_f32(dA, dB, dC)
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
