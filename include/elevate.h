@@ -73,6 +73,7 @@ typedef struct {
     int32_t split_k;              /* K ranges computed by separate workgroups (1: none) */
     int64_t tiles_m, tiles_n;     /* grid */
     int64_t k_range;              /* length of one K range, a multiple of bk */
+    int32_t waves_k;              /* waves of a workgroup that split every K slab between them (1: none) */
 } gemmf32_schedule;
 
 /*

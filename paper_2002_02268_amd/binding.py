@@ -289,7 +289,8 @@ class Schedule(ctypes.Structure):
     _fields_ = [("bm", ctypes.c_int32), ("bn", ctypes.c_int32), ("bk", ctypes.c_int32),
                 ("waves_m", ctypes.c_int32), ("waves_n", ctypes.c_int32),
                 ("wave_m", ctypes.c_int32), ("wave_n", ctypes.c_int32), ("split_k", ctypes.c_int32),
-                ("tiles_m", ctypes.c_int64), ("tiles_n", ctypes.c_int64), ("k_range", ctypes.c_int64)]
+                ("tiles_m", ctypes.c_int64), ("tiles_n", ctypes.c_int64), ("k_range", ctypes.c_int64),
+                ("waves_k", ctypes.c_int32)]
 
     def as_dict(self):
         return {name: int(getattr(self, name)) for name, _ in self._fields_}

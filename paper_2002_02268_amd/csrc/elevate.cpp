@@ -350,14 +350,16 @@ Strategy<TermP> interchange()
 }
 // Implementation choices for a sequential loop, the counterpart of rewriting map into mapPar /
 // mapSeqUnroll (Section 6.2).  Applicable only where the choice is valid: a wave-parallel loop runs
-// over rows or columns of C, never over the reduction; a slab loop is a loop over K.
+// over rows or columns of C, never over the reduction; a slab loop is a loop over K; "share" is a
+// loop over K whose iterations the waves of a workgroup take side by side (inside a slab; their
+// partial sums are added when the K range is done).
 Strategy<TermP> mark(const std::string &kind)
 {
     return rule("mark(" + kind + ")", [kind](const TermP &p) -> TermP {
         Loop l;
         if (!as_loop(p, l) || l.kind != "seq") return nullptr;
         if (kind == "wave" && l.axis == "K") return nullptr;
-        if (kind == "slab" && l.axis != "K") return nullptr;
+        if ((kind == "slab" || kind == "share") && l.axis != "K") return nullptr;
         return make_loop(l.axis, l.extent, kind, l.body);
     });
 }
@@ -545,7 +547,7 @@ Strategy<TermP> compile_strategy(const TermP &e, std::string &err)
     if (h == "mark") {
         if (e->args.size() != 1 || !is_atom(e->args[0])) { err = "mark takes a loop kind"; return S(); }
         const std::string &k = e->args[0]->head;
-        if (k != "grid" && k != "wave" && k != "unroll" && k != "slab") { err = "mark: the kind is grid, wave, unroll or slab"; return S(); }
+        if (k != "grid" && k != "wave" && k != "unroll" && k != "slab" && k != "share") { err = "mark: the kind is grid, wave, unroll, slab or share"; return S(); }
         return mark(k);
     }
     if (h == "separateDot") {
@@ -637,7 +639,13 @@ bool lower_nest(const TermP &nest, long long M, long long N, long long K, Lowere
         } else {
             seen_non_grid = true;
             block[ax] *= l.extent;
-            if (l.kind == "wave") {
+            if (l.kind == "share") {
+                // waves sharing the reduction: only inside the staged loop, where each takes part of a slab
+                if (!in_slab) { err = "a shared loop over the reduction outside the staged loop"; return false; }
+                if (wave[2] != 1) { err = "two shared loops"; return false; }
+                wave[2] = l.extent;
+                bk *= l.extent;
+            } else if (l.kind == "wave") {
                 if (seen_below_wave) { err = "a wave-parallel loop lies inside a sequential loop"; return false; }
                 if (ax == 2) { err = "a wave-parallel loop over the reduction"; return false; }
                 if (wave[ax] != 1) { err = "two wave-parallel loops over the same axis"; return false; }
@@ -672,7 +680,7 @@ bool lower_nest(const TermP &nest, long long M, long long N, long long K, Lowere
     out.tiles_m = grid[0]; out.tiles_n = grid[1]; out.split_k = grid[2];
     out.bm = block[0]; out.bn = block[1]; out.k_range = block[2];
     out.bk = bk;
-    out.waves_m = wave[0]; out.waves_n = wave[1];
+    out.waves_m = wave[0]; out.waves_n = wave[1]; out.waves_k = wave[2];
     out.wave_m = below_wave[0]; out.wave_n = below_wave[1];
     return true;
 }

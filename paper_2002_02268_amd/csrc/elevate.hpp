@@ -236,6 +236,7 @@ struct LoweredSchedule {
     long long bm, bn, k_range;               // per-workgroup block: rows, columns, length of its K range
     long long bk;                            // K extent staged through LDS per slab
     long long waves_m, waves_n;              // waves per workgroup along M and N
+    long long waves_k;                       // waves that split every K slab between them (1: none)
     long long wave_m, wave_n;                // rows / columns of C per wave (register block x MFMA block)
 };
 // Reads the kernel configuration off a scheduled nest; false (and err) if the nest is not a

@@ -88,9 +88,10 @@ std::string default_strategy(long long M, long long N, long long K, const gemmf3
     split_axis('N', 32, "unroll");
     split_axis('K', k_range, "grid");
     split_axis('K', c.bk, "slab");
+    if (c.waves_k > 1) split_axis('K', c.bk / c.waves_k, "kwave");     // the waves share every slab
     split_axis('K', 2, "step");
     // wanted order: grid loops, wave loops, slab, k steps, register block, the instruction's M N K
-    static const char *order[] = {"grid", "wave", "slab", "step", "unroll", "seq"};
+    static const char *order[] = {"grid", "wave", "slab", "kwave", "step", "unroll", "seq"};
     std::vector<size_t> perm;
     for (const char *role : order)
         for (char axis : {'M', 'N', 'K'})
@@ -106,7 +107,7 @@ std::string default_strategy(long long M, long long N, long long K, const gemmf3
     for (size_t i = 0; i < perm.size(); ++i) {
         const char *role = nest[perm[i]].kind;
         if (std::strcmp(role, "seq") != 0 && std::strcmp(role, "step") != 0)
-            emit("(bodyN " + std::to_string(i) + " (mark " + role + "))");
+            emit("(bodyN " + std::to_string(i) + " (mark " + (std::strcmp(role, "kwave") == 0 ? "share" : role) + "))");
     }
     emit("(topDown mfma)");
     return s + ")";
@@ -175,18 +176,18 @@ int elevate_schedule_gemm(int64_t M, int64_t N, int64_t K, const char *strategy,
         return ELEVATE_ELOWER;
     }
     const long long big = 2147483647LL;
-    if (ls.bm > big || ls.bn > big || ls.bk > big || ls.waves_m > big || ls.waves_n > big || ls.split_k > big) {
+    if (ls.bm > big || ls.bn > big || ls.bk > big || ls.waves_m > big || ls.waves_n > big || ls.waves_k > big || ls.split_k > big) {
         put(nest_buf, nest_cap, "block sizes out of range");
         return ELEVATE_ELOWER;
     }
     out->bm = (int32_t)ls.bm; out->bn = (int32_t)ls.bn; out->bk = (int32_t)ls.bk;
-    out->waves_m = (int32_t)ls.waves_m; out->waves_n = (int32_t)ls.waves_n;
+    out->waves_m = (int32_t)ls.waves_m; out->waves_n = (int32_t)ls.waves_n; out->waves_k = (int32_t)ls.waves_k;
     out->wave_m = (int32_t)(ls.wave_m > big ? big : ls.wave_m);
     out->wave_n = (int32_t)(ls.wave_n > big ? big : ls.wave_n);
     out->split_k = (int32_t)ls.split_k;
     out->tiles_m = ls.tiles_m; out->tiles_n = ls.tiles_n;
     out->k_range = ls.k_range;
-    const bool built = gemmf32_host::has_kernel(out->bm, out->bn, out->bk, out->waves_m, out->waves_n) &&
+    const bool built = gemmf32_host::has_kernel(out->bm, out->bn, out->bk, out->waves_m, out->waves_n, out->waves_k) &&
                        (int64_t)out->wave_m * out->waves_m == out->bm && (int64_t)out->wave_n * out->waves_n == out->bn;
     return built ? ELEVATE_OK : ELEVATE_ENOKERNEL;
 }
@@ -227,7 +228,7 @@ int gemm_f32_scheduled(const gemmf32_schedule *s, int64_t M, int64_t N, int64_t 
                        const float *B, int64_t ldb, float *C, int64_t ldc, int transB)
 {
     if (s == nullptr) return GEMMF32_ENULL;
-    if (!gemmf32_host::has_kernel(s->bm, s->bn, s->bk, s->waves_m, s->waves_n)) return GEMMF32_EINVAL;
+    if (!gemmf32_host::has_kernel(s->bm, s->bn, s->bk, s->waves_m, s->waves_n, s->waves_k)) return GEMMF32_EINVAL;
     if (s->split_k < 1) return GEMMF32_EINVAL;
     if (M > 0 && N > 0 && K > 0) {
         // the schedule must be one for this problem: its blocks cover it with no idle workgroup

@@ -116,7 +116,8 @@ const VariantModel kCandidates[] = {
     {T256, 0.975, 0.975, 70, 70},     {T256x128, 0.965, 0.965, 96, 45}, {T128x256, 0.965, 0.965, 96, 45},
     {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
     {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
-    {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120}};
+    {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120},
+    {TQ32, 0.60, 0.60, 400, 150}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -155,7 +156,7 @@ TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
     // start on compute units whose whole tiles ended early); in proportion if there are more than 256
     double quad_benefit = 0.0;
     const int64_t subs = (int64_t)(bm / 32) * (bn / 32);
-    if (bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !std::getenv("GEMMF32_NO_QUAD")) {
+    if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !std::getenv("GEMMF32_NO_QUAD")) {
         const double t_block = 5.0 + 0.0018 * (double)K;
         quad_benefit = t_full - std::max(1.0, (double)(t.tail * subs) / 256.0) * t_block;
     }
@@ -181,7 +182,7 @@ TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
 // set around one call by run_forced: tile and split given by the caller instead of the cost model
 thread_local int g_forced_tile = -1, g_forced_split = -1;
 
-Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
+Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B_NN, int amode = A_MK)
 {
     int forced_tile = g_forced_tile, forced_split = g_forced_split;
     if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
@@ -199,6 +200,14 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K)
         // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
         // are for outputs that are no wider, where the others would compute padding
         if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32))) continue;
+        // One 32 x 32 block per workgroup with the slab shared between its waves: for outputs at most 32
+        // wide whose long operand has k contiguous and needs no element-wise masking.  Where it
+        // applies it replaces the other 32-wide tiles (fewer or no K ranges over workgroups, so no or
+        // a smaller second pass): measured 5-20 % faster on such shapes.
+        const bool narrow_n = N <= 32 && amode == A_MK && (bmode != B_NN || N == 32) && M >= 1024;
+        const bool narrow_m = M <= 32 && bmode == B_NT && (amode == A_MK || M == 32) && N >= 1024;
+        const bool kshare = batch == 1 && (narrow_n || narrow_m);
+        if (forced_tile < 0 && ((c.id == TQ32) != kshare)) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
@@ -319,7 +328,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (batch == 0 || M == 0 || N == 0) return pl;  // nothing to do
 
 
-    const Choice ch = choose_tile(batch, M, N, K);
+    const Choice ch = choose_tile(batch, M, N, K, bmode, amode);
     pl.tile = ch.tile;
     pl.split = ch.split;
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
@@ -486,13 +495,15 @@ TileChoice choose(int64_t M, int64_t N, int64_t K)
         const int64_t k_range = cdiv(cdiv(K, split), sh.bk) * sh.bk;
         split = (int)cdiv(K, k_range);
     }
-    return TileChoice{sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, split};
+    return TileChoice{sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, sh.waves_k, split};
 }
 
-bool has_kernel(int bm, int bn, int bk, int waves_m, int waves_n)
+bool has_kernel(int bm, int bn, int bk, int waves_m, int waves_n, int waves_k)
 {
     for (const TileShape &sh : kShapes)
-        if (sh.bm == bm && sh.bn == bn && sh.bk == bk && sh.waves_m == waves_m && sh.waves_n == waves_n) return true;
+        if (sh.bm == bm && sh.bn == bn && sh.bk == bk && sh.waves_m == waves_m && sh.waves_n == waves_n &&
+            sh.waves_k == waves_k)
+            return true;
     return false;
 }
 

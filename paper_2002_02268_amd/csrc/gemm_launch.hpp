@@ -14,14 +14,14 @@ hipStream_t current_stream();              // the stream set by gemm_f32_set_str
 int record_hip_error(hipError_t e);        // remembers e for gemm_f32_last_hip_error; returns GEMMF32_ELAUNCH
 
 // ---- variants -------------------------------------------------------------------------------
-enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, T128x64 = 6, T64x128 = 7, T128x32 = 8, T32x128 = 9, NUM_TILES = 10 };
+enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, T128x64 = 6, T64x128 = 7, T128x32 = 8, T32x128 = 9, TQ32 = 10, NUM_TILES = 11 };
 
-struct TileShape { int bm, bn, bk, waves_m, waves_n; const char *name; };
+struct TileShape { int bm, bn, bk, waves_m, waves_n, waves_k; const char *name; };   // waves_k: waves that split a slab along k
 const TileShape kShapes[NUM_TILES] = {
-    {256, 256, 16, 2, 2, "t256x256x16"}, {128, 128, 16, 2, 2, "t128x128x16"}, {64, 64, 32, 2, 2, "t64x64x32"},
-    {64, 64, 64, 2, 2, "t64x64x64"},     {256, 128, 16, 2, 2, "t256x128x16"}, {128, 256, 16, 2, 2, "t128x256x16"},
-    {128, 64, 32, 2, 2, "t128x64x32"},   {64, 128, 32, 2, 2, "t64x128x32"},   {128, 32, 32, 4, 1, "t128x32x32"},
-    {32, 128, 32, 1, 4, "t32x128x32"}};
+    {256, 256, 16, 2, 2, 1, "t256x256x16"}, {128, 128, 16, 2, 2, 1, "t128x128x16"}, {64, 64, 32, 2, 2, 1, "t64x64x32"},
+    {64, 64, 64, 2, 2, 1, "t64x64x64"},     {256, 128, 16, 2, 2, 1, "t256x128x16"}, {128, 256, 16, 2, 2, 1, "t128x256x16"},
+    {128, 64, 32, 2, 2, 1, "t128x64x32"},   {64, 128, 32, 2, 2, 1, "t64x128x32"},   {128, 32, 32, 4, 1, 1, "t128x32x32"},
+    {32, 128, 32, 1, 4, 1, "t32x128x32"},   {32, 32, 64, 1, 1, 4, "t32x32x64k4"}};
 
 template <int ID, int BMODE, int AMODE> struct Variant;
 template <int BMODE, int AMODE> struct Variant<T256, BMODE, AMODE> { typedef Tile<256, 256, 16, 2, 2, BMODE, 1, 1, AMODE> type; };
@@ -42,6 +42,10 @@ template <class T, class Q = typename QuadOf<T>::type> struct LdsNeed {
     static constexpr int value = T::LDS_BYTES > Q::LDS_BYTES ? T::LDS_BYTES : Q::LDS_BYTES;
 };
 template <class T> struct LdsNeed<T, void> { static constexpr int value = T::LDS_BYTES; };
+
+// one 32 x 32 block per workgroup, its four waves splitting every slab along k: for outputs at most 32 wide
+// whose other side gives the chip enough blocks, so that K needs no split over workgroups and no second pass
+template <int BMODE, int AMODE> struct Variant<TQ32, BMODE, AMODE> { typedef Tile<32, 32, 64, 1, 1, BMODE, 3, 2, AMODE, 4> type; };
 
 template <class T> int launch(const KArgs &a)
 {
@@ -74,6 +78,7 @@ template <int BMODE, int AMODE> int launch_tile(int tile, const KArgs &a)
     case T64x128: return launch<typename Variant<T64x128, BMODE, AMODE>::type>(a);
     case T128x32: return launch<typename Variant<T128x32, BMODE, AMODE>::type>(a);
     case T32x128: return launch<typename Variant<T32x128, BMODE, AMODE>::type>(a);
+    case TQ32: return launch<typename Variant<TQ32, BMODE, AMODE>::type>(a);
     default: return launch<typename Variant<TB64, BMODE, AMODE>::type>(a);
     }
 }

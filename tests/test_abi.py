@@ -100,15 +100,20 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     pinned so that a change of the model's constants shows up here and not only as a slower benchmark)."""
     from paper_2002_02268_amd import synth
     want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x64x32/nn/a16", "transb2048": "t128x128x16/nt/a16",
-            "ragged": "t64x64x32/nn/a4/quad16", "skinny8192": "t128x32x32/nn/a16/splitk4",
-            "wide8192": "t32x128x32/nt/a16/splitk4"}
+            "ragged": "t64x64x32/nn/a4/quad16", "skinny8192": "t32x32x64k4/nn/a16",
+            "wide8192": "t32x32x64k4/nt/a16"}
     for name, variant in want.items():
         w = synth.WORKLOADS[name]
         assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]) == variant, name
-    # wide outputs never take the 32-wide tiles; outputs no wider than 32 always do
+    # wide outputs never take the 32-wide tiles; outputs no wider than 32 always do: the one whose waves
+    # share the slabs where the long operand has k contiguous and needs no element-wise masks
+    narrow = ("t128x32x32", "t32x128x32", "t32x32x64k4")
     for M, N, K in [(1024, 1024, 1024), (300, 300, 300), (128, 128, 8192), (2048, 64, 2048), (64, 4096, 512)]:
-        assert not binding.variant_name(M, N, K).startswith(("t128x32x32", "t32x128x32")), (M, N, K)
-    for M, N, K in [(4096, 32, 4096), (8192, 8, 8192), (3000, 17, 1000)]:
-        assert binding.variant_name(M, N, K).startswith("t128x32x32"), (M, N, K)
+        assert not binding.variant_name(M, N, K).startswith(narrow), (M, N, K)
+    assert binding.variant_name(4096, 32, 4096).startswith("t32x32x64k4")
+    assert binding.variant_name(8192, 8, 8192).startswith("t128x32x32")            # B stored K x 8: masked element-wise
+    assert binding.variant_name(8192, 8, 8192, transB=True).startswith("t32x32x64k4")
+    assert binding.variant_name(3000, 17, 1000).startswith("t128x32x32")
+    assert binding.variant_name(32, 4096, 4096).startswith("t32x128x32")           # B stored K x N: n contiguous
     for M, N, K in [(32, 4096, 4096), (1, 8192, 8192), (16, 11008, 4096)]:
-        assert binding.variant_name(M, N, K, transB=True).startswith("t32x128x32"), (M, N, K)
+        assert binding.variant_name(M, N, K, transB=True).startswith("t32x32x64k4"), (M, N, K)

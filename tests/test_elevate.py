@@ -258,7 +258,29 @@ def test_hand_written_schedule_of_the_large_tile_lowers_to_its_kernel():
     assert nest == ("(loop M 16 grid (loop N 16 grid (loop M 2 wave (loop N 2 wave (loop K 256 slab (loop K 8 seq "
                     "(loop M 4 unroll (loop N 4 unroll mfma32x32x2))))))))")
     assert s.as_dict() == {"bm": 256, "bn": 256, "bk": 16, "waves_m": 2, "waves_n": 2, "wave_m": 128, "wave_n": 128,
-                           "split_k": 1, "tiles_m": 16, "tiles_n": 16, "k_range": 4096}
+                           "split_k": 1, "tiles_m": 16, "tiles_n": 16, "k_range": 4096, "waves_k": 1}
+
+
+def test_waves_sharing_the_slabs_of_one_block():
+    """The 32 x 32 block whose four waves take a quarter of every 64-column slab each: K split into
+    slabs, a slab into four shares of 16 columns, a share into instruction steps; `share` is valid
+    for loops over K only, and only inside the staged loop."""
+    text = ("(seq (bodyN 0 (split M 32)) (bodyN 3 (split K 64)) (bodyN 4 (split K 16)) (bodyN 5 (split K 2))"
+            " (reorder 0 3 4 5 1 2 6)"
+            " (bodyN 0 (mark grid)) (bodyN 1 (mark slab)) (bodyN 2 (mark share)) (topDown mfma))")
+    code, s, nest = b.elevate_schedule_gemm(8192, 32, 8192, text)
+    assert code == 0, nest
+    assert nest == "(loop M 256 grid (loop K 128 slab (loop K 4 share (loop K 8 seq mfma32x32x2))))"
+    assert s.as_dict() == {"bm": 32, "bn": 32, "bk": 64, "waves_m": 1, "waves_n": 1, "wave_m": 32, "wave_n": 32,
+                           "split_k": 1, "tiles_m": 256, "tiles_n": 1, "k_range": 8192, "waves_k": 4}
+    # the library's own choice for this shape is that kernel
+    assert b.variant_name(8192, 32, 8192) == "t32x32x64k4/nn/a16"
+    d = b.elevate_schedule_gemm(8192, 32, 8192, b.elevate_default_strategy(8192, 32, 8192))
+    assert d[0] == 0 and d[1].as_dict() == s.as_dict()
+    # not over rows or columns, not outside the staged loop
+    assert b.elevate_rewrite("(mark share)", "(loop M 64 seq (loop K 8 seq mac))")[0] == b.ELEVATE_FAILED
+    code, _, why = b.elevate_schedule_gemm(8192, 32, 8192, text.replace("(bodyN 1 (mark slab)) ", ""))
+    assert code == b.ELEVATE_ELOWER and "outside the staged loop" in why
 
 
 def test_lowering_rejects_nests_no_kernel_can_run():
@@ -294,14 +316,14 @@ def test_default_strategy_reproduces_the_dispatch_choice(M, N, K):
     code, s, nest = b.elevate_schedule_gemm(M, N, K, text)
     assert code == 0, (text, nest)
     name = b.variant_name(M, N, K)
-    assert name.startswith(f"t{s.bm}x{s.bn}x{s.bk}/"), (name, s.as_dict())
+    assert name.startswith(f"t{s.bm}x{s.bn}x{s.bk}" + (f"k{s.waves_k}/" if s.waves_k > 1 else "/")), (name, s.as_dict())
     if "splitk" in name:
         assert s.split_k == int(name.split("splitk")[1])
     else:
         assert s.split_k == 1
     assert s.tiles_m == -(-M // s.bm) and s.tiles_n == -(-N // s.bn)
-    grid = {(128, 32): (4, 1), (32, 128): (1, 4)}.get((s.bm, s.bn), (2, 2))   # waves per workgroup
-    assert (s.waves_m, s.waves_n, s.wave_m, s.wave_n) == (*grid, s.bm // grid[0], s.bn // grid[1])
+    grid = {(128, 32): (4, 1, 1), (32, 128): (1, 4, 1), (32, 32): (1, 1, 4)}.get((s.bm, s.bn), (2, 2, 1))   # waves per workgroup
+    assert (s.waves_m, s.waves_n, s.waves_k, s.wave_m, s.wave_n) == (*grid, s.bm // grid[0], s.bn // grid[1])
     assert s.k_range % s.bk == 0 and s.split_k * s.k_range >= K > (s.split_k - 1) * s.k_range
     # same text, same result
     assert b.elevate_default_strategy(M, N, K) == text

@@ -326,7 +326,7 @@ def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
     wide in that dimension (four waves side by side along the other).  Rows and columns that do not fill the tile, K not a
     multiple of the slab, K split or not, padded strides, alpha and beta: exact on integers, within
     tolerance on U(-1,1)."""
-    narrow = "8" if N <= 32 else "9"                       # tile 128x32x32 / 32x128x32
+    narrow_tiles = ("8" if N <= 32 else "9", "10")         # tile 128x32x32 / 32x128x32, and the 32x32 block with shared slabs
     for ints in (True, False):
         gen = synth.small_ints if ints else synth.uniform
         A = gen((M, K), 7000 + M, synth.TENSOR_A)
@@ -338,7 +338,7 @@ def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
             dA, _ = padded_dev(stored(A, tA), 3)
             dB, _ = padded_dev(stored(B, tB), 1)
             dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
-            for forced in (None, narrow):                  # the dispatch's own choice, then the narrow tile
+            for forced in (None,) + narrow_tiles:          # the dispatch's own choice, then the narrow tiles
                 if forced is not None:
                     os.environ["GEMMF32_FORCE_TILE"] = forced
                     dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)

@@ -20,10 +20,10 @@ from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 NTHREADS = min(16, os.cpu_count() or 1)
 TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3", "t256x128": "4", "t128x256": "5", "t128x64": "6",
-         "t64x128": "7", "t128x32": "8", "t32x128": "9"}
+         "t64x128": "7", "t128x32": "8", "t32x128": "9", "tq32": "10"}
 TILE_DIMS = {"t256": (256, 256), "t128": (128, 128), "t64": (64, 64), "tb64": (64, 64), "t256x128": (256, 128),
              "t128x256": (128, 256), "t128x64": (128, 64), "t64x128": (64, 128),
-             "t128x32": (128, 32), "t32x128": (32, 128)}
+             "t128x32": (128, 32), "t32x128": (32, 128), "tq32": (32, 32)}
 
 
 def dev(x: np.ndarray):
@@ -312,8 +312,7 @@ def test_workload_one_short_dimension_full_oracle(name):
     """8192 x 32 x 8192 and 32 x 8192 x 8192 (B stored N x K) as the benchmark launches them: every
     element against the oracle, on U(-1,1) and exactly on integer-valued operands."""
     w = synth.WORKLOADS[name]
-    assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]).startswith(
-        "t128x32x32" if w["N"] == 32 else "t32x128x32")
+    assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]).startswith("t32x32x64k4")
     for dist in (None, "ints"):
         A, B = synth.make_operands(name, dist=dist)
         dC = torch.full((w["M"], w["N"]), float("nan"), device="cuda")
