@@ -58,6 +58,7 @@ CASES = [
     (128, 128, 8192, False, None, 1),
     (520, 260, 300, False, (256, 256, 16), 1),
     (64, 64, 64, False, (64, 64, 64), 1),
+    (2048, 32, 1500, False, None, 1),        # the library's choice here: 32 x 32 blocks whose waves share the slabs
 ]
 
 
