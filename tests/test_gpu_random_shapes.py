@@ -1,0 +1,73 @@
+"""GPU parity of gemm_f32_ex on seeded random shapes, layouts, scalings, row paddings and tile
+choices (the dispatch's own and forced ones) against the general-form CPU oracle.
+
+Integer-valued operands in {-3..3}, integer or half-integer alpha and beta, C_old in {-5..5}:
+every partial sum is an integer (or a multiple of 1/2) far below 2^24, so any summation order is
+exact and the comparison is bit for bit.  The shape classes aim at the dispatch's special cases:
+one short dimension (the 32-wide tiles and the tile whose waves share the slabs), small outputs
+with long K (K splits), tile counts a little above a multiple of 256 (split last round, with and
+without 32 x 32 blocks), and plain mid-size products with ragged edges."""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2002_02268_amd import binding, synth  # noqa: E402
+
+from test_gpu_parity import NTHREADS, TILES, padded_dev  # noqa: E402
+
+TENSOR_C = 2
+CASES_PER_CLASS = 24
+
+
+def _draw(rng, cls):
+    r = lambda lo, hi: int(rng.integers(lo, hi + 1))  # noqa: E731
+    if cls == "short_m":
+        return r(1, 40), r(1, 5000), r(1, 3000)
+    if cls == "short_n":
+        return r(1, 5000), r(1, 40), r(1, 3000)
+    if cls == "long_k":
+        return r(1, 300), r(1, 300), r(2000, 20000)
+    if cls == "second_round":
+        return r(1000, 1300), r(1000, 1300), r(1, 700)
+    return r(1, 1500), r(1, 1500), r(1, 900)
+
+
+@pytest.mark.parametrize("cls", ["short_m", "short_n", "long_k", "second_round", "plain"])
+def test_random_shapes_bit_exact(cls):
+    rng = np.random.default_rng({"short_m": 11, "short_n": 12, "long_k": 13, "second_round": 14, "plain": 15}[cls])
+    tiles = [None, None, None] + list(TILES.values())
+    try:
+        for idx in range(CASES_PER_CLASS):
+            M, N, K = _draw(rng, cls)
+            tA, tB = bool(rng.random() < 0.4), bool(rng.random() < 0.5)
+            alpha = float(rng.choice([1.0, 1.0, -2.0, 0.5]))
+            beta = float(rng.choice([0.0, 0.0, 1.0, -0.5]))
+            pa, pb, pc = int(rng.choice([0, 0, 3, 8])), int(rng.choice([0, 0, 1, 4])), int(rng.choice([0, 0, 5]))
+            tile = tiles[int(rng.integers(0, len(tiles)))]
+            print(f"case {cls}[{idx}] M={M} N={N} K={K} tA={tA} tB={tB} alpha={alpha} beta={beta} "
+                  f"pads=({pa},{pb},{pc}) tile={tile}", flush=True)
+            A = synth.small_ints((K, M) if tA else (M, K), 9000 + idx, synth.TENSOR_A, lo=-3, hi=3)
+            B = synth.small_ints((N, K) if tB else (K, N), 9000 + idx, synth.TENSOR_B, lo=-3, hi=3)
+            C0 = synth.small_ints((M, N), 9000 + idx, TENSOR_C, lo=-5, hi=5)
+            ref = oracle.gemm_f32_ex(A, B, C0, alpha, beta, tA, tB, nthreads=NTHREADS)
+            dA, _ = padded_dev(A, pa)
+            dB, _ = padded_dev(B, pb)
+            dC, bufC = padded_dev(C0, pc)
+            if tile is None:
+                os.environ.pop("GEMMF32_FORCE_TILE", None)
+            else:
+                os.environ["GEMMF32_FORCE_TILE"] = tile
+            binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
+            whole = bufC.cpu().numpy()
+            assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+            assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE", None)
