@@ -233,7 +233,9 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B
             // than 240 workgroups do not reach the full rate)
             const double bytes_per_us = std::min(5.2e6, (double)wgs * 0.022e6);
             const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / bytes_per_us;
-            if (cost < hbm_us) cost = hbm_us;
+            // (between candidates that are all bound by the memory interface, the one with less matrix work
+            // and fewer fixed costs is still the faster: a small share of the compute cost breaks the tie)
+            cost = std::max(cost, hbm_us) + 0.02 * cost;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
@@ -241,7 +243,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B
         }
     }
     if (best_cost < 0 && forced_tile >= 0) best = {forced_tile, 1};   // forced split did not fit: no split
-    if (M <= 64 && N <= 64 && K <= 64 && forced_tile < 0) best = {TB64, 1};
+    if (batch == 1 && M <= 64 && N <= 64 && K <= 64 && forced_tile < 0) best = {TB64, 1};
     return best;
 }
 
