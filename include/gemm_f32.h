@@ -175,6 +175,7 @@ void gemm_f32_shutdown(void);
  *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
  *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
  *   GEMMF32_NO_QUAD=1          split the last round along K only, never into 32 x 32 blocks
+ *   GEMMF32_NO_KSHARE=1        the 32x32x64 tile only for outputs at most 32 wide, not for outputs of a few hundred blocks
  * gemm_f32_scheduled (elevate.h) is the interface for choosing tile and split per call.
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,

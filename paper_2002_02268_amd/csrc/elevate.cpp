@@ -626,6 +626,7 @@ bool lower_nest(const TermP &nest, long long M, long long N, long long K, Lowere
     long long grid[3] = {1, 1, 1}, wave[3] = {1, 1, 1}, block[3] = {1, 1, 1}, below_wave[3] = {1, 1, 1};
     long long bk = 0;
     bool seen_non_grid = false, seen_below_wave = false, in_slab = false, seen_slab = false;
+    bool k_loop_outside = false, share_without_slab = false;
     TermP t = nest;
     for (int depth = 0;; ++depth) {
         if (depth > 64) { err = "nest too deep"; return false; }
@@ -641,10 +642,12 @@ bool lower_nest(const TermP &nest, long long M, long long N, long long K, Lowere
             block[ax] *= l.extent;
             if (l.kind == "share") {
                 // waves sharing the reduction: only inside the staged loop, where each takes part of a slab
-                if (!in_slab) { err = "a shared loop over the reduction outside the staged loop"; return false; }
+                // (or with no staged loop at all, when the whole K range is one slab)
+                if (!in_slab && k_loop_outside) { err = "a shared loop over the reduction outside the staged loop"; return false; }
                 if (wave[2] != 1) { err = "two shared loops"; return false; }
                 wave[2] = l.extent;
-                bk *= l.extent;
+                if (in_slab) bk *= l.extent;
+                else share_without_slab = true;
             } else if (l.kind == "wave") {
                 if (seen_below_wave) { err = "a wave-parallel loop lies inside a sequential loop"; return false; }
                 if (ax == 2) { err = "a wave-parallel loop over the reduction"; return false; }
@@ -656,10 +659,12 @@ bool lower_nest(const TermP &nest, long long M, long long N, long long K, Lowere
                 if (l.kind == "slab") {
                     if (ax != 2) { err = "a staged loop that is not over K"; return false; }
                     if (seen_slab) { err = "two staged K loops"; return false; }
+                    if (share_without_slab) { err = "a staged loop inside a shared loop"; return false; }
                     seen_slab = in_slab = true;
                     bk = 1;
                 } else if (l.kind == "seq" || l.kind == "unroll") {
                     if (in_slab && ax == 2) bk *= l.extent;
+                    if (!in_slab && ax == 2) k_loop_outside = true;
                 } else {
                     err = "unknown loop kind '" + l.kind + "'";
                     return false;

@@ -117,7 +117,7 @@ const VariantModel kCandidates[] = {
     {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
     {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
     {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120},
-    {TQ32, 0.60, 0.60, 400, 150}};
+    {TQ32, 0.775, 0.775, 700, 100}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -201,13 +201,19 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B
         // are for outputs that are no wider, where the others would compute padding
         if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32))) continue;
         // One 32 x 32 block per workgroup with the slab shared between its waves: for outputs at most 32
-        // wide whose long operand has k contiguous and needs no element-wise masking.  Where it
+        // wide whose operands need no element-wise masking (a B stored K x N with fewer than 32 columns
+        // does, and so does an A stored K x M with fewer than 32 rows).  Where it
         // applies it replaces the other 32-wide tiles (fewer or no K ranges over workgroups, so no or
         // a smaller second pass): measured 5-20 % faster on such shapes.
         const bool narrow_n = N <= 32 && amode == A_MK && (bmode != B_NN || N == 32) && M >= 1024;
-        const bool narrow_m = M <= 32 && bmode == B_NT && (amode == A_MK || M == 32) && N >= 1024;
+        const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024;
         const bool kshare = batch == 1 && (narrow_n || narrow_m);
-        if (forced_tile < 0 && ((c.id == TQ32) != kshare)) continue;
+        if (forced_tile < 0 && c.id != TQ32 && kshare) continue;
+        // It also competes on any single product at least 32 x 32: a few hundred blocks occupy the chip
+        // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
+        // 11.7 instead of 19.4 us).
+        const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !std::getenv("GEMMF32_NO_KSHARE");
+        if (forced_tile < 0 && c.id == TQ32 && !kshare && !kshare_general) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};

@@ -105,15 +105,22 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     for name, variant in want.items():
         w = synth.WORKLOADS[name]
         assert binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]) == variant, name
-    # wide outputs never take the 32-wide tiles; outputs no wider than 32 always do: the one whose waves
-    # share the slabs where the long operand has k contiguous and needs no element-wise masks
-    narrow = ("t128x32x32", "t32x128x32", "t32x32x64k4")
+    # wide outputs never take the 128 x 32 and 32 x 128 tiles; outputs no wider than 32 always take a 32-wide
+    # tile: the one whose waves share the slabs where the long operand has k contiguous and needs no
+    # element-wise masks
+    narrow = ("t128x32x32", "t32x128x32")
     for M, N, K in [(1024, 1024, 1024), (300, 300, 300), (128, 128, 8192), (2048, 64, 2048), (64, 4096, 512)]:
         assert not binding.variant_name(M, N, K).startswith(narrow), (M, N, K)
+    # outputs of a few hundred 32 x 32 blocks take the shared-slab tile and need no K split; large ones do not
+    for M, N, K in [(640, 640, 1024), (512, 512, 4096), (300, 300, 300), (2048, 256, 1024)]:
+        assert binding.variant_name(M, N, K) == "t32x32x64k4/nn/a16", (M, N, K)
+    for M, N, K in [(1024, 1024, 1024), (2048, 2048, 2048), (1280, 1280, 1280)]:
+        assert not binding.variant_name(M, N, K).startswith("t32x32x64k4"), (M, N, K)
     assert binding.variant_name(4096, 32, 4096).startswith("t32x32x64k4")
     assert binding.variant_name(8192, 8, 8192).startswith("t128x32x32")            # B stored K x 8: masked element-wise
     assert binding.variant_name(8192, 8, 8192, transB=True).startswith("t32x32x64k4")
     assert binding.variant_name(3000, 17, 1000).startswith("t128x32x32")
-    assert binding.variant_name(32, 4096, 4096).startswith("t32x128x32")           # B stored K x N: n contiguous
+    assert binding.variant_name(5000, 20, 999, lda=999).startswith("t128x32x32")
+    assert binding.variant_name(32, 4096, 4096).startswith("t32x32x64k4")
     for M, N, K in [(32, 4096, 4096), (1, 8192, 8192), (16, 11008, 4096)]:
         assert binding.variant_name(M, N, K, transB=True).startswith("t32x32x64k4"), (M, N, K)

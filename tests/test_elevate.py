@@ -281,6 +281,18 @@ def test_waves_sharing_the_slabs_of_one_block():
     assert b.elevate_rewrite("(mark share)", "(loop M 64 seq (loop K 8 seq mac))")[0] == b.ELEVATE_FAILED
     code, _, why = b.elevate_schedule_gemm(8192, 32, 8192, text.replace("(bodyN 1 (mark slab)) ", ""))
     assert code == b.ELEVATE_ELOWER and "outside the staged loop" in why
+    # a K range that is one slab needs no staged loop: the waves share the whole range
+    short = ("(seq (bodyN 2 (cover K 64)) (bodyN 0 (split M 32)) (bodyN 3 (split K 16)) (bodyN 4 (split K 2)) (reorder 0 3 4 1 2 5)"
+             " (bodyN 0 (mark grid)) (bodyN 1 (mark share)) (topDown mfma))")
+    code, s1, nest = b.elevate_schedule_gemm(2048, 32, 40, short)
+    assert code == 0, nest
+    assert nest == "(loop M 64 grid (loop K 4 share (loop K 8 seq mfma32x32x2)))"
+    assert (s1.bm, s1.bn, s1.bk, s1.waves_k, s1.k_range, s1.split_k) == (32, 32, 64, 4, 64, 1)
+    # but a staged loop cannot lie inside the shared one
+    inside = ("(seq (bodyN 0 (split M 32)) (bodyN 3 (split K 2048)) (bodyN 4 (split K 64)) (bodyN 5 (split K 2))"
+              " (reorder 0 3 4 5 1 2 6) (bodyN 0 (mark grid)) (bodyN 1 (mark share)) (bodyN 2 (mark slab)) (topDown mfma))")
+    code, _, why = b.elevate_schedule_gemm(8192, 32, 8192, inside)
+    assert code == b.ELEVATE_ELOWER and "inside a shared loop" in why
 
 
 def test_lowering_rejects_nests_no_kernel_can_run():

@@ -145,6 +145,7 @@ def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
         for no_quad in (False, True):       # the last round as 32 x 32 blocks (scalars applied in the kernel), then as K ranges
             if no_quad:
                 os.environ["GEMMF32_NO_QUAD"] = "1"
+                os.environ["GEMMF32_NO_KSHARE"] = "1"      # or the shared-slab tile would take the ragged shape whole
             try:
                 name = binding.variant_name(M, N, K, transB=tB)
                 print(f"case tA={tA} tB={tB} M={M} N={N} K={K} variant={name}", flush=True)
@@ -153,6 +154,7 @@ def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
                 binding.gemm_f32_ex(dev(stored(A, tA)), dev(stored(B, tB)), dC, -2.0, 3.0, tA, tB)
             finally:
                 os.environ.pop("GEMMF32_NO_QUAD", None)
+                os.environ.pop("GEMMF32_NO_KSHARE", None)
             assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
 
 

@@ -538,7 +538,7 @@ def test_shutdown_releases_workspace_and_library_stays_usable():
 # --------------------------------------------------------------------- split tail (uneven tile counts)
 
 @pytest.mark.parametrize("tile,how", [("t128", "tail"), ("t64", "tail"), ("tb64", "tail"), ("t64", "quad"), ("tb64", "quad"),
-                                      ("t128x64", "quad"), ("t64x128", "quad")])
+                                      ("t128x64", "quad"), ("t64x128", "quad"), ("tq32", "tail")])
 @pytest.mark.parametrize("transB", [False, True])
 def test_split_tail_bit_exact(force_tile, tile, how, transB):
     """More tiles than one round of 256, with a small remainder.  "tail": the remainder's tiles are cut
@@ -550,7 +550,7 @@ def test_split_tail_bit_exact(force_tile, tile, how, transB):
         os.environ["GEMMF32_NO_QUAD"] = "1"
     shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
               "tb64": [(1000, 1030, 999), (1100, 1100, 1100)], "t128x64": [(2100, 1090, 700), (2200, 1000, 333)],
-              "t64x128": [(1090, 2100, 700)]}[tile]
+              "t64x128": [(1090, 2100, 700)], "tq32": [(520, 530, 3000), (576, 570, 4100)]}[tile]
     try:
         _split_tail_cases(shapes, how, transB)
     finally:
@@ -592,6 +592,7 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
     binding.gemm_f32_packed(dA, dBp, dC)
     check_close(dC.cpu().numpy(), ref, 999)
     os.environ["GEMMF32_NO_QUAD"] = "1"
+    os.environ["GEMMF32_NO_KSHARE"] = "1"          # or the tile whose waves share the slabs takes the shape whole
     try:
         assert "/tail16x8" in binding.variant_name(1000, 1030, 999)
         dC.fill_(float("nan"))
@@ -599,6 +600,7 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
         os.environ.pop("GEMMF32_NO_QUAD", None)
+        os.environ.pop("GEMMF32_NO_KSHARE", None)
     os.environ["GEMMF32_NO_TAIL_SPLIT"] = "1"
     try:
         name = binding.variant_name(1000, 1030, 999)
