@@ -137,14 +137,34 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 // quad: instead, every tail tile is cut into its 32 x 32 blocks (`pieces` of them), each computed by a
 // whole workgroup whose waves share the slabs along k: a quarter of a tile's time per block, and no
 // second pass.  Better than K ranges when K is short (the second pass costs a fixed 10 us).
+// The test hooks of the environment, read once per call (every lookup scans the whole environment).
+struct Hooks {
+    bool no_tail_split, no_quad, no_kshare;
+    int force_tile, force_split;       // -1: not forced
+};
+Hooks read_hooks()
+{
+    Hooks h = {std::getenv("GEMMF32_NO_TAIL_SPLIT") != nullptr, std::getenv("GEMMF32_NO_QUAD") != nullptr,
+               std::getenv("GEMMF32_NO_KSHARE") != nullptr, -1, -1};
+    if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
+        const int t = std::atoi(f);
+        if (t >= 0 && t < NUM_TILES) h.force_tile = t;
+    }
+    if (const char *f = std::getenv("GEMMF32_FORCE_SPLITK")) {
+        const int t = std::atoi(f);
+        if (t >= 1 && t <= 256) h.force_split = t;
+    }
+    return h;
+}
+
 struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; bool quad; };
 
-TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
+TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t tiles, int64_t K)
 {
     const VariantModel &vm = variant_model(tile);
     const int bm = kShapes[tile].bm, bn = kShapes[tile].bn, bk = kShapes[tile].bk;
     TailSplit t = {tiles % 256, 1, 0, 0.0, false};
-    if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || std::getenv("GEMMF32_NO_TAIL_SPLIT")) return t;
+    if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || hooks.no_tail_split) return t;
     const int64_t units = cdiv(K, bk);
     int64_t S = 256 / t.tail;
     if (S > 8) S = 8;     // shorter pieces than an eighth of K cost more in the second pass than they save
@@ -156,7 +176,7 @@ TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
     // start on compute units whose whole tiles ended early); in proportion if there are more than 256
     double quad_benefit = 0.0;
     const int64_t subs = (int64_t)(bm / 32) * (bn / 32);
-    if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !std::getenv("GEMMF32_NO_QUAD")) {
+    if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !hooks.no_quad) {
         const double t_block = 5.0 + 0.0018 * (double)K;
         quad_benefit = t_full - std::max(1.0, (double)(t.tail * subs) / 256.0) * t_block;
     }
@@ -182,17 +202,42 @@ TailSplit plan_tail_split(int tile, int64_t batch, int64_t tiles, int64_t K)
 // set around one call by run_forced: tile and split given by the caller instead of the cost model
 thread_local int g_forced_tile = -1, g_forced_split = -1;
 
-Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B_NN, int amode = A_MK)
+Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split, int64_t batch, int64_t M, int64_t N,
+                           int64_t K, int bmode, int amode);
+
+// The cost model walks every (tile, split) candidate: 1-2 us, as much as the launch itself for a small
+// product.  A caller repeats a few shapes; each thread remembers the choices of the last ones it asked for.
+struct ChoiceKey {
+    int64_t batch, M, N, K;
+    int bmode, amode, forced_tile, forced_split, flags;
+    bool operator==(const ChoiceKey &o) const
+    {
+        return batch == o.batch && M == o.M && N == o.N && K == o.K && bmode == o.bmode && amode == o.amode &&
+               forced_tile == o.forced_tile && forced_split == o.forced_split && flags == o.flags;
+    }
+};
+struct ChoiceSlot { ChoiceKey key; Choice choice; bool valid; };
+thread_local ChoiceSlot g_choice_cache[64];
+
+Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B_NN, int amode = A_MK)
 {
-    int forced_tile = g_forced_tile, forced_split = g_forced_split;
-    if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
-        int t = std::atoi(f);
-        if (t >= 0 && t < NUM_TILES) forced_tile = t;
-    }
-    if (const char *f = std::getenv("GEMMF32_FORCE_SPLITK")) {
-        int t = std::atoi(f);
-        if (t >= 1 && t <= 256) forced_split = t;
-    }
+    const int forced_tile = hooks.force_tile >= 0 ? hooks.force_tile : g_forced_tile;
+    const int forced_split = hooks.force_split >= 1 ? hooks.force_split : g_forced_split;
+    const ChoiceKey key = {batch, M, N, K, bmode, amode, forced_tile, forced_split,
+                           (hooks.no_tail_split ? 1 : 0) | (hooks.no_quad ? 2 : 0) | (hooks.no_kshare ? 4 : 0)};
+    const uint64_t h = ((uint64_t)M * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)N * 0xC2B2AE3D27D4EB4Full) ^
+                       ((uint64_t)K * 0x165667B19E3779F9ull) ^ ((uint64_t)batch * 0x27D4EB2F165667C5ull);
+    ChoiceSlot &slot = g_choice_cache[h >> 58];
+    if (slot.valid && slot.key == key) return slot.choice;
+    slot.key = key;
+    slot.choice = evaluate_candidates(hooks, forced_tile, forced_split, batch, M, N, K, bmode, amode);
+    slot.valid = true;
+    return slot.choice;
+}
+
+Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split, int64_t batch, int64_t M, int64_t N,
+                           int64_t K, int bmode, int amode)
+{
     Choice best = {TB64, 1};
     double best_cost = -1;
     for (const auto &c : kCandidates) {
@@ -212,7 +257,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B
         // It also competes on any single product at least 32 x 32: a few hundred blocks occupy the chip
         // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
         // 11.7 instead of 19.4 us).
-        const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !std::getenv("GEMMF32_NO_KSHARE");
+        const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !hooks.no_kshare;
         if (forced_tile < 0 && c.id == TQ32 && !kshare && !kshare_general) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
@@ -243,7 +288,7 @@ Choice choose_tile(int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B
             // and fewer fixed costs is still the faster: a small share of the compute cost breaks the tie)
             cost = std::max(cost, hbm_us) + 0.02 * cost;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
-            if (S == 1) cost -= plan_tail_split(c.id, batch, tiles, K).benefit_us;
+            if (S == 1) cost -= plan_tail_split(hooks, c.id, batch, tiles, K).benefit_us;
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
             if (forced_split >= 1) break;
         }
@@ -336,7 +381,8 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (batch == 0 || M == 0 || N == 0) return pl;  // nothing to do
 
 
-    const Choice ch = choose_tile(batch, M, N, K, bmode, amode);
+    const Hooks hooks = read_hooks();
+    const Choice ch = choose_tile(hooks, batch, M, N, K, bmode, amode);
     pl.tile = ch.tile;
     pl.split = ch.split;
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
@@ -374,7 +420,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
     // 16 become 256 pieces that run beside the full round).
     if (pl.split == 1) {
-        const TailSplit ts = plan_tail_split(pl.tile, batch, total, K);
+        const TailSplit ts = plan_tail_split(hooks, pl.tile, batch, total, K);
         if (ts.pieces > 1) {
             a.tail_first = (int)(total - ts.tail);
             a.tail_split = (int)ts.pieces;
@@ -496,7 +542,7 @@ namespace gemmf32_host {
 
 TileChoice choose(int64_t M, int64_t N, int64_t K)
 {
-    const Choice c = choose_tile(1, M, N, K);
+    const Choice c = choose_tile(read_hooks(), 1, M, N, K);
     const TileShape &sh = kShapes[c.tile];
     int split = c.split;
     if (split > 1) {   // the ranges that are not empty, as make_plan counts them
