@@ -285,6 +285,9 @@ def main() -> int:
                     help="time the seven ladder levels (baseline ... parallel) on square1024 and square4096 "
                          "and print one JSON object; levels 4-6 include pack_b in every step, as the paper's "
                          "array-packing versions include their packing loop")
+    ap.add_argument("--ladder-pass", action="store_true",
+                    help="run every ladder level --steps times on --workload (square1024 or square4096), untimed: "
+                         "the program that the counter runs of the ladder profile attach to")
     ap.add_argument("--protocol", action="store_true",
                     help="time every workload in 20 windows of at least 50 ms (median and best), the latency of one "
                          "square1024 launch, and the batched workload with operands streamed from HBM; one JSON object")
@@ -320,6 +323,20 @@ def main() -> int:
 
     if args.ladder:
         print(json.dumps(ladder(torch, binding, synth)))
+        return 0
+
+    if args.ladder_pass:
+        w = synth.WORKLOADS[args.workload]
+        A, B = synth.make_operands(args.workload)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        dC = torch.empty((w["M"], w["N"]), device="cuda")
+        dBp = torch.empty(binding.pack_b_size(w["N"], w["K"]) // 4, device="cuda")
+        binding.pack_b(dB, dBp)
+        for level in range(binding.gemm_f32_ladder_levels()):
+            for _ in range(args.steps):
+                binding.gemm_f32_ladder(level, dA, dB, dC, dBp)
+            torch.cuda.synchronize()
+        print(json.dumps({"ladder_pass": args.workload, "launches_per_level": args.steps}))
         return 0
 
     if args.protocol:
