@@ -26,11 +26,11 @@ HBM_GBS = 8000.0
 # of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
 # one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "bd1ba1db50cef1033f14e4d486ef48efea5a6d5438f08635f1d1dd24b03fae2d",
-    "square4096": {"fetch_kib": 196784.1, "write_kib": 65536.0, "copy_fetch_kib": 32818.1, "copy_write_kib": 65536.0},
-    "square1024": {"fetch_kib": 14412.5, "write_kib": 4096.0, "copy_fetch_kib": 32818.1, "copy_write_kib": 65536.0},
-    "batched64": {"fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32818.1, "copy_write_kib": 65536.0},
-    "skinny8192": {"fetch_kib": 135438.8, "write_kib": 1024.0, "copy_fetch_kib": 32818.1, "copy_write_kib": 65536.0},
+    "sources_sha256": "e6f4d2ad2d4b71ca122eb96859e430651ab7caeec8911c0b86c097da46c703f0",
+    "square4096": {"fetch_kib": 196784.1, "write_kib": 65536.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
+    "square1024": {"fetch_kib": 14412.5, "write_kib": 4096.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
+    "batched64": {"fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
+    "skinny8192": {"fetch_kib": 135747.9, "write_kib": 1024.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 
@@ -145,9 +145,16 @@ def cpu_baseline(runner, target_s=12.0):
     rows = max(used, rows // used * used)
     t = run(rows)
     gflops = 2.0 * rows * w["N"] * w["K"] / t / 1e9
+    # the same oracle on one thread, for about 3 s (rows scaled from the threaded run)
+    rows1 = int(max(1, min(w["M"], rows * 3.0 / max(t, 1e-3) / used)))
+    t0 = time.perf_counter()
+    oracle.gemm_f32(np.ascontiguousarray(A[:rows1]), B, transB=w["transB"], nthreads=1)
+    t1 = time.perf_counter() - t0
     return {"value": round(gflops, 3), "unit": "GFLOP/s", "cores": used, "kind": "oracle",
             "sample": f"first {rows} of {w['M']} rows of A against all of B ({runner.name}), "
-                      f"{t:.1f} s, fp64 triple loop"}
+                      f"{t:.1f} s, fp64 triple loop",
+            "one_thread": {"value": round(2.0 * rows1 * w["N"] * w["K"] / t1 / 1e9, 3), "unit": "GFLOP/s",
+                           "sample": f"first {rows1} rows, {t1:.1f} s"}}
 
 
 def ladder(torch, binding, synth):
