@@ -170,8 +170,9 @@ void gemm_f32_shutdown(void);
  * "aligned".  The string lives in a per-thread buffer that the next call on the thread overwrites.
  *
  * Test hooks read from the environment at every call (not meant for production use):
- *   GEMMF32_FORCE_TILE=0..10   tile 256x256x16, 128x128x16, 64x64x32, 64x64x64, 256x128x16, 128x256x16,
- *                              128x64x32, 64x128x32, 128x32x32, 32x128x32, 32x32x64 with four waves sharing each slab
+ *   GEMMF32_FORCE_TILE=0..12   tile 256x256x16, 128x128x16, 64x64x32, 64x64x64, 256x128x16, 128x256x16,
+ *                              128x64x32, 64x128x32, 128x32x32, 32x128x32, and 32x32x64, 64x32x64, 32x64x64 with
+ *                              four waves sharing each slab
  *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
  *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
  *   GEMMF32_NO_QUAD=1          split the last round along K only, never into 32 x 32 blocks

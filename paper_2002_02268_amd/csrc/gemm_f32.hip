@@ -117,7 +117,7 @@ const VariantModel kCandidates[] = {
     {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
     {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
     {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120},
-    {TQ32, 0.775, 0.775, 700, 100}};
+    {TQ32, 0.775, 0.775, 700, 100},   {TQ64x32, 0.87, 0.86, 350, 80},   {TQ32x64, 0.87, 0.86, 350, 80}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -176,7 +176,8 @@ TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t t
     // start on compute units whose whole tiles ended early); in proportion if there are more than 256
     double quad_benefit = 0.0;
     const int64_t subs = (int64_t)(bm / 32) * (bn / 32);
-    if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && !hooks.no_quad) {
+    // (only tiles whose waves each own a block have the block kernel: the kernel header's QuadOf)
+    if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && kShapes[tile].waves_k == 1 && !hooks.no_quad) {
         const double t_block = 5.0 + 0.0018 * (double)K;
         quad_benefit = t_full - std::max(1.0, (double)(t.tail * subs) / 256.0) * t_block;
     }
@@ -259,6 +260,10 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         // 11.7 instead of 19.4 us).
         const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !hooks.no_kshare;
         if (forced_tile < 0 && c.id == TQ32 && !kshare && !kshare_general) continue;
+        // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
+        // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
+        // 21 -> 18.3 us).
+        if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && (kshare || !kshare_general)) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};

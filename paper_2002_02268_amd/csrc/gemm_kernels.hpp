@@ -123,8 +123,8 @@ struct Tile {
     static_assert(BMODE != B_PACKED || BN % kPanel == 0 || kPanel % BN == 0, "tile vs panel");
     static_assert(LDS_BYTES <= 160 * 1024, "fits the 160 KB of LDS per compute unit");
     static_assert(G % WGK == 0 && GQ >= 2 && GQ % 2 == 0, "every wave multiplies an even number of groups of a slab");
-    static_assert(WGK == 1 || (MB == 1 && NB == 1 && WGM == 1 && WGN == 1), "k-split waves share one 32 x 32 block");
-    static_assert(WGK == 1 || WGK * 32 * 33 * 4 <= LDS_BYTES, "room for the final sum of the k-split accumulators");
+    static_assert(WGK == 1 || (WGM == 1 && WGN == 1), "k-split waves share the whole tile");
+    static_assert(WGK == 1 || WGK * BM * (BN + 1) * 4 <= LDS_BYTES, "room for the final sum of the k-split accumulators");
 };
 
 // Maps the hardware workgroup id to a tile.  Workgroups are handed to the 8 XCDs round
@@ -689,21 +689,30 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const float alpha = p.alpha, beta = p.beta;
     const bool add_old = (beta != 0.f);                      // uniform over the grid
     if constexpr (T::WGK > 1) {
-        // the waves hold partial sums of the same 32 x 32 block: through LDS (element (i, j) of wave w
-        // at red[w][i * 33 + j]), added in wave order, stored by all threads
+        // the waves hold partial sums of the same tile: through LDS (element (r, c) of wave w at
+        // red[w][r * (BN + 1) + c]), added in wave order, stored by all threads
         __syncthreads();                                      // the slab buffers are free
         float *red = lds;
+        constexpr int RS = BN + 1, RW = BM * RS;
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            red[kq * (32 * 33) + (8 * (v / 4) + 4 * half + (v % 4)) * 33 + l32] = acc[0][0][v];
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int mrow = 8 * (v / 4) + 4 * half + (v % 4);
+                    const int r = A_KMAJOR ? 32 * i + mrow : MB * mrow + i;
+                    const int c = (T::BMODE == B_NT) ? 32 * j + l32 : NB * l32 + j;
+                    red[kq * RW + r * RS + c] = acc[i][j][v];
+                }
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 32 * 32 / NTHR; ++t) {
-            const int e = tid + NTHR * t, i = e >> 5, j = e & 31;
+        for (int t = 0; t < BM * BN / NTHR; ++t) {
+            const int e = tid + NTHR * t, i = e / BN, j = e % BN;
             const int gi = m0 + i, gj = n0 + j;
-            float sum = red[i * 33 + j];
+            float sum = red[i * RS + j];
 #pragma unroll
-            for (int w = 1; w < T::WGK; ++w) sum += red[w * (32 * 33) + i * 33 + j];
+            for (int w = 1; w < T::WGK; ++w) sum += red[w * RW + i * RS + j];
             if (row_ok(gi) && cols_ok(gj, 1)) {
                 float *dst = C + (int64_t)gi * p.ldc + gj;
                 float r = alpha * sum;

@@ -99,7 +99,7 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     """The tile and split the cost model takes for the workloads the benchmark times (a host computation;
     pinned so that a change of the model's constants shows up here and not only as a slower benchmark)."""
     from paper_2002_02268_amd import synth
-    want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x64x32/nn/a16", "transb2048": "t128x128x16/nt/a16",
+    want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x32x64k4/nn/a16", "transb2048": "t128x128x16/nt/a16",
             "ragged": "t64x64x32/nn/a4/quad16", "skinny8192": "t32x32x64k4/nn/a16",
             "wide8192": "t32x32x64k4/nt/a16"}
     for name, variant in want.items():
@@ -113,9 +113,10 @@ def test_dispatch_choices_for_the_benchmark_workloads():
         assert not binding.variant_name(M, N, K).startswith(narrow), (M, N, K)
     # outputs of a few hundred 32 x 32 blocks take the shared-slab tile and need no K split; large ones do not
     for M, N, K in [(640, 640, 1024), (512, 512, 4096), (300, 300, 300), (2048, 256, 1024)]:
-        assert binding.variant_name(M, N, K) == "t32x32x64k4/nn/a16", (M, N, K)
-    for M, N, K in [(1024, 1024, 1024), (2048, 2048, 2048), (1280, 1280, 1280)]:
-        assert not binding.variant_name(M, N, K).startswith("t32x32x64k4"), (M, N, K)
+        tile, layout, align = binding.variant_name(M, N, K).split("/")
+        assert tile in ("t32x32x64k4", "t64x32x64k4", "t32x64x64k4") and (layout, align) == ("nn", "a16"), (M, N, K)
+    for M, N, K in [(2048, 2048, 2048), (1280, 1280, 1280), (4096, 4096, 4096)]:
+        assert "k4" not in binding.variant_name(M, N, K), (M, N, K)
     assert binding.variant_name(4096, 32, 4096).startswith("t32x32x64k4")
     assert binding.variant_name(8192, 8, 8192).startswith("t128x32x32")            # B stored K x 8: masked element-wise
     assert binding.variant_name(8192, 8, 8192, transB=True).startswith("t32x32x64k4")
@@ -124,3 +125,22 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     assert binding.variant_name(32, 4096, 4096).startswith("t32x32x64k4")
     for M, N, K in [(32, 4096, 4096), (1, 8192, 8192), (16, 11008, 4096)]:
         assert binding.variant_name(M, N, K, transB=True).startswith("t32x32x64k4"), (M, N, K)
+
+
+def test_block_tails_are_planned_only_for_tiles_that_have_the_block_kernel():
+    """The last round is cut into 32 x 32 blocks only for tile shapes whose kernel contains the block
+    path (four waves that each own blocks); the tiles whose waves share the slabs split it along K."""
+    import os
+    import random
+    rng = random.Random(5)
+    with_blocks = {"t64x64x32", "t64x64x64", "t128x64x32", "t64x128x32", "t128x32x32", "t32x128x32"}
+    try:
+        for tile in range(13):
+            os.environ["GEMMF32_FORCE_TILE"] = str(tile)
+            for _ in range(400):
+                M, N, K = rng.randint(1, 3000), rng.randint(1, 3000), rng.randint(1, 5000)
+                name = binding.variant_name(M, N, K, transB=rng.random() < 0.5)
+                if "/quad" in name:
+                    assert name.split("/")[0] in with_blocks, (M, N, K, name)
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE", None)

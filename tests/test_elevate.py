@@ -334,7 +334,8 @@ def test_default_strategy_reproduces_the_dispatch_choice(M, N, K):
     else:
         assert s.split_k == 1
     assert s.tiles_m == -(-M // s.bm) and s.tiles_n == -(-N // s.bn)
-    grid = {(128, 32): (4, 1, 1), (32, 128): (1, 4, 1), (32, 32): (1, 1, 4)}.get((s.bm, s.bn), (2, 2, 1))   # waves per workgroup
+    grid = {(128, 32): (4, 1, 1), (32, 128): (1, 4, 1), (32, 32): (1, 1, 4), (64, 32): (1, 1, 4),
+            (32, 64): (1, 1, 4)}.get((s.bm, s.bn), (2, 2, 1))                                                # waves per workgroup
     assert (s.waves_m, s.waves_n, s.waves_k, s.wave_m, s.wave_n) == (*grid, s.bm // grid[0], s.bn // grid[1])
     assert s.k_range % s.bk == 0 and s.split_k * s.k_range >= K > (s.split_k - 1) * s.k_range
     # same text, same result

@@ -20,10 +20,10 @@ from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 NTHREADS = min(16, os.cpu_count() or 1)
 TILES = {"t256": "0", "t128": "1", "t64": "2", "tb64": "3", "t256x128": "4", "t128x256": "5", "t128x64": "6",
-         "t64x128": "7", "t128x32": "8", "t32x128": "9", "tq32": "10"}
+         "t64x128": "7", "t128x32": "8", "t32x128": "9", "tq32": "10", "tq64x32": "11", "tq32x64": "12"}
 TILE_DIMS = {"t256": (256, 256), "t128": (128, 128), "t64": (64, 64), "tb64": (64, 64), "t256x128": (256, 128),
              "t128x256": (128, 256), "t128x64": (128, 64), "t64x128": (64, 128),
-             "t128x32": (128, 32), "t32x128": (32, 128), "tq32": (32, 32)}
+             "t128x32": (128, 32), "t32x128": (32, 128), "tq32": (32, 32), "tq64x32": (64, 32), "tq32x64": (32, 64)}
 
 
 def dev(x: np.ndarray):
@@ -538,7 +538,7 @@ def test_shutdown_releases_workspace_and_library_stays_usable():
 # --------------------------------------------------------------------- split tail (uneven tile counts)
 
 @pytest.mark.parametrize("tile,how", [("t128", "tail"), ("t64", "tail"), ("tb64", "tail"), ("t64", "quad"), ("tb64", "quad"),
-                                      ("t128x64", "quad"), ("t64x128", "quad"), ("tq32", "tail")])
+                                      ("t128x64", "quad"), ("t64x128", "quad"), ("tq32", "tail"), ("tq64x32", "tail"), ("tq32x64", "tail")])
 @pytest.mark.parametrize("transB", [False, True])
 def test_split_tail_bit_exact(force_tile, tile, how, transB):
     """More tiles than one round of 256, with a small remainder.  "tail": the remainder's tiles are cut
@@ -550,7 +550,8 @@ def test_split_tail_bit_exact(force_tile, tile, how, transB):
         os.environ["GEMMF32_NO_QUAD"] = "1"
     shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
               "tb64": [(1000, 1030, 999), (1100, 1100, 1100)], "t128x64": [(2100, 1090, 700), (2200, 1000, 333)],
-              "t64x128": [(1090, 2100, 700)], "tq32": [(520, 530, 3000), (576, 570, 4100)]}[tile]
+              "t64x128": [(1090, 2100, 700)], "tq32": [(520, 530, 3000), (576, 570, 4100)], "tq64x32": [(770, 760, 2100), (1030, 520, 3000)],
+              "tq32x64": [(770, 760, 2100), (1030, 520, 3000)]}[tile]
     try:
         _split_tail_cases(shapes, how, transB)
     finally:
