@@ -26,11 +26,11 @@ HBM_GBS = 8000.0
 # of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
 # one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "e6f4d2ad2d4b71ca122eb96859e430651ab7caeec8911c0b86c097da46c703f0",
-    "square4096": {"fetch_kib": 196784.1, "write_kib": 65536.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
-    "square1024": {"fetch_kib": 14412.5, "write_kib": 4096.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
-    "batched64": {"fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
-    "skinny8192": {"fetch_kib": 135747.9, "write_kib": 1024.0, "copy_fetch_kib": 32818.3, "copy_write_kib": 65536.0},
+    "sources_sha256": "9ee5481b050d08411a16aceb989947d960fb2943a57029e41f3f5ef2ecff8bf5",
+    "square4096": {"fetch_kib": 196791.6, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "square1024": {"fetch_kib": 12354.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "batched64": {"fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "skinny8192": {"fetch_kib": 135464.4, "write_kib": 1024.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 
