@@ -24,13 +24,15 @@ HBM_GBS = 8000.0
 # HBM traffic of the dominant kernel, from rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per
 # dispatch; summaries under profiles/).  Each is scaled by what the same counter reads for a plain copy
 # of known size (pack_b of a row-major 4096x4096 B: 65536 KiB in, 65536 KiB out).  The figures belong to
-# one version of the kernel sources: when the hash below no longer matches, traffic is reported as null.
+# one version of the device code and to the kernel variant the dispatch ran when they were taken: when the
+# hash of the kernel headers below no longer matches, or the dispatch now picks another variant for the
+# workload, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "9ee5481b050d08411a16aceb989947d960fb2943a57029e41f3f5ef2ecff8bf5",
-    "square4096": {"fetch_kib": 196791.6, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
-    "square1024": {"fetch_kib": 12354.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
-    "batched64": {"fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
-    "skinny8192": {"fetch_kib": 135464.4, "write_kib": 1024.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "sources_sha256": "cbcec089c0c3e7ac72ec1ae9436755ab8570962f44804cc16a4d2f186d3c46ff",
+    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196791.6, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "square1024": {"variant": "t64x32x64k4/nn/a16", "fetch_kib": 12354.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "batched64": {"variant": None, "fetch_kib": 65567.0, "write_kib": 65536.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
+    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135464.4, "write_kib": 1024.0, "copy_fetch_kib": 32817.5, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 
@@ -38,7 +40,7 @@ COPY_KIB = 65536.0
 SETTLE_S = 0.08        # untimed launches before the warm-up steps, see Runner.time
 
 
-KERNEL_SOURCES = ("gemm_f32.hip", "gemm_launch.hpp", "gemm_kernels.hpp")    # what the measured kernels are built from
+KERNEL_SOURCES = ("gemm_launch.hpp", "gemm_kernels.hpp")    # the device code the measured kernels are built from
 
 
 def kernel_sources_sha256() -> str:
@@ -51,9 +53,18 @@ def kernel_sources_sha256() -> str:
     return h.hexdigest()
 
 
+def workload_variant(workload: str):
+    """The kernel variant the dispatch runs for a workload (None: the batched streaming kernel, which has one)."""
+    from paper_2002_02268_amd import binding, synth
+    w = synth.WORKLOADS[workload]
+    if w["batch"]:
+        return None
+    return binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"])
+
+
 def traffic_bytes(workload: str):
     t = TRAFFIC.get(workload)
-    if not t or TRAFFIC["sources_sha256"] != kernel_sources_sha256():
+    if not t or TRAFFIC["sources_sha256"] != kernel_sources_sha256() or t["variant"] != workload_variant(workload):
         return None
     fetch = t["fetch_kib"] * COPY_KIB / t["copy_fetch_kib"]
     write = t["write_kib"] * COPY_KIB / t["copy_write_kib"]

@@ -240,7 +240,7 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
                            int64_t K, int bmode, int amode)
 {
     Choice best = {TB64, 1};
-    double best_cost = -1;
+    double best_cost = -1, best_area = 0;
     for (const auto &c : kCandidates) {
         if (forced_tile >= 0 && c.id != forced_tile) continue;
         // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
@@ -294,7 +294,14 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             cost = std::max(cost, hbm_us) + 0.02 * cost;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             if (S == 1) cost -= plan_tail_split(hooks, c.id, batch, tiles, K).benefit_us;
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {c.id, S}; }
+            // equal cost (the two orientations of a tile on the same number of rounds): the one that
+            // computes less padding
+            const double area = (double)wgs * sh.bm * sh.bn;
+            if (best_cost < 0 || cost < best_cost || (cost == best_cost && area < best_area)) {
+                best_cost = cost;
+                best_area = area;
+                best = {c.id, S};
+            }
             if (forced_split >= 1) break;
         }
     }

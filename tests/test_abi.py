@@ -91,6 +91,13 @@ def test_traffic_figures_are_dropped_when_the_kernel_sources_change():
         assert t is not None and 4 * 3 * 4096 * 4096 <= t < 4 * 4 * 3 * 4096 * 4096   # between 1x and 4x the compulsory bytes
         bench.TRAFFIC["sources_sha256"] = "0" * 64
         assert bench.traffic_bytes("square4096") is None
+        # ... and only while the dispatch still runs the variant they were taken on
+        bench.TRAFFIC["sources_sha256"] = current
+        variant = bench.TRAFFIC["square4096"]["variant"]
+        assert variant == bench.workload_variant("square4096")
+        bench.TRAFFIC["square4096"]["variant"] = "t128x128x16/nn/a16"
+        assert bench.traffic_bytes("square4096") is None
+        bench.TRAFFIC["square4096"]["variant"] = variant
     finally:
         bench.TRAFFIC["sources_sha256"] = saved
 
