@@ -117,7 +117,7 @@ const VariantModel kCandidates[] = {
     {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
     {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
     {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120},
-    {TQ32, 0.775, 0.775, 700, 100},   {TQ64x32, 0.87, 0.86, 350, 80},   {TQ32x64, 0.87, 0.86, 350, 80}};
+    {TQ32, 0.775, 0.775, 700, 200},   {TQ64x32, 0.87, 0.86, 350, 80},   {TQ32x64, 0.87, 0.86, 350, 80}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -276,6 +276,10 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             }
             const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
             const int64_t wgs = tiles * S;
+            // two workgroups of the two-block shared-slab tiles fit a compute unit; measured, they pay while all
+            // of them are resident at once (1024^3: 512 workgroups, 19.3 us) and not beyond (648 x 3072 x 752:
+            // 1008 workgroups, 42 us against 31 for 64 x 128 tiles)
+            if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && wgs > 512) continue;
             double cost = (double)cdiv(wgs, 256) * tile_us(c, sh.bm, sh.bn, k_range, wgs > 256);
             // what a launch pays once (start-up, first loads, last stores) is part of the single-round
             // overhead; with several rounds it is still paid once, on top of the per-round overheads
