@@ -13,7 +13,10 @@
  *     (fun img (map2D (fun nbh (reduce add 0 (map mult (zip (join weights2d) (join nbh)))))
  *                     (slide2D 3 1 (pad2D 1 img))))
  *   loop nests over the product's axes (stand-in for the RISE program of Section 6.3):
- *     (loop AXIS EXTENT KIND body), AXIS in M N K, KIND in seq grid wave unroll slab,
+ *     (loop AXIS EXTENT KIND body), AXIS in M N K, KIND in seq grid wave unroll slab share
+ *     (grid: over workgroups; wave: over the waves of a workgroup; unroll: register blocks of a wave;
+ *      slab: the K loop staged through LDS; share: a K loop inside a slab whose iterations the waves
+ *      of a workgroup take side by side, adding their sums at the end),
  *     leaves mac (one multiply-accumulate) and mfma32x32x2 (one matrix instruction)
  * Strategies:
  *   id fail (seq s ...) (lChoice s ...) (try s) (repeat s)                       Section 3.4
