@@ -208,6 +208,70 @@ def ladder(torch, binding, synth):
     return out
 
 
+SURVEY_SHAPES = (
+    [(n, n, n, False) for n in (256, 384, 512, 640, 768, 896, 1100, 1152, 1280, 1408, 1536, 1792, 2048, 2560, 3072,
+                                3584, 4096, 5120, 6144, 8192)] +
+    [(640, 640, 2048, False), (512, 512, 4096, False), (256, 256, 8192, False), (1024, 1024, 4000, False),
+     (2048, 2048, 512, False), (4096, 4096, 256, False), (8192, 8192, 64, False), (128, 16384, 4096, False),
+     (16384, 128, 4096, False), (64, 8192, 8192, False), (256, 4096, 4096, False), (4096, 256, 4096, False),
+     (100, 100, 100, False), (300, 300, 300, False), (2000, 2000, 2000, False), (3000, 3000, 3000, False),
+     (1024, 4096, 1024, False), (8192, 1024, 128, False), (333, 4096, 777, False), (128, 128, 65536, False),
+     (1, 1, 1000000, False), (8192, 8, 8192, False), (32, 32000, 4096, False),
+     (16, 11008, 4096, True), (4, 4096, 11008, True), (1, 8192, 8192, True), (128, 16384, 4096, True),
+     (512, 4096, 4096, True), (2048, 11008, 4096, True), (4096, 4096, 4096, True), (1024, 1024, 1024, True),
+     (64, 64, 65536, True)])
+
+
+def survey(torch, binding, synth, random_shapes=40, seed=3):
+    """Shape coverage beyond the benchmark workloads: per shape, the time of one gemm_f32 launch and, for
+    context, of torch.matmul (the vendor library) on the same operands: the best of three windows of back
+    to back launches between two events.  Fixed shapes above, then seeded random ones (M, N log-uniform in
+    32..4096, K in 64..8192, either layout of B).  U(-1,1) operands from torch's generator: only times are
+    reported, parity is the tests' business."""
+    import math
+    import random
+    rng = random.Random(seed)
+    shapes = list(SURVEY_SHAPES)
+    while len(shapes) < len(SURVEY_SHAPES) + random_shapes:
+        M, N, K = (int(round(math.exp(rng.uniform(math.log(a), math.log(b))))) for a, b in ((32, 4096), (32, 4096), (64, 8192)))
+        if 2.0 * M * N * K <= 4e10:
+            shapes.append((M, N, K, rng.random() < 0.5))
+
+    def best_ms(fn, flops):
+        reps = int(max(20, min(200, 2e10 / max(flops, 1.0))))
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            per.append(a.elapsed_time(b) / reps)
+        return min(per)
+
+    torch.manual_seed(seed)
+    rows = []
+    for M, N, K, tB in shapes:
+        A = torch.rand(M, K, device="cuda") * 2 - 1
+        B = (torch.rand(N, K, device="cuda") if tB else torch.rand(K, N, device="cuda")) * 2 - 1
+        C = torch.empty(M, N, device="cuda")
+        Bm = B.T if tB else B
+        ours = best_ms(lambda: binding.gemm_f32(A, B, C, transB=tB), 2.0 * M * N * K)
+        vendor = best_ms(lambda: torch.matmul(A, Bm), 2.0 * M * N * K)
+        rows.append({"M": M, "N": N, "K": K, "transB": tB, "variant": binding.variant_name(M, N, K, transB=tB),
+                     "us": round(ours * 1e3, 2), "torch_matmul_us": round(vendor * 1e3, 2),
+                     "ratio": round(ours / vendor, 3)})
+        del A, B, C
+    ratios = [r["ratio"] for r in rows]
+    geo = math.exp(sum(math.log(x) for x in ratios) / len(ratios))
+    return {"survey": rows, "fixed_shapes": len(SURVEY_SHAPES), "random_shapes": random_shapes, "seed": seed,
+            "geomean_ratio": round(geo, 3), "worst_ratio": max(ratios), "best_ratio": min(ratios)}
+
+
 def protocol(torch, binding, synth):
     """Every workload timed the long way: 10 warm-up launches, then windows of R back-to-back launches
     between two events on the launch stream (R sized for a window of at least 50 ms, at least 100
@@ -306,6 +370,9 @@ def main() -> int:
     ap.add_argument("--ladder-pass", action="store_true",
                     help="run every ladder level --steps times on --workload (square1024 or square4096), untimed: "
                          "the program that the counter runs of the ladder profile attach to")
+    ap.add_argument("--survey", action="store_true",
+                    help="time gemm_f32 and, for context, torch.matmul on about 100 shapes beyond the benchmark "
+                         "workloads (fixed list plus seeded random shapes); one JSON object")
     ap.add_argument("--protocol", action="store_true",
                     help="time every workload in 20 windows of at least 50 ms (median and best), the latency of one "
                          "square1024 launch, and the batched workload with operands streamed from HBM; one JSON object")
@@ -341,6 +408,10 @@ def main() -> int:
 
     if args.ladder:
         print(json.dumps(ladder(torch, binding, synth)))
+        return 0
+
+    if args.survey:
+        print(json.dumps(survey(torch, binding, synth)))
         return 0
 
     if args.ladder_pass:

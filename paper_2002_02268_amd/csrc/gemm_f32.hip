@@ -252,18 +252,22 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         // applies it replaces the other 32-wide tiles (fewer or no K ranges over workgroups, so no or
         // a smaller second pass): measured 5-20 % faster on such shapes.
         const bool narrow_n = N <= 32 && amode == A_MK && (bmode != B_NN || N == 32) && M >= 1024;
-        const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024;
+        // (a B stored K x N is read in panels of 32 columns, 128 bytes per row: fine from the memory-side
+        // cache, slower than the 128-column tile once B is larger than that cache and streams from HBM:
+        // 32 x 32000 x 4096: 125 us against 96)
+        const bool b_streams_narrow = bmode == B_NN && M <= 32 && 4.0 * (double)K * (double)N > 268435456.0;
+        const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024 && !b_streams_narrow;
         const bool kshare = batch == 1 && (narrow_n || narrow_m);
         if (forced_tile < 0 && c.id != TQ32 && kshare) continue;
         // It also competes on any single product at least 32 x 32: a few hundred blocks occupy the chip
         // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
         // 11.7 instead of 19.4 us).
         const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !hooks.no_kshare;
-        if (forced_tile < 0 && c.id == TQ32 && !kshare && !kshare_general) continue;
+        if (forced_tile < 0 && c.id == TQ32 && ((!kshare && !kshare_general) || b_streams_narrow)) continue;
         // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
         // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
         // 21 -> 18.3 us).
-        if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && (kshare || !kshare_general)) continue;
+        if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && (kshare || !kshare_general || b_streams_narrow)) continue;
         const TileShape &sh = kShapes[c.id];
         const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
