@@ -259,10 +259,10 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024 && !b_streams_narrow;
         const bool kshare = batch == 1 && (narrow_n || narrow_m);
         if (forced_tile < 0 && c.id != TQ32 && kshare) continue;
-        // It also competes on any single product at least 32 x 32: a few hundred blocks occupy the chip
+        // It also competes on any product at least 32 x 32: a few hundred blocks occupy the chip
         // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
         // 11.7 instead of 19.4 us).
-        const bool kshare_general = batch == 1 && M >= 32 && N >= 32 && !hooks.no_kshare;
+        const bool kshare_general = M >= 32 && N >= 32 && !hooks.no_kshare;   // batched products too (they cannot split K)
         if (forced_tile < 0 && c.id == TQ32 && ((!kshare && !kshare_general) || b_streams_narrow)) continue;
         // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
         // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
