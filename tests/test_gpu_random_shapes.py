@@ -71,3 +71,30 @@ def test_random_shapes_bit_exact(cls):
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
         os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+def test_random_batched_shapes_bit_exact():
+    """Batched products on seeded random shapes and batch counts, either layout of B, the dispatch's own
+    tile and forced ones (small outputs with long K take the tiles whose waves share the slabs, since a
+    batched product cannot split K): integer operands, exact against a loop of single oracle products."""
+    rng = np.random.default_rng(21)
+    tiles = [None, None] + list(TILES.values())
+    try:
+        for idx in range(30):
+            batch = int(rng.integers(2, 40))
+            M, N, K = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 2500))
+            tB = bool(rng.random() < 0.5)
+            tile = tiles[int(rng.integers(0, len(tiles)))]
+            print(f"case batched[{idx}] batch={batch} M={M} N={N} K={K} tB={tB} tile={tile}", flush=True)
+            A = synth.small_ints((batch, M, K), 9500 + idx, synth.TENSOR_A, lo=-3, hi=3)
+            B = synth.small_ints((batch, N, K) if tB else (batch, K, N), 9500 + idx, synth.TENSOR_B, lo=-3, hi=3)
+            ref = oracle.gemm_f32_batched(A, B, transB=tB, nthreads=NTHREADS)
+            dC = torch.full((batch, M, N), float("nan"), device="cuda")
+            if tile is None:
+                os.environ.pop("GEMMF32_FORCE_TILE", None)
+            else:
+                os.environ["GEMMF32_FORCE_TILE"] = tile
+            binding.gemm_f32_batched(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, transB=tB)
+            assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE", None)
