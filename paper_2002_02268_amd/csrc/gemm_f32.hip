@@ -262,7 +262,9 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         // It also competes on any product at least 32 x 32: a few hundred blocks occupy the chip
         // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
         // 11.7 instead of 19.4 us).
-        const bool kshare_general = M >= 32 && N >= 32 && !hooks.no_kshare;   // batched products too (they cannot split K)
+        // (batched products too: they cannot split K; and batches of products no larger than one block,
+        // where a 64 x 64 tile would compute four times the padding: 4096 x 16x16x64 29 -> 20 us)
+        const bool kshare_general = ((M >= 32 && N >= 32) || (batch > 1 && M <= 32 && N <= 32)) && !hooks.no_kshare;
         if (forced_tile < 0 && c.id == TQ32 && ((!kshare && !kshare_general) || b_streams_narrow)) continue;
         // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
         // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
