@@ -236,7 +236,7 @@ template <class T, int EDGE_MODE>
 __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int batch, const int tm, const int tn)
 {
     constexpr bool SHIFTED = (EDGE_MODE == 3);
-    constexpr int EDGE = SHIFTED ? 0 : (EDGE_MODE == 4 ? 1 : EDGE_MODE);   // how the loads treat the boundaries
+    constexpr int EDGE = SHIFTED ? 0 : (EDGE_MODE == 4 ? 1 : (EDGE_MODE == 5 ? 2 : EDGE_MODE));   // how the loads treat the boundaries
     constexpr bool RANGED = (EDGE_MODE == 1 && T::AMODE == A_MK);           // boundaries masked by the descriptors' ranges
     constexpr bool BUF = (EDGE == 0) || RANGED;                            // buffer addressing
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, G = T::G;
@@ -246,7 +246,10 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     constexpr int A_F4_ROW = T::A_F4_ROW, B_F4_ROW = T::B_F4_ROW;
     constexpr bool B_KMAJOR = (T::BMODE == B_NT);           // B fragments are 4 consecutive k of one column
     constexpr int NBV = B_KMAJOR ? NB : 4;   // B fragment vectors per 8-column group
-    constexpr bool B_ELEMENTWISE = (T::BMODE == B_NN && EDGE == 2);
+    // mode 5: as mode 2, for an N that is a multiple of 4: a 16-byte slot of B stored K x N then lies either
+    // wholly inside a row or wholly beyond column N, so B is loaded 16 bytes at a time and masked per slot
+    constexpr bool B_SLOTWISE = (T::BMODE == B_NN && EDGE_MODE == 5);
+    constexpr bool B_ELEMENTWISE = (T::BMODE == B_NN && EDGE == 2 && !B_SLOTWISE);
     constexpr bool A_KMAJOR = (T::AMODE == A_MK);           // A fragments are 4 consecutive k of one row
     constexpr int NAV = A_KMAJOR ? MB : 4;                  // A fragment vectors per 8-column group
     constexpr bool A_ELEMENTWISE = (!A_KMAJOR && EDGE != 0);
@@ -327,7 +330,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             const int gj = n0 + c;
             b_col[r] = gj;
             b_ok[r] = (gj < N);
-            const int gjc = (gj < N) ? gj : (N - 1);
+            const int gjc = (gj < N) ? gj : (B_SLOTWISE ? 0 : N - 1);   // slot-wise: the 16 bytes read stay inside the row
             pb[r] = B + (int64_t)row * p.ldb + gjc;
 #pragma unroll
             for (int e = 0; e < 4; ++e) b_d[r][e] = ((gj + e < N) ? (gj + e) : (N - 1)) - gjc;
@@ -447,7 +450,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                     const bool ok = A_ELEMENTWISE ? (a_col[S] + e < M) : a_ok[S];
                     v[e] = ok ? v[e] : 0.f;
                 }
-            } else if constexpr (B_ELEMENTWISE || T::BMODE != B_NN) {
+            } else if constexpr (B_ELEMENTWISE || B_SLOTWISE || T::BMODE != B_NN) {
                 constexpr int r = S - A_ITERS;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -794,7 +797,15 @@ __device__ __forceinline__ void run_tile(const KArgs &q, float *lds, int batch, 
     const bool can_shift = (!m_edge || q.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && q.N >= T::BN));
     if (!m_edge && !n_edge && offsets_fit_32) gemm_tile<T, 0>(q, lds, batch, tm, tn);
     else if (can_shift && (m_edge || n_edge) && offsets_fit_32) gemm_tile<T, 3>(q, lds, batch, tm, tn);
-    else if (T::BMODE == B_NN && n_edge) gemm_tile<T, 2>(q, lds, batch, tm, tn);
+    else if (T::BMODE == B_NN && n_edge) {
+        if constexpr (T::BMODE == B_NN && T::BN <= 32) {
+            if (q.N % 4 == 0) {
+                gemm_tile<T, 5>(q, lds, batch, tm, tn);
+                return;
+            }
+        }
+        gemm_tile<T, 2>(q, lds, batch, tm, tn);
+    }
     else if (T::AMODE != A_MK || offsets_fit_32) gemm_tile<T, 1>(q, lds, batch, tm, tn);
     else if constexpr (T::AMODE == A_MK) gemm_tile<T, 4>(q, lds, batch, tm, tn);
 }

@@ -98,3 +98,37 @@ def test_random_batched_shapes_bit_exact():
             assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
     finally:
         os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+def test_narrow_b_stored_k_by_n_bit_exact():
+    """Outputs narrower than a 32-wide tile with B stored K x N (rows of N floats, NaN behind them): for
+    N a multiple of 4 the 32-wide tiles load B 16 bytes at a time and mask whole slots, otherwise
+    element by element; nothing beyond column N may be read into the sum or written."""
+    rng = np.random.default_rng(31)
+    tiles = [None, None, TILES["t128x32"], TILES["tq32"], TILES["tq64x32"], TILES["t64"]]
+    try:
+        for idx in range(48):
+            N = int(rng.choice([4, 8, 12, 16, 20, 24, 28, 32, 36, 44, 6, 17, 31, 1, 3]))
+            M = int(rng.choice([rng.integers(1, 40), rng.integers(1, 3000), rng.integers(1024, 5000)]))
+            K = int(rng.integers(1, 2500))
+            tA = bool(rng.random() < 0.3)
+            alpha, beta = float(rng.choice([1.0, -2.0, 0.5])), float(rng.choice([0.0, 1.0, -0.5]))
+            tile = tiles[int(rng.integers(0, len(tiles)))]
+            print(f"case narrow[{idx}] M={M} N={N} K={K} tA={tA} alpha={alpha} beta={beta} tile={tile}", flush=True)
+            A = synth.small_ints((K, M) if tA else (M, K), 9700 + idx, synth.TENSOR_A, lo=-3, hi=3)
+            B = synth.small_ints((K, N), 9700 + idx, synth.TENSOR_B, lo=-3, hi=3)
+            C0 = synth.small_ints((M, N), 9700 + idx, TENSOR_C, lo=-5, hi=5)
+            ref = oracle.gemm_f32_ex(A, B, C0, alpha, beta, tA, False, nthreads=NTHREADS)
+            dA, _ = padded_dev(A, int(rng.choice([0, 3, 8])))
+            dB, _ = padded_dev(B, int(rng.choice([0, 1, 4, 7])))
+            dC, bufC = padded_dev(C0, int(rng.choice([0, 5])))
+            if tile is None:
+                os.environ.pop("GEMMF32_FORCE_TILE", None)
+            else:
+                os.environ["GEMMF32_FORCE_TILE"] = tile
+            binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, False)
+            whole = bufC.cpu().numpy()
+            assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+            assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE", None)
