@@ -176,6 +176,8 @@ void gemm_f32_shutdown(void);
  *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
  *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
  *   GEMMF32_NO_QUAD=1          split the last round along K only, never into 32 x 32 blocks
+ *   GEMMF32_NO_THIN=1          never the vector-unit kernel for products with at most 4 rows or columns
+ *   GEMMF32_FORCE_THIN=1       that kernel wherever it can run (at most 8 rows or columns, both operands with k contiguous)
  *   GEMMF32_NO_KSHARE=1        the 32x32x64 tile only for outputs at most 32 wide, not for outputs of a few hundred blocks
  * gemm_f32_scheduled (elevate.h) is the interface for choosing tile and split per call.
  */

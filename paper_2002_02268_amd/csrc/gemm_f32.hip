@@ -139,13 +139,13 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 // second pass.  Better than K ranges when K is short (the second pass costs a fixed 10 us).
 // The test hooks of the environment, read once per call (every lookup scans the whole environment).
 struct Hooks {
-    bool no_tail_split, no_quad, no_kshare;
+    bool no_tail_split, no_quad, no_kshare, no_thin;
     int force_tile, force_split;       // -1: not forced
 };
 Hooks read_hooks()
 {
     Hooks h = {std::getenv("GEMMF32_NO_TAIL_SPLIT") != nullptr, std::getenv("GEMMF32_NO_QUAD") != nullptr,
-               std::getenv("GEMMF32_NO_KSHARE") != nullptr, -1, -1};
+               std::getenv("GEMMF32_NO_KSHARE") != nullptr, std::getenv("GEMMF32_NO_THIN") != nullptr, -1, -1};
     if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
         const int t = std::atoi(f);
         if (t >= 0 && t < NUM_TILES) h.force_tile = t;
@@ -340,6 +340,7 @@ struct Plan {
     int tail_tiles;      // tiles of the last round that are split along K (0: none)
     int64_t user_ldc;    // leading dimension of the caller's C (args.ldc is the workspace's when split)
     bool vec;
+    int thin;            // 0: tiles; 1: at most 8 rows, B streamed by the vector-unit kernel; 2: at most 8 columns, A streamed
     KArgs args;
 };
 
@@ -407,6 +408,19 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     const Choice ch = choose_tile(hooks, batch, M, N, K, bmode, amode);
     pl.tile = ch.tile;
     pl.split = ch.split;
+    // At most 4 rows or columns, both operands with k contiguous, a long side too short to give 256 blocks of
+    // 32 and a long operand of at least 128 MB: streamed by the vector-unit kernel instead of 32-wide tiles
+    // with K ranges and a second pass (4 x 4096 x 11008: 28.4 instead of 32.4 us).  Measured slower for
+    // shorter operands (the tiles' second pass is cheap against the launch) and for 5 to 8 rows (the short
+    // operand's loads through the caches then outweigh the stream).
+    pl.thin = 0;
+    if (batch == 1 && bmode == B_NT && amode == A_MK && K >= 1 && !hooks.no_thin && hooks.force_tile < 0 &&
+        hooks.force_split < 0 && g_forced_tile < 0 && g_forced_split < 0) {
+        const bool force_thin = std::getenv("GEMMF32_FORCE_THIN") != nullptr;       // test hook: whenever it can run
+        if (M <= 8 && N >= 64 && (force_thin || (M <= 4 && N < 8192 && N * K >= (32LL << 20)))) pl.thin = 1;
+        else if (N <= 8 && M >= 64 && (force_thin || (N <= 4 && M < 8192 && M * K >= (32LL << 20)))) pl.thin = 2;
+    }
+    if (pl.thin != 0) pl.split = 1;             // the arguments below stay those of the whole product
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
     const int64_t tiles_m = cdiv(M, bm), tiles_n = cdiv(N, bn);
     const int64_t total = (pl.split > 1 ? pl.split : batch) * tiles_m * tiles_n;
@@ -441,7 +455,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     // Split tail: when the last round of tiles would leave most compute units idle, its tiles are
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
     // 16 become 256 pieces that run beside the full round).
-    if (pl.split == 1) {
+    if (pl.split == 1 && pl.thin == 0) {
         const TailSplit ts = plan_tail_split(hooks, pl.tile, batch, total, K);
         if (ts.pieces > 1) {
             a.tail_first = (int)(total - ts.tail);
@@ -497,10 +511,46 @@ int launch_splitk_reduce(const float *W, float *C, int M, int N, int64_t ldc, in
     return GEMMF32_OK;
 }
 
+template <int S> int launch_thin_s(const ThinArgs &t)
+{
+    hipLaunchKernelGGL(thin_nt_kernel<S>, dim3((unsigned)cdiv(t.rows, kThinRowsPerWorkgroup)), dim3(256), 0, g_stream, t);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e);
+    return GEMMF32_OK;
+}
+
+int launch_thin(const Plan &pl)
+{
+    const KArgs &a = pl.args;
+    ThinArgs t;
+    t.K = a.K;
+    t.alpha = pl.alpha;
+    t.beta = pl.beta;
+    t.C = a.C;
+    int small;
+    if (pl.thin == 1) {          // C[m][n]: n runs over the streamed rows of B
+        t.X = a.B; t.ldx = a.ldb; t.rows = a.N; t.Y = a.A; t.ldy = a.lda; t.c_big = 1; t.c_small = pl.user_ldc; small = a.M;
+    } else {                     // m runs over the streamed rows of A
+        t.X = a.A; t.ldx = a.lda; t.rows = a.M; t.Y = a.B; t.ldy = a.ldb; t.c_big = pl.user_ldc; t.c_small = 1; small = a.N;
+    }
+    switch (small) {
+    case 1: return launch_thin_s<1>(t);
+    case 2: return launch_thin_s<2>(t);
+    case 3: return launch_thin_s<3>(t);
+    case 4: return launch_thin_s<4>(t);
+    case 5: return launch_thin_s<5>(t);
+    case 6: return launch_thin_s<6>(t);
+    case 7: return launch_thin_s<7>(t);
+    case 8: return launch_thin_s<8>(t);
+    default: return GEMMF32_EINVAL;
+    }
+}
+
 int run_plan(const Plan &pl)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
+    if (pl.thin != 0) return launch_thin(pl);
     if (pl.split <= 1 && pl.tail_tiles > 0 && pl.args.quad == 0) {
         const TileShape &sh = kShapes[pl.tile];
         KArgs a = pl.args;
@@ -737,7 +787,9 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
-    if (pl.tail_tiles > 0 && pl.args.quad != 0)
+    if (pl.thin != 0)
+        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "thin%dx%d/nt", (int)(pl.thin == 1 ? M : N), kThinRows);
+    else if (pl.tail_tiles > 0 && pl.args.quad != 0)
         std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/quad%d", kShapes[pl.tile].name,
                       pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles);
     else if (pl.tail_tiles > 0)

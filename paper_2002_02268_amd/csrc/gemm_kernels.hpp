@@ -861,6 +861,100 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     run_tile<T>(q, lds, batch, tm, tn);
 }
 
+// Products with at most 8 rows (or columns) whose two operands both have k contiguous (A stored M x K, B
+// stored N x K).  Such a product has 2 to 16 flop per byte of its long operand and is bound by reading
+// that operand once; the matrix instruction would spend 3/4 or more of its work on padding, and a 32-wide
+// tile gives too few workgroups unless K is split.  Here the long operand X (rows x K) is streamed: a wave
+// takes kThinRows consecutive rows, its lanes stride over k 16 bytes at a time (a wave reads 1 KB of a row
+// per request), multiply with the S rows of the short operand Y (read through the caches) in the vector
+// unit, and the 64 partial sums of every (row, s) pair are added by a fixed butterfly over the lanes, so the
+// result does not depend on the launch.  Element (r, s) goes to C[r * c_big + s * c_small].
+struct ThinArgs {
+    const float *X;
+    int64_t ldx;
+    int rows;
+    const float *Y;
+    int64_t ldy;
+    float *C;
+    int64_t c_big, c_small;
+    int K;
+    float alpha, beta;
+};
+constexpr int kThinRows = 4;                      // rows of X per wave
+constexpr int kThinRowsPerWorkgroup = 4 * kThinRows;
+
+template <int S> __global__ void __launch_bounds__(256) thin_nt_kernel(const ThinArgs p)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r0 = (blockIdx.x * 4 + wave) * kThinRows;
+    if (r0 >= p.rows) return;                      // whole waves leave together
+    const float *x[kThinRows];
+#pragma unroll
+    for (int j = 0; j < kThinRows; ++j) {
+        const int r = (r0 + j < p.rows) ? (r0 + j) : (p.rows - 1);      // rows past the end repeat the last one; not stored
+        x[j] = p.X + (int64_t)r * p.ldx;
+    }
+    float acc[S][kThinRows];
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int j = 0; j < kThinRows; ++j) acc[s][j] = 0.f;
+    const int k4 = p.K & ~3;                       // columns covered 16 bytes at a time
+    auto chunk = [&](int k) {                      // k + 3 < k4
+        v4f xv[kThinRows], yv[S];
+#pragma unroll
+        for (int j = 0; j < kThinRows; ++j) xv[j] = load4(x[j] + k);
+#pragma unroll
+        for (int s = 0; s < S; ++s) yv[s] = load4(p.Y + (int64_t)s * p.ldy + k);
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int j = 0; j < kThinRows; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[s][j] = __builtin_fmaf(yv[s][e], xv[j][e], acc[s][j]);
+    };
+    int k = lane * 4;
+    for (; k + 256 < k4; k += 512) {               // two requests per row in flight
+        chunk(k);
+        chunk(k + 256);
+    }
+    if (k < k4) chunk(k);
+    const int kt = k4 + lane;                      // the last K % 4 columns, one per lane
+    if (kt < p.K) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const float yv = p.Y[(int64_t)s * p.ldy + kt];
+#pragma unroll
+            for (int j = 0; j < kThinRows; ++j) acc[s][j] = __builtin_fmaf(yv, x[j][kt], acc[s][j]);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int j = 0; j < kThinRows; ++j) {
+            float v = acc[s][j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            acc[s][j] = v;
+        }
+    // lane s * kThinRows + j stores element (r0 + j, s)
+    if (lane < S * kThinRows) {
+        const int s = lane / kThinRows, j = lane % kThinRows;
+        float v = 0.f;
+#pragma unroll
+        for (int ss = 0; ss < S; ++ss)
+#pragma unroll
+            for (int jj = 0; jj < kThinRows; ++jj)
+                if (ss == s && jj == j) v = acc[ss][jj];
+        if (r0 + j < p.rows) {
+            float *dst = p.C + (int64_t)(r0 + j) * p.c_big + (int64_t)s * p.c_small;
+            float out = p.alpha * v;
+            if (p.beta != 0.f) out += p.beta * *dst;
+            *dst = out;
+        }
+    }
+}
+
 // Sums the K ranges of the split tail tiles in ascending k and stores them into C.
 // One wave per (tail tile, 256-element chunk of the tile), so that even a few tiles spread over the chip.
 static __global__ void __launch_bounds__(64) tail_reduce_kernel(const KArgs p, int BM, int BN)

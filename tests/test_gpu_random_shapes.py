@@ -132,3 +132,55 @@ def test_narrow_b_stored_k_by_n_bit_exact():
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
         os.environ.pop("GEMMF32_FORCE_TILE", None)
+
+
+def test_thin_products_vector_unit_kernel_bit_exact():
+    """Products with at most 8 rows or columns and both operands stored with k contiguous: the kernel
+    that streams the long operand through the vector unit, forced wherever it can run, on ragged row
+    counts (waves with fewer than four rows left), K around the 16-byte and 1 KB request sizes, NaN
+    behind every row of both operands, alpha / beta, padded C.  Exact on integer operands.  The last
+    case is one the dispatch sends there by itself."""
+    rng = np.random.default_rng(41)
+    os.environ["GEMMF32_FORCE_THIN"] = "1"
+    try:
+        for idx in range(40):
+            S = int(rng.integers(1, 9))
+            big = int(rng.choice([64, 65, 66, 67, 100, 257, 1000, 4099, int(rng.integers(64, 6000))]))
+            K = int(rng.choice([1, 2, 3, 4, 5, 255, 256, 257, 511, 512, 513, 1000, 2051, int(rng.integers(1, 6000))]))
+            M, N = (S, big) if rng.random() < 0.5 else (big, S)
+            alpha, beta = float(rng.choice([1.0, -2.0, 0.5])), float(rng.choice([0.0, 1.0, -0.5]))
+            name = binding.variant_name(M, N, K, transB=True)
+            print(f"case thin[{idx}] M={M} N={N} K={K} alpha={alpha} beta={beta} {name}", flush=True)
+            assert name == f"thin{S}x4/nt", name
+            A = synth.small_ints((M, K), 9800 + idx, synth.TENSOR_A, lo=-3, hi=3)
+            B = synth.small_ints((N, K), 9800 + idx, synth.TENSOR_B, lo=-3, hi=3)
+            C0 = synth.small_ints((M, N), 9800 + idx, TENSOR_C, lo=-5, hi=5)
+            ref = oracle.gemm_f32_ex(A, B, C0, alpha, beta, False, True, nthreads=NTHREADS)
+            dA, _ = padded_dev(A, int(rng.choice([0, 3, 8])))
+            dB, _ = padded_dev(B, int(rng.choice([0, 1, 4, 7])))
+            dC, bufC = padded_dev(C0, int(rng.choice([0, 5])))
+            binding.gemm_f32_ex(dA, dB, dC, alpha, beta, False, True)
+            whole = bufC.cpu().numpy()
+            assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+            assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+    finally:
+        os.environ.pop("GEMMF32_FORCE_THIN", None)
+    M, N, K = 3, 4100, 8200
+    assert binding.variant_name(M, N, K, transB=True) == "thin3x4/nt"
+    A = synth.small_ints((M, K), 9900, synth.TENSOR_A)
+    B = synth.small_ints((N, K), 9900, synth.TENSOR_B)
+    ref = oracle.gemm_f32(A, B, transB=True, nthreads=NTHREADS)
+    dC = torch.full((M, N), float("nan"), device="cuda")
+    binding.gemm_f32(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, transB=True)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+    # uniform operands: within the product's tolerance, and the same bits on every launch
+    A, B = synth.uniform((M, K), 9901, synth.TENSOR_A), synth.uniform((N, K), 9901, synth.TENSOR_B)
+    ref = oracle.gemm_f32(A, B, transB=True, nthreads=NTHREADS)
+    outs = []
+    for _ in range(3):
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, transB=True)
+        outs.append(dC.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    err = np.abs(outs[0].astype(np.float64) - ref).max()
+    assert err <= 1e-3 * (K / 1024.0) ** 0.5, err
