@@ -9,6 +9,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 import oracle  # noqa: E402
+import workload_refs  # noqa: E402
 from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 from test_gpu_parity import NTHREADS, check_close, dev, padded_dev  # noqa: E402
@@ -49,13 +50,18 @@ def test_ladder_level_integer_bit_exact(level):
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
 
 
-def test_ladder_levels_agree_on_square1024():
-    A, B = synth.make_operands("square1024")
-    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+@pytest.mark.parametrize("name", ["square1024", "square4096"])
+def test_ladder_levels_match_the_oracle_on_both_square_workloads(name):
+    """The two sizes the ladder is timed at: every element of every level against the oracle's fp64
+    product (computed once per size and shared with the product's own parity test)."""
+    w = synth.WORKLOADS[name]
+    A, B = workload_refs.operands(name)
+    ref = workload_refs.reference(name)
     dA, dB = dev(A), dev(B)
-    dBp = torch.empty(binding.pack_b_size(1024, 1024) // 4, device="cuda")
+    dBp = torch.empty(binding.pack_b_size(w["N"], w["K"]) // 4, device="cuda")
     binding.pack_b(dB, dBp)
     for level in range(7):
-        dC = torch.full((1024, 1024), float("nan"), device="cuda")
+        print(f"ladder {name} level={level}", flush=True)
+        dC = torch.full((w["M"], w["N"]), float("nan"), device="cuda")
         binding.gemm_f32_ladder(level, dA, dB, dC, dBp)
-        check_close(dC.cpu().numpy(), ref, 1024)
+        check_close(dC.cpu().numpy(), ref, w["K"])

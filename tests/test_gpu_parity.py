@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 import oracle  # noqa: E402
+import workload_refs  # noqa: E402
 from paper_2002_02268_amd import binding, synth  # noqa: E402
 
 NTHREADS = min(16, os.cpu_count() or 1)
@@ -257,11 +258,10 @@ def test_transpose_identity_on_gpu():
 # --------------------------------------------------------------------- the five workloads
 
 def test_workload_square1024_full_oracle():
-    A, B = synth.make_operands("square1024")
-    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    A, B = workload_refs.operands("square1024")
     dC = torch.full((1024, 1024), float("nan"), device="cuda")
     binding.gemm_f32(dev(A), dev(B), dC)
-    check_close(dC.cpu().numpy(), ref, 1024)
+    check_close(dC.cpu().numpy(), workload_refs.reference("square1024"), 1024)
 
 
 def test_workload_ragged_full_oracle_with_guards():
@@ -283,13 +283,9 @@ def test_workload_ragged_integer_bit_exact():
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
 
 
-def _sampled_rows_and_freivalds(A, B, C, transB, K, seed, scale=1.0, nrows=48):
-    """At sizes the O(n^3) oracle cannot cover in seconds: the oracle on seeded sample rows
-    (all columns), plus A(Bx) = Cx over the whole output in fp64."""
-    M = A.shape[0]
-    rows = np.unique(np.concatenate([[0, M - 1], (synth._bits24(seed, 7, nrows) % M)]))
-    ref = oracle.gemm_f32(np.ascontiguousarray(A[rows]), B, transB=transB, nthreads=NTHREADS)
-    check_close(C[rows], ref, K, scale)
+def _vector_check(A, B, C, transB, K, seed, scale=1.0):
+    """A(Bx) = Cx over the whole output, both sides in fp64 on the host: O(n^2), independent of the
+    O(n^3) oracle."""
     N = C.shape[1]
     x = synth.signs(N, seed)
     Bx = (B.astype(np.float64).T @ x) if transB else (B.astype(np.float64) @ x)
@@ -298,13 +294,16 @@ def _sampled_rows_and_freivalds(A, B, C, transB, K, seed, scale=1.0, nrows=48):
     assert np.max(np.abs(C.astype(np.float64) @ x - lhs)) <= tol
 
 
-def test_workload_square4096_sampled_rows_and_vector_check():
-    A, B = synth.make_operands("square4096")
+def test_workload_square4096_full_oracle():
+    """Every element of the 4096 x 4096 output against the fp64 triple loop (about 22 s of oracle time),
+    launched as the benchmark launches it; the tolerance is the one stated over the whole output."""
+    A, B = workload_refs.operands("square4096")
+    assert binding.variant_name(4096, 4096, 4096) == "t256x256x16/nn/a16"
     dC = torch.full((4096, 4096), float("nan"), device="cuda")
     binding.gemm_f32(dev(A), dev(B), dC)
     C = dC.cpu().numpy()
-    assert np.isfinite(C).all()
-    _sampled_rows_and_freivalds(A, B, C, False, 4096, seed=2)
+    check_close(C, workload_refs.reference("square4096"), 4096)
+    _vector_check(A, B, C, False, 4096, seed=2)
 
 
 @pytest.mark.parametrize("name", ["skinny8192", "wide8192"])
@@ -325,27 +324,30 @@ def test_workload_one_short_dimension_full_oracle(name):
             check_close(C, ref, w["K"])
 
 
-def test_workload_square4096_integer_bit_exact_vs_library_int_product():
-    """Whole 4096^2 output, exact: integer-valued operands against an int64 product of a row
-    sample by the oracle, and the +-1 vector check (exact in fp64) over everything."""
-    A, B = synth.make_operands("square4096", dist="ints")
+def test_workload_square4096_integer_bit_exact_full_oracle():
+    """Whole 4096^2 output, exact: integer-valued operands against the oracle on every row, and the
+    +-1 vector check (exact in fp64) over everything."""
+    A, B = workload_refs.operands("square4096", "ints")
     dC = torch.empty((4096, 4096), device="cuda")
     binding.gemm_f32(dev(A), dev(B), dC)
     C = dC.cpu().numpy()
-    rows = np.arange(0, 4096, 97)
-    ref = oracle.gemm_f32(np.ascontiguousarray(A[rows]), B, nthreads=NTHREADS)
-    assert np.array_equal(C[rows].astype(np.float64), ref)
+    assert np.array_equal(C.astype(np.float64), workload_refs.reference("square4096", "ints"))
     x = synth.signs(4096, 2)
     assert np.array_equal(C.astype(np.float64) @ x, A.astype(np.float64) @ (B.astype(np.float64) @ x))
 
 
-def test_workload_transb2048_and_packed():
-    A, Bt = synth.make_operands("transb2048")          # Bt is B stored N x K
+def test_workload_transb2048_and_packed_full_oracle():
+    """2048^3 with B stored N x K, N(0,1) operands, and the same product through pack_b: every element
+    of both outputs against the oracle (the plain one, and the one that reads packedB); then the same
+    on integer-valued operands, bit for bit."""
+    A, Bt = workload_refs.operands("transb2048")          # Bt is B stored N x K
+    ref = workload_refs.reference("transb2048")
     dA, dBt = dev(A), dev(Bt)
     dC = torch.full((2048, 2048), float("nan"), device="cuda")
     binding.gemm_f32(dA, dBt, dC, transB=True)
     C = dC.cpu().numpy()
-    _sampled_rows_and_freivalds(A, Bt, C, True, 2048, seed=3, scale=3.0)
+    check_close(C, ref, 2048, 3.0)
+    _vector_check(A, Bt, C, True, 2048, seed=3, scale=3.0)
 
     P = binding.pack_b_panel_width()
     nbytes = binding.pack_b_size(2048, 2048)
@@ -357,10 +359,21 @@ def test_workload_transb2048_and_packed():
     dC2 = torch.full((2048, 2048), float("nan"), device="cuda")
     binding.gemm_f32_packed(dA, dBp, dC2)
     C2 = dC2.cpu().numpy()
-    _sampled_rows_and_freivalds(A, Bt, C2, True, 2048, seed=3, scale=3.0)
-    rows = np.arange(0, 2048, 171)
-    ref = oracle.gemm_f32_packed(np.ascontiguousarray(A[rows]), want, 2048, nthreads=NTHREADS)
-    check_close(C2[rows], ref, 2048, 3.0)
+    ref_packed = oracle.gemm_f32_packed(A, want, 2048, nthreads=NTHREADS)
+    assert np.array_equal(ref_packed, ref)                 # the rewritten expression names the same sums
+    check_close(C2, ref_packed, 2048, 3.0)
+    _vector_check(A, Bt, C2, True, 2048, seed=3, scale=3.0)
+
+    Ai, Bti = workload_refs.operands("transb2048", "ints")
+    refi = workload_refs.reference("transb2048", "ints")
+    dAi, dBti = dev(Ai), dev(Bti)
+    dC.fill_(float("nan"))
+    binding.gemm_f32(dAi, dBti, dC, transB=True)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), refi)
+    binding.pack_b(dBti, dBp, transB=True)
+    dC2.fill_(float("nan"))
+    binding.gemm_f32_packed(dAi, dBp, dC2)
+    assert np.array_equal(dC2.cpu().numpy().astype(np.float64), refi)
 
 
 @pytest.mark.parametrize("N,K,transB,pad", [(130, 70, False, 0), (130, 70, True, 3), (64, 9, False, 5),
