@@ -15,7 +15,7 @@
  *             (same pointer: GEMMF32_EALIAS; partial overlap is undefined).
  *   Pixels outside [0,H) x [0,W) of out (the ld padding) are never written.
  *   H == 0 or W == 0: success, nothing launched.
- *   Asynchronous on the stream given to binomial3x3_f32_set_stream (default: null stream).
+ *   Asynchronous on the stream the calling host thread gave to binomial3x3_f32_set_stream (default: null stream).
  *   Returns 0 or a negative gemmf32_status (see gemm_f32.h); nothing is launched on error.
  */
 #ifndef BINOMIAL_F32_H

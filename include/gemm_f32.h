@@ -12,12 +12,18 @@
  * Conventions shared by every entry point
  *   - All matrix pointers are DEVICE pointers owned by the caller.  The library
  *     never allocates, frees or retains them.  The only device memory the
- *     library owns is a workspace for products whose output is too small to
- *     occupy the chip (few tiles, long K): their K range is split, partial
- *     products go to the workspace and a second pass sums them in a fixed order.
- *     It is allocated on first need (at most 256 MiB; GEMMF32_ENOMEM if that
- *     fails), reused, and released by gemm_f32_shutdown.  It is one per process:
- *     calls that may split K must not run concurrently on different streams.
+ *     library owns is a workspace for partial products.  Two kinds of products
+ *     use it: those whose output is too small to occupy the chip (few tiles,
+ *     long K: their K range is split, the partial products go to the workspace
+ *     and a second pass sums them in a fixed order), and those whose tile count
+ *     leaves a small remainder after whole rounds of 256 tiles (the remainder's
+ *     tiles are split along K the same way).  There is one workspace per stream,
+ *     so calls on different streams never share one, and calls on one stream
+ *     are ordered by the stream.  It is allocated by the first call that needs
+ *     it and replaced by a larger one when a later call needs more (at most
+ *     256 MiB per stream; GEMMF32_ENOMEM if the allocation fails); no call frees
+ *     memory or waits for the device.  gemm_f32_reserve_workspace sizes it ahead
+ *     of time and gemm_f32_shutdown releases everything.
  *   - Row-major storage with element strides (BLAS style):
  *       A   M x K, element (i,k) at A[i*lda + k],              lda >= max(K,1)
  *       B   transB == 0: K x N, element (k,j) at B[k*ldb + j], ldb >= max(N,1)
@@ -29,8 +35,8 @@
  *   - Elements of C outside [0,M) x [0,N) (the ldc padding) are never written.
  *   - M == 0 or N == 0: success, nothing launched.  K == 0: C is filled with
  *     +0.0 (the empty sum).
- *   - Work is enqueued on the stream given to gemm_f32_set_stream (default: the
- *     null stream) and the call returns without waiting for it.
+ *   - Work is enqueued on the calling thread's stream (gemm_f32_set_stream;
+ *     default: the null stream) and the call returns without waiting for it.
  *   - Return value: GEMMF32_OK (0) or a negative gemmf32_status.  On error
  *     nothing has been launched.  C must not be the same pointer as A or B
  *     (GEMMF32_EALIAS); partially overlapping buffers are undefined behaviour.
@@ -38,8 +44,10 @@
  *     elements (GEMMF32_EINVAL beyond that).
  *   - Results are deterministic run to run for a fixed shape, strides and
  *     pointer alignment; no floating-point atomics are used.
- *   - The stream setting is one process-wide value; changing it while another
- *     thread is inside a call is a race.  Calls themselves keep no other state.
+ *   - The stream setting is per host thread: every thread that calls the
+ *     library sets its own stream, and threads on different streams may call
+ *     concurrently.  Two threads that use the same stream are ordered only by
+ *     the order in which their launches reach the stream.
  */
 #ifndef GEMM_F32_H
 #define GEMM_F32_H
@@ -57,7 +65,7 @@ typedef enum {
     GEMMF32_ENULL = -2,   /* a required pointer is NULL */
     GEMMF32_EALIAS = -3,  /* C is the same buffer as A or B */
     GEMMF32_ELAUNCH = -4, /* the HIP runtime refused; see gemm_f32_last_hip_error */
-    GEMMF32_ENOMEM = -5   /* the split-K workspace could not be allocated */
+    GEMMF32_ENOMEM = -5   /* the workspace could not be allocated */
 } gemmf32_status;
 
 /*
@@ -133,9 +141,21 @@ int gemm_f32_packed(int64_t M, int64_t N, int64_t K,
                     const float *Bp,
                     float *C, int64_t ldc);
 
-/* Stream for all later launches (a hipStream_t passed as void*; NULL = null
- * stream).  The caller keeps ownership of the stream. */
+/* Stream for all later launches of the calling host thread (a hipStream_t
+ * passed as void*; NULL = null stream).  The caller keeps ownership of the
+ * stream. */
 int gemm_f32_set_stream(void *hip_stream);
+
+/*
+ * Makes the workspace of the calling thread's stream at least `bytes` large
+ * now, so that later calls on that stream which need no more than that
+ * allocate nothing.  bytes > 256 MiB: GEMMF32_EINVAL.  A product whose K is
+ * split into S ranges needs S*M*N*4 bytes (S is chosen so that this stays
+ * within 256 MiB); one whose last round is split needs at most 256 tiles'
+ * worth of floats (2 MiB for the 64 x 64 tiles, 64 MiB for 256 x 256).
+ * Allocates (hipMalloc) unless the workspace is already that large.
+ */
+int gemm_f32_reserve_workspace(size_t bytes);
 
 /* Static, never-NULL description of a status code. */
 const char *gemm_f32_strerror(int status);
@@ -143,22 +163,7 @@ const char *gemm_f32_strerror(int status);
 /* hipError_t (as int) of the most recent GEMMF32_ELAUNCH / GEMMF32_ENOMEM on this thread, else 0. */
 int gemm_f32_last_hip_error(void);
 
-/*
- * Measurement aid: launches 256 workgroups of 4 waves (one wave per SIMD of every compute unit) that
- * issue mfma_per_wave (a multiple of 16) fp32 32x32x2 matrix instructions each on register operands
- * and touch no memory.  One such instruction occupies the matrix pipe for 64 cycles, so
- *     64 * mfma_per_wave / (run time)
- * is the clock the chip sustains under full matrix load, and 256 CUs * 256 flop/cycle times that
- * clock is the matrix peak actually available (the nominal 157.3 TFLOP/s assumes 2.4 GHz).
- * operands: DEVICE pointer to 512 floats; thread t of every workgroup multiplies operands[2t] by
- * operands[2t+1] throughout (the sustained clock depends on the values: zeros draw less power than
- * random numbers, and the chip is power-limited under matrix load).
- * sink: DEVICE pointer to at least one float (never written in practice).  Asynchronous on the
- * library's stream; the caller times it.
- */
-int gemm_f32_mfma_rate_probe(int64_t mfma_per_wave, const float *operands, float *sink);
-
-/* Releases the split-K workspace (waits for the device).  The library stays usable. */
+/* Waits for the device, then releases every workspace.  The library stays usable. */
 void gemm_f32_shutdown(void);
 
 /*
@@ -168,18 +173,6 @@ void gemm_f32_shutdown(void);
  * "t64x64x32/nn/a4/quad16" (the 16 tiles of the last round computed as 32 x 32 blocks); for
  * diagnostics and benchmarks.  The pointers are only inspected for alignment and may be NULL for
  * "aligned".  The string lives in a per-thread buffer that the next call on the thread overwrites.
- *
- * Test hooks read from the environment at every call (not meant for production use):
- *   GEMMF32_FORCE_TILE=0..12   tile 256x256x16, 128x128x16, 64x64x32, 64x64x64, 256x128x16, 128x256x16,
- *                              128x64x32, 64x128x32, 128x32x32, 32x128x32, and 32x32x64, 64x32x64, 32x64x64 with
- *                              four waves sharing each slab
- *   GEMMF32_FORCE_SPLITK=S     K split into S ranges where that fits
- *   GEMMF32_NO_TAIL_SPLIT=1    never split the last round
- *   GEMMF32_NO_QUAD=1          split the last round along K only, never into 32 x 32 blocks
- *   GEMMF32_NO_THIN=1          never the vector-unit kernel for products with at most 4 rows or columns
- *   GEMMF32_FORCE_THIN=1       that kernel wherever it can run (at most 8 rows or columns, both operands with k contiguous)
- *   GEMMF32_NO_KSHARE=1        the 32x32x64 tile only for outputs at most 32 wide, not for outputs of a few hundred blocks
- * gemm_f32_scheduled (elevate.h) is the interface for choosing tile and split per call.
  */
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K,
                                   const float *A, int64_t lda,

@@ -10,7 +10,7 @@
  * each add one class of optimisation and exist to be measured.
  *
  * Same conventions as gemm_f32.h: device pointers owned by the caller, element strides,
- * C overwritten, nothing outside [0,M) x [0,N) written, asynchronous on the stream given
+ * C overwritten, nothing outside [0,M) x [0,N) written, asynchronous on the stream the calling thread gave
  * to gemm_f32_ladder_set_stream (default: null stream), 0 on success or a negative
  * gemmf32_status (GEMMF32_EINVAL for an unknown level or bad dimensions, GEMMF32_ENULL for
  * a missing pointer), nothing launched on error.

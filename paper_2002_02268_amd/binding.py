@@ -28,6 +28,8 @@ SYMBOLS = {
     "pack_b": (ctypes.c_int, [_i64, _i64, _ptr, _i64, ctypes.c_int, _ptr]),
     "gemm_f32_packed": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _ptr, _i64]),
     "gemm_f32_set_stream": (ctypes.c_int, [_ptr]),
+    "gemm_f32_reserve_workspace": (ctypes.c_int, [ctypes.c_size_t]),
+    "gemm_f32_set_test_hooks": (ctypes.c_int, [_ptr]),
     "gemm_f32_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "gemm_f32_last_hip_error": (ctypes.c_int, []),
     "gemm_f32_shutdown": (None, []),
@@ -119,6 +121,41 @@ def gemm_f32(A, B, C, transB: bool = False) -> None:
     _use_current_stream(C)
     _check(lib().gemm_f32(M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), C.data_ptr(), _ld(C),
                           int(bool(transB))))
+
+
+def gemm_f32_reserve_workspace(nbytes: int, device=None) -> None:
+    """Sizes the workspace of the current torch stream ahead of time."""
+    import torch
+    lib().gemm_f32_set_stream(ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream))
+    _check(lib().gemm_f32_reserve_workspace(int(nbytes)))
+
+
+class HookSettings(ctypes.Structure):
+    """gemmf32_test_hooks (include/gemm_f32_testing.h)"""
+    _fields_ = [("force_tile", ctypes.c_int32), ("force_split", ctypes.c_int32), ("no_tail_split", ctypes.c_int32),
+                ("no_quad", ctypes.c_int32), ("no_kshare", ctypes.c_int32), ("no_thin", ctypes.c_int32),
+                ("force_thin", ctypes.c_int32)]
+
+
+_hooks = {}
+
+
+def set_test_hooks(**changes) -> None:
+    """Changes some of the dispatch overrides and leaves the others as they are: force_tile=3,
+    no_quad=True, ...; a value of None (or False, or 0 for force_split) switches that override off.
+    Without arguments: everything off (production)."""
+    if not changes:
+        _hooks.clear()
+    for key, value in changes.items():
+        if key not in dict(HookSettings._fields_):
+            raise KeyError(key)
+        if value is None or value is False:
+            _hooks.pop(key, None)
+        else:
+            _hooks[key] = int(value)
+    h = HookSettings(force_tile=_hooks.get("force_tile", -1), force_split=_hooks.get("force_split", 0),
+                  **{k: _hooks.get(k, 0) for k in ("no_tail_split", "no_quad", "no_kshare", "no_thin", "force_thin")})
+    _check(lib().gemm_f32_set_test_hooks(ctypes.byref(h)))
 
 
 def gemm_f32_batched(A, B, C, transB: bool = False) -> None:

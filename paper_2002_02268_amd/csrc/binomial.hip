@@ -16,7 +16,7 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef v4f v4f_g __attribute__((aligned(4)));   // 16-byte access to 4-byte-aligned global memory
 
-hipStream_t g_stream = nullptr;
+thread_local hipStream_t g_stream = nullptr;   // per host thread
 
 struct Args {
     const float *in;

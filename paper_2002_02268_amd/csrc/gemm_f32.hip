@@ -1,6 +1,7 @@
 // C-ABI entry points and dispatch for the fp32 matrix product on gfx950.
 // Argument checks, choice of tile variant from the shape, launch on the configured stream.
 #include "../../include/gemm_f32.h"
+#include "../../include/gemm_f32_testing.h"
 
 #include <type_traits>
 
@@ -8,15 +9,20 @@
 #include "gemm_launch.hpp"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 using namespace gemmf32;
 
 namespace {
 
-hipStream_t g_stream = nullptr;
+// Each host thread has its own current stream, so threads that drive different streams do not
+// disturb each other.
+thread_local hipStream_t g_stream = nullptr;
 thread_local int g_last_hip_error = 0;
 
 constexpr int64_t kMaxDim = 2147483647LL;
@@ -66,14 +72,10 @@ template <int BMODE> int launch_batched64_mode(const BatchArgs &a)
 {
     constexpr int SB = (BMODE == B_NT) ? 68 : 64;
     constexpr int lds_bytes = 2 * (64 * 68 + 64 * SB) * 4;
-    static bool attr_set = false;
+    static std::atomic<uint64_t> lds_limit_set{0};
     auto kern = batched64_kernel<BMODE>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return fail_hip(e);
-        attr_set = true;
-    }
+    const int rc = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, lds_limit_set);
+    if (rc != GEMMF32_OK) return rc;
     // two workgroups per compute unit (what the LDS holds); more residency does not raise the
     // achieved bandwidth, which already equals that of a plain device copy
     const int grid = a.batch < 512 ? a.batch : 512;
@@ -137,24 +139,21 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 // quad: instead, every tail tile is cut into its 32 x 32 blocks (`pieces` of them), each computed by a
 // whole workgroup whose waves share the slabs along k: a quarter of a tile's time per block, and no
 // second pass.  Better than K ranges when K is short (the second pass costs a fixed 10 us).
-// The test hooks of the environment, read once per call (every lookup scans the whole environment).
+// Test hooks (gemm_f32_set_test_hooks): process-wide, all off in production.  The environment is never read.
 struct Hooks {
-    bool no_tail_split, no_quad, no_kshare, no_thin;
+    bool no_tail_split, no_quad, no_kshare, no_thin, force_thin;
     int force_tile, force_split;       // -1: not forced
 };
+struct HookState {
+    std::atomic<int> force_tile{-1}, force_split{-1};
+    std::atomic<int> no_tail_split{0}, no_quad{0}, no_kshare{0}, no_thin{0}, force_thin{0};
+} g_hooks;
 Hooks read_hooks()
 {
-    Hooks h = {std::getenv("GEMMF32_NO_TAIL_SPLIT") != nullptr, std::getenv("GEMMF32_NO_QUAD") != nullptr,
-               std::getenv("GEMMF32_NO_KSHARE") != nullptr, std::getenv("GEMMF32_NO_THIN") != nullptr, -1, -1};
-    if (const char *f = std::getenv("GEMMF32_FORCE_TILE")) {
-        const int t = std::atoi(f);
-        if (t >= 0 && t < NUM_TILES) h.force_tile = t;
-    }
-    if (const char *f = std::getenv("GEMMF32_FORCE_SPLITK")) {
-        const int t = std::atoi(f);
-        if (t >= 1 && t <= 256) h.force_split = t;
-    }
-    return h;
+    const auto get = [](const std::atomic<int> &a) { return a.load(std::memory_order_relaxed); };
+    return Hooks{get(g_hooks.no_tail_split) != 0, get(g_hooks.no_quad) != 0, get(g_hooks.no_kshare) != 0,
+                 get(g_hooks.no_thin) != 0,       get(g_hooks.force_thin) != 0, get(g_hooks.force_tile),
+                 get(g_hooks.force_split)};
 }
 
 struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; bool quad; };
@@ -341,31 +340,48 @@ struct Plan {
     int64_t user_ldc;    // leading dimension of the caller's C (args.ldc is the workspace's when split)
     bool vec;
     int thin;            // 0: tiles; 1: at most 8 rows, B streamed by the vector-unit kernel; 2: at most 8 columns, A streamed
+    size_t workspace_bytes;   // what the launch needs besides the operands (0: nothing)
     KArgs args;
 };
 
-// Workspace of the split-K first pass (S dense M x N partial products).  Owned by the library, grown
-// on demand, freed by gemm_f32_shutdown.  One per process: calls that split K must not overlap.
-float *g_workspace = nullptr;
-size_t g_workspace_bytes = 0;
+// Workspace: the partial products of a K split (S dense M x N matrices) or of a split last round
+// (dense BM x BN tiles).  One buffer per (device, stream), so calls on different streams never share
+// one; calls on one stream are ordered by the stream.  A buffer that is too small is replaced by a
+// larger one (at least twice its size); the old one may still be read by work already enqueued, so it
+// is kept until gemm_f32_shutdown: no call ever frees memory or waits for the device.
+struct Workspace { int device; hipStream_t stream; float *ptr; size_t bytes; };
+std::mutex g_workspace_mutex;
+std::vector<Workspace> g_workspaces;
+std::vector<void *> g_retired;
 
-int ensure_workspace(size_t bytes)
+int acquire_workspace(size_t bytes, float **out)
 {
-    if (bytes <= g_workspace_bytes) return GEMMF32_OK;
-    if (g_workspace != nullptr) {
-        hipError_t e = hipFree(g_workspace);   // waits for work that may still use it
-        g_workspace = nullptr;
-        g_workspace_bytes = 0;
-        if (e != hipSuccess) return fail_hip(e);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e);
+    std::lock_guard<std::mutex> lock(g_workspace_mutex);
+    Workspace *w = nullptr;
+    for (auto &cand : g_workspaces)
+        if (cand.device == dev && cand.stream == g_stream) w = &cand;
+    if (w == nullptr) {
+        g_workspaces.push_back(Workspace{dev, g_stream, nullptr, 0});
+        w = &g_workspaces.back();
     }
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&g_workspace), bytes);
-    if (e != hipSuccess) {
-        g_workspace = nullptr;
-        (void)hipGetLastError();
-        g_last_hip_error = (int)e;
-        return GEMMF32_ENOMEM;
+    if (bytes > w->bytes) {
+        size_t want = std::max(bytes, std::min<size_t>(2 * w->bytes, (size_t)kMaxWorkspaceBytes));
+        want = (want + 65535) & ~(size_t)65535;
+        float *fresh = nullptr;
+        e = hipMalloc(reinterpret_cast<void **>(&fresh), want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            g_last_hip_error = (int)e;
+            return GEMMF32_ENOMEM;
+        }
+        if (w->ptr != nullptr) g_retired.push_back(w->ptr);
+        w->ptr = fresh;
+        w->bytes = want;
     }
-    g_workspace_bytes = bytes;
+    *out = w->ptr;
     return GEMMF32_OK;
 }
 
@@ -416,7 +432,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     pl.thin = 0;
     if (batch == 1 && bmode == B_NT && amode == A_MK && K >= 1 && !hooks.no_thin && hooks.force_tile < 0 &&
         hooks.force_split < 0 && g_forced_tile < 0 && g_forced_split < 0) {
-        const bool force_thin = std::getenv("GEMMF32_FORCE_THIN") != nullptr;       // test hook: whenever it can run
+        const bool force_thin = hooks.force_thin;       // test hook: whenever it can run
         if (M <= 8 && N >= 64 && (force_thin || (M <= 4 && N < 8192 && N * K >= (32LL << 20)))) pl.thin = 1;
         else if (N <= 8 && M >= 64 && (force_thin || (N <= 4 && M < 8192 && M * K >= (32LL << 20)))) pl.thin = 2;
     }
@@ -485,6 +501,9 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
             a.K = (int)K; a.k_total = 0; a.sA = a.sB = a.sC = 0; a.ldc = ldc; a.alpha = alpha; a.beta = beta;
         }
     }
+    if (pl.split > 1) pl.workspace_bytes = (size_t)pl.split * (size_t)M * (size_t)N * sizeof(float);
+    else if (pl.tail_tiles > 0 && a.quad == 0)
+        pl.workspace_bytes = (size_t)pl.tail_tiles * a.tail_split * kShapes[pl.tile].bm * kShapes[pl.tile].bn * sizeof(float);
     pl.launch = true;
     return pl;
 }
@@ -551,13 +570,16 @@ int run_plan(const Plan &pl)
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
     if (pl.thin != 0) return launch_thin(pl);
+    float *workspace = nullptr;
+    if (pl.workspace_bytes > 0) {
+        const int rc = acquire_workspace(pl.workspace_bytes, &workspace);
+        if (rc != GEMMF32_OK) return rc;
+    }
     if (pl.split <= 1 && pl.tail_tiles > 0 && pl.args.quad == 0) {
         const TileShape &sh = kShapes[pl.tile];
         KArgs a = pl.args;
-        int rc = ensure_workspace((size_t)pl.tail_tiles * a.tail_split * sh.bm * sh.bn * sizeof(float));
-        if (rc != GEMMF32_OK) return rc;
-        a.tail_slots = g_workspace;
-        rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
+        a.tail_slots = workspace;
+        const int rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
         if (rc != GEMMF32_OK) return rc;
         hipLaunchKernelGGL(tail_reduce_kernel, dim3((unsigned)(pl.tail_tiles * (sh.bm * sh.bn / 256))), dim3(64), 0,
                            g_stream, a, sh.bm, sh.bn);
@@ -568,15 +590,12 @@ int run_plan(const Plan &pl)
     if (pl.split <= 1) return launch_variant(pl.bmode, pl.amode, pl.tile, pl.args);
     // split K: partial products into the workspace, then one pass that sums them in order
     KArgs a = pl.args;
-    const int64_t mn = (int64_t)a.M * a.N;
-    int rc = ensure_workspace((size_t)pl.split * mn * sizeof(float));
-    if (rc != GEMMF32_OK) return rc;
     float *C = a.C;
     const int64_t ldc = pl.user_ldc;
-    a.C = g_workspace;
-    rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
+    a.C = workspace;
+    const int rc = launch_variant(pl.bmode, pl.amode, pl.tile, a);
     if (rc != GEMMF32_OK) return rc;
-    return launch_splitk_reduce(g_workspace, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta);
+    return launch_splitk_reduce(workspace, C, a.M, a.N, ldc, pl.split, pl.alpha, pl.beta);
 }
 
 thread_local char g_variant_buf[64];
@@ -666,7 +685,7 @@ int gemm_f32_batched(int64_t batch, int64_t M, int64_t N, int64_t K, const float
                      int64_t strideC, int transB)
 {
     if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
-    if (M == 64 && N == 64 && K == 64 && batch >= 2 && !std::getenv("GEMMF32_FORCE_TILE")) {
+    if (M == 64 && N == 64 && K == 64 && batch >= 2 && read_hooks().force_tile < 0) {
         // streaming path for many 64^3 products; same argument checks as the general path
         Plan pl = make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
                             transB ? B_NT : B_NN);
@@ -772,9 +791,36 @@ int gemm_f32_last_hip_error(void) { return g_last_hip_error; }
 
 void gemm_f32_shutdown(void)
 {
-    if (g_workspace != nullptr) (void)hipFree(g_workspace);
-    g_workspace = nullptr;
-    g_workspace_bytes = 0;
+    (void)hipDeviceSynchronize();      // work that still reads a workspace
+    std::lock_guard<std::mutex> lock(g_workspace_mutex);
+    for (auto &w : g_workspaces)
+        if (w.ptr != nullptr) (void)hipFree(w.ptr);
+    for (void *p : g_retired) (void)hipFree(p);
+    g_workspaces.clear();
+    g_retired.clear();
+}
+
+int gemm_f32_reserve_workspace(size_t bytes)
+{
+    if (bytes > (size_t)kMaxWorkspaceBytes) return GEMMF32_EINVAL;
+    if (bytes == 0) return GEMMF32_OK;
+    float *unused = nullptr;
+    return acquire_workspace(bytes, &unused);
+}
+
+int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)
+{
+    const gemmf32_test_hooks off = {-1, 0, 0, 0, 0, 0, 0};
+    if (h == nullptr) h = &off;
+    if (h->force_tile < -1 || h->force_tile >= NUM_TILES || h->force_split < 0 || h->force_split > 256) return GEMMF32_EINVAL;
+    g_hooks.force_tile.store(h->force_tile);
+    g_hooks.force_split.store(h->force_split >= 1 ? h->force_split : -1);
+    g_hooks.no_tail_split.store(h->no_tail_split != 0);
+    g_hooks.no_quad.store(h->no_quad != 0);
+    g_hooks.no_kshare.store(h->no_kshare != 0);
+    g_hooks.no_thin.store(h->no_thin != 0);
+    g_hooks.force_thin.store(h->force_thin != 0);
+    return GEMMF32_OK;
 }
 
 const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,

@@ -6,12 +6,29 @@
 #include "../../include/gemm_f32.h"
 #include "gemm_kernels.hpp"
 
+#include <atomic>
+
 namespace gemmf32_host {
 
 using namespace gemmf32;
 
-hipStream_t current_stream();              // the stream set by gemm_f32_set_stream
+hipStream_t current_stream();              // the calling thread's stream (gemm_f32_set_stream)
 int record_hip_error(hipError_t e);        // remembers e for gemm_f32_last_hip_error; returns GEMMF32_ELAUNCH
+
+// Raises a kernel's dynamic LDS limit once per device.  `done` (one per kernel) holds a bit per device
+// ordinal; two threads that both find their bit clear both set the attribute, which is harmless.
+inline int ensure_lds_limit(const void *kernel, int bytes, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip_error(e);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return GEMMF32_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return record_hip_error(e);
+    done.fetch_or(bit, std::memory_order_release);
+    return GEMMF32_OK;
+}
 
 // ---- variants -------------------------------------------------------------------------------
 enum TileId : int { T256 = 0, T128 = 1, T64 = 2, TB64 = 3, T256x128 = 4, T128x256 = 5, T128x64 = 6, T64x128 = 7, T128x32 = 8, T32x128 = 9, TQ32 = 10, TQ64x32 = 11, TQ32x64 = 12, NUM_TILES = 13 };
@@ -54,14 +71,10 @@ template <int BMODE, int AMODE> struct Variant<TQ32x64, BMODE, AMODE> { typedef 
 
 template <class T> int launch(const KArgs &a)
 {
-    static bool attr_set = false;  // per instantiation; benign if set twice
+    static std::atomic<uint64_t> lds_limit_set{0};  // per instantiation
     auto kern = gemm_kernel<T>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LdsNeed<T>::value);
-        if (e != hipSuccess) return record_hip_error(e);
-        attr_set = true;
-    }
+    const int rc = ensure_lds_limit(reinterpret_cast<const void *>(kern), LdsNeed<T>::value, lds_limit_set);
+    if (rc != GEMMF32_OK) return rc;
     // blocks of tail tiles only for shapes that have the block kernel: without it the pieces would be
     // taken for K ranges and stored through a slot pointer that was never set
     if (a.quad != 0 && std::is_void<typename QuadOf<T>::type>::value) return GEMMF32_EINVAL;

@@ -6,9 +6,13 @@
 
 using namespace gemmf32_ladder;
 
+namespace gemmf32_host {
+hipStream_t current_stream();   // the product library's stream of the calling thread (gemm_f32.hip)
+}
+
 namespace {
 
-hipStream_t g_ladder_stream = nullptr;
+thread_local hipStream_t g_ladder_stream = nullptr;   // per host thread, like the product's
 
 const char *const kNames[7] = {"baseline",      "blocking",     "vectorization", "loop permutation",
                                "array packing", "cache blocks", "parallel"};
@@ -42,8 +46,12 @@ int gemm_f32_ladder(int level, int64_t M, int64_t N, int64_t K, const float *A, 
     if (K > 0 && (A == nullptr || (packed ? Bp : B) == nullptr)) return GEMMF32_ENULL;
     if (C == A || C == B || C == Bp) return GEMMF32_EALIAS;
     if (level == 6) {
+        // the product itself, on the ladder's stream; the product's own stream setting is put back
+        hipStream_t saved = gemmf32_host::current_stream();
         gemm_f32_set_stream(g_ladder_stream);
-        return gemm_f32_packed(M, N, K, A, lda, Bp, C, ldc);
+        const int rc = gemm_f32_packed(M, N, K, A, lda, Bp, C, ldc);
+        gemm_f32_set_stream(saved);
+        return rc;
     }
     Args a;
     a.A = A; a.B = packed ? Bp : B; a.C = C;

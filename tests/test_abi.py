@@ -150,11 +150,66 @@ def test_block_tails_are_planned_only_for_tiles_that_have_the_block_kernel():
     with_blocks = {"t64x64x32", "t64x64x64", "t128x64x32", "t64x128x32", "t128x32x32", "t32x128x32"}
     try:
         for tile in range(13):
-            os.environ["GEMMF32_FORCE_TILE"] = str(tile)
+            binding.set_test_hooks(force_tile=tile)
             for _ in range(400):
                 M, N, K = rng.randint(1, 3000), rng.randint(1, 3000), rng.randint(1, 5000)
                 name = binding.variant_name(M, N, K, transB=rng.random() < 0.5)
                 if "/quad" in name:
                     assert name.split("/")[0] in with_blocks, (M, N, K, name)
     finally:
-        os.environ.pop("GEMMF32_FORCE_TILE", None)
+        binding.set_test_hooks(force_tile=None)
+
+
+def test_planning_from_many_host_threads_agrees_with_one_thread():
+    """The dispatch's planning (cost model, its per-thread cache of choices, the per-thread name buffer) run
+    from eight host threads at once on the same seeded shapes gives every thread the single-threaded answers."""
+    import random
+    import threading
+    binding.set_test_hooks()
+    rng = random.Random(17)
+    shapes = [(rng.randint(1, 5000), rng.randint(1, 5000), rng.randint(1, 20000), rng.random() < 0.5) for _ in range(300)]
+    want = [binding.variant_name(M, N, K, transB=t) for (M, N, K, t) in shapes]
+    results, errors = {}, []
+
+    def run(tid):
+        try:
+            order = list(range(len(shapes)))
+            random.Random(tid).shuffle(order)
+            got = {}
+            for _ in range(3):
+                for i in order:
+                    M, N, K, t = shapes[i]
+                    got[i] = binding.variant_name(M, N, K, transB=t)
+            results[tid] = [got[i] for i in range(len(shapes))]
+        except Exception as e:                      # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=run, args=(tid,)) for tid in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    for tid in range(8):
+        assert results[tid] == want
+
+
+def test_test_hooks_validate_and_reset():
+    lib = binding.lib()
+    binding.set_test_hooks(force_tile=3)
+    assert binding.variant_name(4096, 4096, 4096).startswith("t64x64x64")
+    binding.set_test_hooks(force_tile=None, force_split=4)
+    assert binding.variant_name(512, 512, 4096).endswith("splitk4")
+    binding.set_test_hooks()
+    assert binding.variant_name(4096, 4096, 4096).startswith("t256x256x16")
+    bad = binding.HookSettings(force_tile=13)
+    import ctypes
+    assert lib.gemm_f32_set_test_hooks(ctypes.byref(bad)) == -1
+    assert lib.gemm_f32_set_test_hooks(None) == 0
+    # the environment is not a hook any more
+    import os
+    os.environ["GEMMF32_FORCE_TILE"] = "3"
+    try:
+        assert binding.variant_name(4096, 4096, 4096).startswith("t256x256x16")
+    finally:
+        os.environ.pop("GEMMF32_FORCE_TILE")

@@ -39,9 +39,9 @@ def tolerance(K, alpha, beta, c_max):
 @pytest.fixture
 def force_tile():
     def _set(name):
-        os.environ["GEMMF32_FORCE_TILE"] = TILES[name]
+        binding.set_test_hooks(force_tile=TILES[name])
     yield _set
-    os.environ.pop("GEMMF32_FORCE_TILE", None)
+    binding.set_test_hooks(force_tile=None)
 
 
 SHAPES = [(1, 1, 1), (33, 65, 17), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33), (700, 5, 40)]
@@ -144,8 +144,8 @@ def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
         ref = oracle.gemm_f32_ex(stored(A, tA), stored(B, tB), C0, -2.0, 3.0, tA, tB, nthreads=NTHREADS)
         for no_quad in (False, True):       # the last round as 32 x 32 blocks (scalars applied in the kernel), then as K ranges
             if no_quad:
-                os.environ["GEMMF32_NO_QUAD"] = "1"
-                os.environ["GEMMF32_NO_KSHARE"] = "1"      # or the shared-slab tile would take the ragged shape whole
+                binding.set_test_hooks(no_quad=True)
+                binding.set_test_hooks(no_kshare=True)  # or the shared-slab tile would take the ragged shape whole
             try:
                 name = binding.variant_name(M, N, K, transB=tB)
                 print(f"case tA={tA} tB={tB} M={M} N={N} K={K} variant={name}", flush=True)
@@ -153,8 +153,8 @@ def test_ex_split_k_and_split_last_round_apply_scalars_once(tA, tB):
                 dC = dev(C0)
                 binding.gemm_f32_ex(dev(stored(A, tA)), dev(stored(B, tB)), dC, -2.0, 3.0, tA, tB)
             finally:
-                os.environ.pop("GEMMF32_NO_QUAD", None)
-                os.environ.pop("GEMMF32_NO_KSHARE", None)
+                binding.set_test_hooks(no_quad=None)
+                binding.set_test_hooks(no_kshare=None)
             assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
 
 
@@ -342,12 +342,12 @@ def test_ex_products_with_one_short_dimension_match(M, N, K, tA, tB):
             dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
             for forced in (None,) + narrow_tiles:          # the dispatch's own choice, then the narrow tiles
                 if forced is not None:
-                    os.environ["GEMMF32_FORCE_TILE"] = forced
+                    binding.set_test_hooks(force_tile=forced)
                     dC, bufC = padded_dev(C0 if beta else np.full((M, N), np.nan, np.float32), 2)
                 try:
                     binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
                 finally:
-                    os.environ.pop("GEMMF32_FORCE_TILE", None)
+                    binding.set_test_hooks(force_tile=None)
                 whole = bufC.cpu().numpy()
                 got = whole[:, :N].astype(np.float64)
                 if ints:

@@ -58,11 +58,11 @@ def check_close(C: np.ndarray, ref: np.ndarray, K: int, scale: float = 1.0):
 def force_tile():
     def _set(name):
         if name is None:
-            os.environ.pop("GEMMF32_FORCE_TILE", None)
+            binding.set_test_hooks(force_tile=None)
         else:
-            os.environ["GEMMF32_FORCE_TILE"] = TILES[name]
+            binding.set_test_hooks(force_tile=TILES[name])
     yield _set
-    os.environ.pop("GEMMF32_FORCE_TILE", None)
+    binding.set_test_hooks(force_tile=None)
 
 
 SMALL_SHAPES = [(1, 1, 1), (33, 65, 17), (64, 64, 64), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33)]
@@ -459,13 +459,13 @@ def test_batched64_streaming_path_many_products_bit_exact(transB):
     assert np.array_equal(whole[:, :64, :64].astype(np.float64), ref)
     assert np.isnan(whole[:, 64:, :]).all() and np.isnan(whole[:, :, 64:]).all()
     # the same products through the general tiled kernel agree bit for bit in the exact regime
-    os.environ["GEMMF32_FORCE_TILE"] = "3"
+    binding.set_test_hooks(force_tile=3)
     try:
         dC2 = torch.full((batch, 64, 64), float("nan"), device="cuda")
         binding.gemm_f32_batched(dA, dB, dC2, transB=transB)
         assert np.array_equal(dC2.cpu().numpy().astype(np.float64), ref)
     finally:
-        os.environ.pop("GEMMF32_FORCE_TILE", None)
+        binding.set_test_hooks(force_tile=None)
 
 
 def test_batched64_uniform_values_and_two_products():
@@ -505,7 +505,7 @@ def test_split_k_small_outputs_long_k(transB):
 def test_split_k_forced_factors_bit_exact_and_deterministic(split):
     """Any split factor gives the exact result on integer operands (also through packed B), and the
     same bits on every run for float operands."""
-    os.environ["GEMMF32_FORCE_SPLITK"] = str(split)
+    binding.set_test_hooks(force_split=split)
     try:
         M, N, K = 150, 200, 2000
         A = synth.small_ints((M, K), 710, synth.TENSOR_A)
@@ -534,7 +534,7 @@ def test_split_k_forced_factors_bit_exact_and_deterministic(split):
         assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
         check_close(outs[0], oracle.gemm_f32(Af, Bf, nthreads=NTHREADS), K)
     finally:
-        os.environ.pop("GEMMF32_FORCE_SPLITK", None)
+        binding.set_test_hooks(force_split=None)
 
 
 def test_shutdown_releases_workspace_and_library_stays_usable():
@@ -560,7 +560,7 @@ def test_split_tail_bit_exact(force_tile, tile, how, transB):
     operands; ragged edges (blocks of edge tiles that lie outside the matrix), a K tail, padded C."""
     force_tile(tile)
     if how == "tail":
-        os.environ["GEMMF32_NO_QUAD"] = "1"
+        binding.set_test_hooks(no_quad=True)
     shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
               "tb64": [(1000, 1030, 999), (1100, 1100, 1100)], "t128x64": [(2100, 1090, 700), (2200, 1000, 333)],
               "t64x128": [(1090, 2100, 700)], "tq32": [(520, 530, 3000), (576, 570, 4100)], "tq64x32": [(770, 760, 2100), (1030, 520, 3000)],
@@ -568,7 +568,7 @@ def test_split_tail_bit_exact(force_tile, tile, how, transB):
     try:
         _split_tail_cases(shapes, how, transB)
     finally:
-        os.environ.pop("GEMMF32_NO_QUAD", None)
+        binding.set_test_hooks(no_quad=None)
 
 
 def _split_tail_cases(shapes, how, transB):
@@ -605,17 +605,17 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
     dC = torch.full((1000, 1030), float("nan"), device="cuda")
     binding.gemm_f32_packed(dA, dBp, dC)
     check_close(dC.cpu().numpy(), ref, 999)
-    os.environ["GEMMF32_NO_QUAD"] = "1"
-    os.environ["GEMMF32_NO_KSHARE"] = "1"          # or the tile whose waves share the slabs takes the shape whole
+    binding.set_test_hooks(no_quad=True)
+    binding.set_test_hooks(no_kshare=True)  # or the tile whose waves share the slabs takes the shape whole
     try:
         assert "/tail16x8" in binding.variant_name(1000, 1030, 999)
         dC.fill_(float("nan"))
         binding.gemm_f32(dA, dB, dC)
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
-        os.environ.pop("GEMMF32_NO_QUAD", None)
-        os.environ.pop("GEMMF32_NO_KSHARE", None)
-    os.environ["GEMMF32_NO_TAIL_SPLIT"] = "1"
+        binding.set_test_hooks(no_quad=None)
+        binding.set_test_hooks(no_kshare=None)
+    binding.set_test_hooks(no_tail_split=True)
     try:
         name = binding.variant_name(1000, 1030, 999)
         assert "/tail" not in name and "/quad" not in name
@@ -623,7 +623,7 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
         binding.gemm_f32(dA, dB, dC)
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
-        os.environ.pop("GEMMF32_NO_TAIL_SPLIT", None)
+        binding.set_test_hooks(no_tail_split=None)
 
 
 def test_mfma_rate_probe_runs_and_validates_its_arguments():

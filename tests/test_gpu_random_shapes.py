@@ -62,15 +62,15 @@ def test_random_shapes_bit_exact(cls):
             dB, _ = padded_dev(B, pb)
             dC, bufC = padded_dev(C0, pc)
             if tile is None:
-                os.environ.pop("GEMMF32_FORCE_TILE", None)
+                binding.set_test_hooks(force_tile=None)
             else:
-                os.environ["GEMMF32_FORCE_TILE"] = tile
+                binding.set_test_hooks(force_tile=tile)
             binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, tB)
             whole = bufC.cpu().numpy()
             assert np.array_equal(whole[:, :N].astype(np.float64), ref)
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
-        os.environ.pop("GEMMF32_FORCE_TILE", None)
+        binding.set_test_hooks(force_tile=None)
 
 
 def test_random_batched_shapes_bit_exact():
@@ -91,13 +91,13 @@ def test_random_batched_shapes_bit_exact():
             ref = oracle.gemm_f32_batched(A, B, transB=tB, nthreads=NTHREADS)
             dC = torch.full((batch, M, N), float("nan"), device="cuda")
             if tile is None:
-                os.environ.pop("GEMMF32_FORCE_TILE", None)
+                binding.set_test_hooks(force_tile=None)
             else:
-                os.environ["GEMMF32_FORCE_TILE"] = tile
+                binding.set_test_hooks(force_tile=tile)
             binding.gemm_f32_batched(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, transB=tB)
             assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
     finally:
-        os.environ.pop("GEMMF32_FORCE_TILE", None)
+        binding.set_test_hooks(force_tile=None)
 
 
 def test_narrow_b_stored_k_by_n_bit_exact():
@@ -123,15 +123,15 @@ def test_narrow_b_stored_k_by_n_bit_exact():
             dB, _ = padded_dev(B, int(rng.choice([0, 1, 4, 7])))
             dC, bufC = padded_dev(C0, int(rng.choice([0, 5])))
             if tile is None:
-                os.environ.pop("GEMMF32_FORCE_TILE", None)
+                binding.set_test_hooks(force_tile=None)
             else:
-                os.environ["GEMMF32_FORCE_TILE"] = tile
+                binding.set_test_hooks(force_tile=tile)
             binding.gemm_f32_ex(dA, dB, dC, alpha, beta, tA, False)
             whole = bufC.cpu().numpy()
             assert np.array_equal(whole[:, :N].astype(np.float64), ref)
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
-        os.environ.pop("GEMMF32_FORCE_TILE", None)
+        binding.set_test_hooks(force_tile=None)
 
 
 def test_thin_products_vector_unit_kernel_bit_exact():
@@ -141,7 +141,7 @@ def test_thin_products_vector_unit_kernel_bit_exact():
     behind every row of both operands, alpha / beta, padded C.  Exact on integer operands.  The last
     case is one the dispatch sends there by itself."""
     rng = np.random.default_rng(41)
-    os.environ["GEMMF32_FORCE_THIN"] = "1"
+    binding.set_test_hooks(force_thin=True)
     try:
         for idx in range(40):
             S = int(rng.integers(1, 9))
@@ -164,7 +164,7 @@ def test_thin_products_vector_unit_kernel_bit_exact():
             assert np.array_equal(whole[:, :N].astype(np.float64), ref)
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
-        os.environ.pop("GEMMF32_FORCE_THIN", None)
+        binding.set_test_hooks(force_thin=None)
     M, N, K = 3, 4100, 8200
     assert binding.variant_name(M, N, K, transB=True) == "thin3x4/nt"
     A = synth.small_ints((M, K), 9900, synth.TENSOR_A)
