@@ -23,7 +23,8 @@
  *     it and replaced by a larger one when a later call needs more (at most
  *     256 MiB per stream; GEMMF32_ENOMEM if the allocation fails); no call frees
  *     memory or waits for the device.  gemm_f32_reserve_workspace sizes it ahead
- *     of time and gemm_f32_shutdown releases everything.
+ *     of time, gemm_f32_shutdown releases everything, and gemm_f32_noalloc is the
+ *     entry point for callers that must not allocate at all.
  *   - Row-major storage with element strides (BLAS style):
  *       A   M x K, element (i,k) at A[i*lda + k],              lda >= max(K,1)
  *       B   transB == 0: K x N, element (k,j) at B[k*ldb + j], ldb >= max(N,1)
@@ -65,7 +66,8 @@ typedef enum {
     GEMMF32_ENULL = -2,   /* a required pointer is NULL */
     GEMMF32_EALIAS = -3,  /* C is the same buffer as A or B */
     GEMMF32_ELAUNCH = -4, /* the HIP runtime refused; see gemm_f32_last_hip_error */
-    GEMMF32_ENOMEM = -5   /* the workspace could not be allocated */
+    GEMMF32_ENOMEM = -5,  /* the workspace could not be allocated */
+    GEMMF32_ESCRATCH = -6 /* gemm_f32_noalloc: the product needs more scratch than the fixed array holds */
 } gemmf32_status;
 
 /*
@@ -156,6 +158,26 @@ int gemm_f32_set_stream(void *hip_stream);
  * Allocates (hipMalloc) unless the workspace is already that large.
  */
 int gemm_f32_reserve_workspace(size_t bytes);
+
+/*
+ * gemm_f32 for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and the same result, bit for bit, as gemm_f32; the
+ * partial products of a split K or a split last round go to a fixed array of
+ * gemm_f32_noalloc_scratch_bytes() (32 MiB) in the library's code object, one
+ * copy per device, instead of the allocated workspace.  The call allocates and
+ * frees nothing.  A product whose split needs more than the array holds is
+ * refused with GEMMF32_ESCRATCH and nothing is launched (gemm_f32 serves it).
+ * Every call on a device shares that device's array, whatever its stream:
+ * calls that may overlap in time on one device race on it and must be ordered
+ * by the caller.  Nothing in the array needs clearing between calls: the
+ * second pass reads only what the first pass of the same call has written.
+ */
+int gemm_f32_noalloc(int64_t M, int64_t N, int64_t K,
+                     const float *A, int64_t lda,
+                     const float *B, int64_t ldb,
+                     float *C, int64_t ldc, int transB);
+size_t gemm_f32_noalloc_scratch_bytes(void);
 
 /* Static, never-NULL description of a status code. */
 const char *gemm_f32_strerror(int status);

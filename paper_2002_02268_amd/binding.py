@@ -29,6 +29,8 @@ SYMBOLS = {
     "gemm_f32_packed": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _ptr, _i64]),
     "gemm_f32_set_stream": (ctypes.c_int, [_ptr]),
     "gemm_f32_reserve_workspace": (ctypes.c_int, [ctypes.c_size_t]),
+    "gemm_f32_noalloc": (ctypes.c_int, [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
+    "gemm_f32_noalloc_scratch_bytes": (ctypes.c_size_t, []),
     "gemm_f32_set_test_hooks": (ctypes.c_int, [_ptr]),
     "gemm_f32_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "gemm_f32_last_hip_error": (ctypes.c_int, []),
@@ -121,6 +123,24 @@ def gemm_f32(A, B, C, transB: bool = False) -> None:
     _use_current_stream(C)
     _check(lib().gemm_f32(M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), C.data_ptr(), _ld(C),
                           int(bool(transB))))
+
+
+def gemm_f32_noalloc(A, B, C, transB: bool = False) -> None:
+    """gemm_f32 through the entry point that allocates nothing (fixed scratch array)."""
+    A = _dev_f32(A, "A", 2)
+    B = _dev_f32(B, "B", 2)
+    C = _dev_f32(C, "C", 2)
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    if (B.shape[1] if transB else B.shape[0]) != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _use_current_stream(C)
+    _check(lib().gemm_f32_noalloc(M, N, K, A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), C.data_ptr(), _ld(C),
+                                  int(bool(transB))))
+
+
+def gemm_f32_noalloc_scratch_bytes() -> int:
+    return int(lib().gemm_f32_noalloc_scratch_bytes())
 
 
 def gemm_f32_reserve_workspace(nbytes: int, device=None) -> None:

@@ -18,6 +18,10 @@
 
 using namespace gemmf32;
 
+// Scratch of gemm_f32_noalloc (see there): a fixed array in the code object, one copy per device.
+constexpr size_t kScratchBytes = 32u << 20;
+static __device__ __align__(256) float scratch[kScratchBytes / sizeof(float)];
+
 namespace {
 
 // Each host thread has its own current stream, so threads that drive different streams do not
@@ -385,6 +389,28 @@ int acquire_workspace(size_t bytes, float **out)
     return GEMMF32_OK;
 }
 
+// Scratch of the entry point that allocates nothing: a fixed array in the code object, one copy per
+// device.  Host code must not use the array's name as an address; the device address is looked up once
+// per device, with that device current.
+constexpr int kMaxDevices = 64;
+std::atomic<float *> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(float **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return GEMMF32_EINVAL;
+    float *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) return fail_hip(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return GEMMF32_OK;
+}
+
 int check_common(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, int amode,
                  const float *B, const float *C, int64_t ldc)
 {
@@ -565,14 +591,16 @@ int launch_thin(const Plan &pl)
     }
 }
 
-int run_plan(const Plan &pl)
+// static_only: the workspace is the fixed scratch array and nothing is allocated
+int run_plan(const Plan &pl, bool static_only = false)
 {
     if (pl.status != GEMMF32_OK) return pl.status;
     if (!pl.launch) return GEMMF32_OK;
     if (pl.thin != 0) return launch_thin(pl);
     float *workspace = nullptr;
     if (pl.workspace_bytes > 0) {
-        const int rc = acquire_workspace(pl.workspace_bytes, &workspace);
+        if (static_only && pl.workspace_bytes > kScratchBytes) return GEMMF32_ESCRATCH;
+        const int rc = static_only ? static_scratch(&workspace) : acquire_workspace(pl.workspace_bytes, &workspace);
         if (rc != GEMMF32_OK) return rc;
     }
     if (pl.split <= 1 && pl.tail_tiles > 0 && pl.args.quad == 0) {
@@ -783,6 +811,7 @@ const char *gemm_f32_strerror(int status)
     case GEMMF32_EALIAS: return "output aliases an input";
     case GEMMF32_ELAUNCH: return "HIP runtime error (see gemm_f32_last_hip_error)";
     case GEMMF32_ENOMEM: return "out of memory";
+    case GEMMF32_ESCRATCH: return "the product needs more scratch memory than the allocation-free entry point holds";
     default: return "unknown status";
     }
 }
@@ -806,6 +835,15 @@ int gemm_f32_reserve_workspace(size_t bytes)
     if (bytes == 0) return GEMMF32_OK;
     float *unused = nullptr;
     return acquire_workspace(bytes, &unused);
+}
+
+size_t gemm_f32_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+int gemm_f32_noalloc(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                     float *C, int64_t ldc, int transB)
+{
+    if (transB != 0 && transB != 1) return GEMMF32_EINVAL;
+    return run_plan(make_plan(1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, transB ? B_NT : B_NN), true);
 }
 
 int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)

@@ -213,3 +213,5 @@ def test_test_hooks_validate_and_reset():
         assert binding.variant_name(4096, 4096, 4096).startswith("t256x256x16")
     finally:
         os.environ.pop("GEMMF32_FORCE_TILE")
+    assert lib.gemm_f32_noalloc_scratch_bytes() == 32 << 20
+    assert lib.gemm_f32_strerror(-6).decode().startswith("the product needs more scratch")
