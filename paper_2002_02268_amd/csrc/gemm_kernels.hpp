@@ -691,6 +691,35 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     auto cols_ok = [&](int gj, int n) { return SHIFTED ? gj >= n_own : (EDGE == 0 || gj + n <= N); };
     const float alpha = p.alpha, beta = p.beta;
     const bool add_old = (beta != 0.f);                      // uniform over the grid
+    // Tiles addressed through 32-bit offsets (BUF) store the same way: through a buffer descriptor based
+    // at the tile's origin in C, with the row's byte offset (a compile-time row number times ldc) in a
+    // scalar register and one 32-bit byte offset per lane, computed once.  A store then needs no vector
+    // address arithmetic; 64-bit per-lane products for every element took about as long as the stores
+    // themselves.  run_tile sends a tile here only if (BM - 1) * ldc + BN fits 30 bits.
+    [[maybe_unused]] __amdgpu_buffer_rsrc_t c_rsrc;
+    if constexpr (BUF)
+        c_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(uniform_pointer(C + (int64_t)m0 * p.ldc + n0)), 0, -1,
+                                                   0x00020000);
+    [[maybe_unused]] const int ldc32 = (int)p.ldc;
+    // element(s) at row `crow` (uniform), lane byte offset `off`: C = alpha * value (+ beta * C_old)
+    auto put = [&](auto old_tag, int crow, unsigned off, auto value) {
+        typedef decltype(value) V;
+        constexpr bool ADD_OLD = decltype(old_tag)::value;
+        const int row_bytes = crow * ldc32 * 4;
+        V o = alpha * value;
+        if constexpr (std::is_same<V, float>::value) {
+            if constexpr (ADD_OLD) o += beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(c_rsrc, (int)off, row_bytes, 0));
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, o), c_rsrc, (int)off, row_bytes, 0);
+        } else if constexpr (sizeof(V) == 8) {
+            typedef unsigned u2 __attribute__((ext_vector_type(2)));
+            if constexpr (ADD_OLD) o += beta * __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(c_rsrc, (int)off, row_bytes, 0));
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, o), c_rsrc, (int)off, row_bytes, 0);
+        } else {
+            typedef unsigned u4 __attribute__((ext_vector_type(4)));
+            if constexpr (ADD_OLD) o += beta * __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(c_rsrc, (int)off, row_bytes, 0));
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, o), c_rsrc, (int)off, row_bytes, 0);
+        }
+    };
     if constexpr (T::WGK > 1) {
         // the waves hold partial sums of the same tile: through LDS (element (r, c) of wave w at
         // red[w][r * (BN + 1) + c]), added in wave order, stored by all threads
@@ -709,9 +738,30 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                     red[kq * RW + r * RS + c] = acc[i][j][v];
                 }
         __syncthreads();
+        constexpr int PASS_ROWS = NTHR / BN;                  // rows one pass of all threads covers
+        const int li = tid / BN, lj = tid % BN;
+        if constexpr (BUF) {
+            const unsigned off = (unsigned)(li * ldc32 + lj) * 4u;
+            const int row_lo = SHIFTED ? m_own - m0 - li : 0;                 // this lane stores rows crow in [row_lo, row_hi)
+            const int row_hi = (EDGE != 0) ? M - m0 - li : BM;
+            const bool col_ok = cols_ok(n0 + lj, 1);
+            auto pass = [&](auto old_tag) {
+#pragma unroll
+                for (int t = 0; t < BM / PASS_ROWS; ++t) {
+                    const int crow = PASS_ROWS * t;
+                    float sum = red[(li + crow) * RS + lj];
+#pragma unroll
+                    for (int w = 1; w < T::WGK; ++w) sum += red[w * RW + (li + crow) * RS + lj];
+                    if (col_ok && crow >= row_lo && crow < row_hi) put(old_tag, crow, off, sum);
+                }
+            };
+            if (add_old) pass(std::true_type{});
+            else pass(std::false_type{});
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < BM * BN / NTHR; ++t) {
-            const int e = tid + NTHR * t, i = e / BN, j = e % BN;
+            const int i = li + PASS_ROWS * t, j = lj;
             const int gi = m0 + i, gj = n0 + j;
             float sum = red[i * RS + j];
 #pragma unroll
@@ -723,6 +773,53 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 *dst = r;
             }
         }
+        return;
+    }
+    if constexpr (BUF) {
+        const int lane_row = wm0 + (A_KMAJOR ? 4 : 4 * MB) * half;
+        const int lane_col = wn0 + (T::BMODE == B_NT ? l32 : NB * l32);
+        const unsigned off = (unsigned)(lane_row * ldc32 + lane_col) * 4u;
+        const int row_lo = SHIFTED ? m_own - m0 - lane_row : 0;                // rows crow in [row_lo, row_hi) are this lane's to store
+        const int row_hi = (EDGE != 0) ? M - m0 - lane_row : BM;
+        bool col_ok[NB], all_cols = true;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            col_ok[j] = cols_ok(n0 + lane_col + (T::BMODE == B_NT ? 32 * j : j), 1);
+            all_cols = all_cols && col_ok[j];
+        }
+        auto pass = [&](auto old_tag) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int crow = A_KMAJOR ? 32 * i + 8 * (v / 4) + (v % 4) : MB * (8 * (v / 4) + (v % 4)) + i;
+                    const bool rok = crow >= row_lo && crow < row_hi;
+                    if constexpr (T::BMODE == B_NT) {
+#pragma unroll
+                        for (int j = 0; j < NB; ++j)
+                            if (rok && col_ok[j]) put(old_tag, crow, off + 128u * j, acc[i][j][v]);
+                    } else {
+                        bool done = false;
+                        if constexpr (NB > 1) {
+                            if (rok && all_cols) {
+                                vnb o;
+#pragma unroll
+                                for (int j = 0; j < NB; ++j) o[j] = acc[i][j][v];
+                                put(old_tag, crow, off, o);
+                                done = true;
+                            }
+                        }
+                        if (!done) {
+#pragma unroll
+                            for (int j = 0; j < NB; ++j)
+                                if (rok && col_ok[j]) put(old_tag, crow, off + 4u * j, acc[i][j][v]);
+                        }
+                    }
+                }
+            }
+        };
+        if (add_old) pass(std::true_type{});
+        else pass(std::false_type{});
         return;
     }
 #pragma unroll
@@ -791,7 +888,8 @@ __device__ __forceinline__ void run_tile(const KArgs &q, float *lds, int batch, 
     const int64_t b_span = (T::BMODE == B_NT)   ? (int64_t)(T::BN - 1) * q.ldb + T::BK
                            : (T::BMODE == B_NN) ? (int64_t)(T::BK - 1) * q.ldb + T::BN
                                                 : ((int64_t)((T::BN + kPanel - 1) / kPanel) * q.k_panel + T::BK) * kPanel;
-    const bool offsets_fit_32 = a_span < kSpanLimit && b_span < kSpanLimit;
+    const int64_t c_span = (int64_t)(T::BM - 1) * q.ldc + T::BN;            // the epilogue of these paths: 32-bit offsets into C too
+    const bool offsets_fit_32 = a_span < kSpanLimit && b_span < kSpanLimit && c_span < kSpanLimit;
     // an edge tile can be moved back inside the matrix unless the matrix is shorter than a tile
     // (packed B: columns come in whole panels, so only rows move)
     const bool can_shift = (!m_edge || q.M >= T::BM) && (!n_edge || (T::BMODE != B_PACKED && q.N >= T::BN));
