@@ -272,6 +272,81 @@ def survey(torch, binding, synth, random_shapes=40, seed=3):
             "geomean_ratio": round(geo, 3), "worst_ratio": max(ratios), "best_ratio": min(ratios)}
 
 
+AUDIT_FIXED = [(1024, 1024, 1024, False), (1000, 1030, 999, False), (2048, 2048, 2048, True), (4096, 4096, 4096, False),
+               (1100, 1100, 1100, False), (1536, 1536, 1536, False), (640, 640, 2048, False), (8192, 32, 8192, False)]
+NUM_TILES = 13
+
+
+def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.0):
+    """Guard of the dispatch's cost model: for the fixed shapes above and seeded random ones (M, N log-uniform in
+    32..4096, K in 64..8192, either layout of B) the time of the dispatch's own choice against every tile forced
+    in turn (each with the split the model picks for it).  A shape fails when the choice takes more than
+    `tolerance` times the best forced tile and more than `slack_us` longer.  Best of three windows each."""
+    import math
+    import random
+    rng = random.Random(seed)
+    shapes = list(AUDIT_FIXED)
+    while len(shapes) < len(AUDIT_FIXED) + random_shapes:
+        M, N, K = (int(round(math.exp(rng.uniform(math.log(a), math.log(b))))) for a, b in ((32, 4096), (32, 4096), (64, 8192)))
+        if 2.0 * M * N * K <= 4e10:
+            shapes.append((M, N, K, rng.random() < 0.5))
+
+    def best_us(fn, flops):
+        # the chip needs tens of milliseconds of work to reach its steady clock after idling (allocation,
+        # the previous shape's host work): 30 ms untimed, then three windows of about 10 ms each
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 0.03:
+            fn()
+            n += 1
+            if n % 50 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        once = (time.perf_counter() - t0) / n
+        reps = int(max(20, min(2000, 0.01 / max(once, 1e-6))))
+        per = []
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            per.append(a.elapsed_time(b) / reps * 1e3)
+        return min(per)
+
+    torch.manual_seed(seed)
+    rows, failures = [], 0
+    try:
+        for M, N, K, tB in shapes:
+            A = torch.rand(M, K, device="cuda") * 2 - 1
+            B = (torch.rand(N, K, device="cuda") if tB else torch.rand(K, N, device="cuda")) * 2 - 1
+            C = torch.empty(M, N, device="cuda")
+            fn = lambda: binding.gemm_f32(A, B, C, transB=tB)
+            binding.set_test_hooks()
+            chosen = binding.variant_name(M, N, K, transB=tB)
+            t_chosen = best_us(fn, 2.0 * M * N * K)
+            forced = {}
+            for tile in range(NUM_TILES):
+                binding.set_test_hooks(force_tile=tile)
+                name = binding.variant_name(M, N, K, transB=tB)
+                forced[name] = round(best_us(fn, 2.0 * M * N * K), 2)
+            binding.set_test_hooks()
+            best_name = min(forced, key=forced.get)
+            t_best = min(forced[best_name], t_chosen)
+            ok = t_chosen <= tolerance * t_best or t_chosen - t_best <= slack_us
+            failures += 0 if ok else 1
+            rows.append({"M": M, "N": N, "K": K, "transB": tB, "chosen": chosen, "us": round(t_chosen, 2),
+                         "best": best_name, "best_us": forced[best_name], "ratio": round(t_chosen / t_best, 3), "ok": ok,
+                         "forced": forced})
+            del A, B, C
+    finally:
+        binding.set_test_hooks()
+    ratios = [r["ratio"] for r in rows]
+    return {"audit": rows, "shapes": len(rows), "seed": seed, "tolerance": tolerance, "slack_us": slack_us,
+            "mean_ratio": round(sum(ratios) / len(ratios), 3), "worst_ratio": max(ratios), "failures": failures}
+
+
 def protocol(torch, binding, synth):
     """Every workload timed the long way: 10 warm-up launches, then windows of R back-to-back launches
     between two events on the launch stream (R sized for a window of at least 50 ms, at least 100
@@ -376,6 +451,9 @@ def main() -> int:
     ap.add_argument("--protocol", action="store_true",
                     help="time every workload in 20 windows of at least 50 ms (median and best), the latency of one "
                          "square1024 launch, and the batched workload with operands streamed from HBM; one JSON object")
+    ap.add_argument("--audit", action="store_true",
+                    help="guard of the cost model: on about 34 shapes, the dispatch's choice against every tile forced in "
+                         "turn; one JSON object; exit status 3 if a choice is more than 10 %% and 1 us behind the best tile")
     ap.add_argument("--sources-sha256", action="store_true", help="print the kernel source hash and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
@@ -413,6 +491,11 @@ def main() -> int:
     if args.survey:
         print(json.dumps(survey(torch, binding, synth)))
         return 0
+
+    if args.audit:
+        res = audit(torch, binding)
+        print(json.dumps(res))
+        return 3 if res["failures"] else 0
 
     if args.ladder_pass:
         w = synth.WORKLOADS[args.workload]

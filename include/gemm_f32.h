@@ -192,7 +192,8 @@ void gemm_f32_shutdown(void);
  * Which kernel variant the dispatcher would run for a shape, as a string such as
  * "t256x256x16/nn/a16", "t64x64x64/nn/a16/splitk32" (K split into 32 ranges) or
  * "t64x64x64/nn/a4/tail16x8" (the 16 tiles of the last round split into 8 K ranges each) or
- * "t64x64x32/nn/a4/quad16" (the 16 tiles of the last round computed as 32 x 32 blocks); for
+ * "t64x64x32/nn/a4/quad16" (the 16 tiles of the last round computed as 32 x 32 blocks) or
+ * "t64x64x64/nn/a4/strip6" (the last 6 columns of C computed in the vector unit beside the tiles); for
  * diagnostics and benchmarks.  The pointers are only inspected for alignment and may be NULL for
  * "aligned".  The string lives in a per-thread buffer that the next call on the thread overwrites.
  */

@@ -25,6 +25,7 @@ extern "C" {
  *   no_kshare      the 32x32x64 tile only for outputs at most 32 wide, not for outputs of a few hundred blocks
  *   no_thin        never the vector-unit kernel for products with at most 4 rows or columns
  *   force_thin     that kernel wherever it can run (at most 8 rows or columns, both operands with k contiguous)
+ *   no_strip       never the vector-unit strip for the last few columns of C: they take an edge tile column
  * gemm_f32_set_test_hooks(NULL) restores production.  Returns GEMMF32_EINVAL for values out of range
  * (nothing is changed then).  Changing the hooks while another thread is inside a call is a race in the
  * sense that the call may see the old or the new setting, never a mixture that is invalid.
@@ -38,6 +39,7 @@ typedef struct {
     int32_t no_kshare;
     int32_t no_thin;
     int32_t force_thin;
+    int32_t no_strip;
 } gemmf32_test_hooks;
 
 int gemm_f32_set_test_hooks(const gemmf32_test_hooks *hooks);

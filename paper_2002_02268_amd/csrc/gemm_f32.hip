@@ -119,11 +119,11 @@ struct Choice { int tile; int split; };
 // expressed as extra columns of K.
 struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
 const VariantModel kCandidates[] = {
-    {T256, 0.975, 0.975, 70, 70},     {T256x128, 0.965, 0.965, 96, 45}, {T128x256, 0.965, 0.965, 96, 45},
-    {T128, 0.958, 0.958, 72, 25},     {T128x64, 0.959, 0.95, 174, 52},  {T64x128, 0.955, 0.95, 154, 52},
-    {TB64, 0.906, 0.93, 322, 98},     {T64, 0.873, 0.916, 266, 40},
-    {T128x32, 0.88, 0.88, 330, 120},  {T32x128, 0.88, 0.88, 330, 120},
-    {TQ32, 0.775, 0.775, 700, 200},   {TQ64x32, 0.87, 0.86, 350, 80},   {TQ32x64, 0.87, 0.86, 350, 80}};
+    {T256, 0.975, 0.976, 63, 53},      {T256x128, 0.956, 0.962, 71, 27},  {T128x256, 0.957, 0.965, 72, 26},
+    {T128, 0.967, 0.976, 103, 40},     {T128x64, 0.958, 0.973, 159, 69},  {T64x128, 0.950, 0.972, 153, 64},
+    {TB64, 0.947, 0.963, 259, 110},    {T64, 0.904, 0.954, 213, 90},
+    {T128x32, 0.898, 0.933, 223, 294}, {T32x128, 0.895, 0.797, 223, 110},
+    {TQ32, 0.715, 0.837, 510, 241},    {TQ64x32, 0.874, 0.900, 429, 188}, {TQ32x64, 0.857, 0.919, 440, 245}};
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -147,18 +147,33 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 struct Hooks {
     bool no_tail_split, no_quad, no_kshare, no_thin, force_thin;
     int force_tile, force_split;       // -1: not forced
+    bool no_strip;
 };
 struct HookState {
     std::atomic<int> force_tile{-1}, force_split{-1};
-    std::atomic<int> no_tail_split{0}, no_quad{0}, no_kshare{0}, no_thin{0}, force_thin{0};
+    std::atomic<int> no_tail_split{0}, no_quad{0}, no_kshare{0}, no_thin{0}, force_thin{0}, no_strip{0};
 } g_hooks;
 Hooks read_hooks()
 {
     const auto get = [](const std::atomic<int> &a) { return a.load(std::memory_order_relaxed); };
     return Hooks{get(g_hooks.no_tail_split) != 0, get(g_hooks.no_quad) != 0, get(g_hooks.no_kshare) != 0,
                  get(g_hooks.no_thin) != 0,       get(g_hooks.force_thin) != 0, get(g_hooks.force_tile),
-                 get(g_hooks.force_split)};
+                 get(g_hooks.force_split),        get(g_hooks.no_strip) != 0};
 }
+
+// Columns of C left to the strip workgroups (kernel header, KArgs): when N is at most kStripMax columns more
+// than whole tiles, one product, no K ranges, A stored M x K, B not packed, a tile of four waves that each own
+// blocks.  0: no strip (the last tile column is an edge tile).
+int strip_cols(const Hooks &hooks, int tile, int64_t batch, int64_t N, int bmode, int amode)
+{
+    const TileShape &sh = kShapes[tile];
+    if (hooks.no_strip || batch != 1 || amode != A_MK || bmode == B_PACKED) return 0;
+    if (sh.waves_k != 1 || sh.waves_m * sh.waves_n != 4) return 0;
+    const int64_t rest = N % sh.bn;
+    return (N >= sh.bn && rest >= 1 && rest <= kStripMax) ? (int)rest : 0;
+}
+// (the strip addresses a B stored K x N with 32-bit byte offsets)
+bool strip_fits(int64_t K, int64_t ldb, int bmode) { return bmode != B_NN || (K + 1024) * ldb < (1LL << 30); }
 
 struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; bool quad; };
 
@@ -182,7 +197,8 @@ TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t t
     // (only tiles whose waves each own a block have the block kernel: the kernel header's QuadOf)
     if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && kShapes[tile].waves_k == 1 && !hooks.no_quad) {
         const double t_block = 5.0 + 0.0018 * (double)K;
-        quad_benefit = t_full - std::max(1.0, (double)(t.tail * subs) / 256.0) * t_block;
+        // (whole rounds of blocks: with 272 blocks some compute unit gets two, and the round takes twice as long)
+        quad_benefit = t_full - (double)cdiv(t.tail * subs, 256) * t_block;
     }
     double range_benefit = 0.0;
     if (S > 1 && t.tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
@@ -228,7 +244,7 @@ Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int6
     const int forced_tile = hooks.force_tile >= 0 ? hooks.force_tile : g_forced_tile;
     const int forced_split = hooks.force_split >= 1 ? hooks.force_split : g_forced_split;
     const ChoiceKey key = {batch, M, N, K, bmode, amode, forced_tile, forced_split,
-                           (hooks.no_tail_split ? 1 : 0) | (hooks.no_quad ? 2 : 0) | (hooks.no_kshare ? 4 : 0)};
+                           (hooks.no_tail_split ? 1 : 0) | (hooks.no_quad ? 2 : 0) | (hooks.no_kshare ? 4 : 0) | (hooks.no_strip ? 8 : 0)};
     const uint64_t h = ((uint64_t)M * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)N * 0xC2B2AE3D27D4EB4Full) ^
                        ((uint64_t)K * 0x165667B19E3779F9ull) ^ ((uint64_t)batch * 0x27D4EB2F165667C5ull);
     ChoiceSlot &slot = g_choice_cache[h >> 58];
@@ -248,7 +264,10 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         if (forced_tile >= 0 && c.id != forced_tile) continue;
         // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
         // are for outputs that are no wider, where the others would compute padding
-        if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32))) continue;
+        // (measured: beyond one round of workgroups they still pay where their tile count fits the chip better,
+        // 1100^3 25 against 30 us; they stay out of outputs of more than 2048 tiles, where the traffic counts)
+        if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32)) &&
+            cdiv(M, kShapes[c.id].bm) * cdiv(N, kShapes[c.id].bn) > 2048) continue;
         // One 32 x 32 block per workgroup with the slab shared between its waves: for outputs at most 32
         // wide whose operands need no element-wise masking (a B stored K x N with fewer than 32 columns
         // does, and so does an A stored K x M with fewer than 32 rows).  Where it
@@ -274,7 +293,8 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
         // 21 -> 18.3 us).
         if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && (kshare || !kshare_general || b_streams_narrow)) continue;
         const TileShape &sh = kShapes[c.id];
-        const int64_t tiles = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
+        const int strip = strip_cols(hooks, c.id, batch, N, bmode, amode);       // only without K ranges (and taken to fit: see strip_fits)
+        const int64_t tiles_whole = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
         for (int S : kSplits) {
             if (forced_split >= 1) S = forced_split;
@@ -284,6 +304,7 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
                 if ((int64_t)S * M * N * 4 > kMaxWorkspaceBytes) break;
             }
             const double k_range = (double)cdiv(cdiv(K, S), sh.bk) * sh.bk;
+            const int64_t tiles = (S == 1 && strip > 0) ? cdiv(M, sh.bm) * (N / sh.bn) : tiles_whole;
             const int64_t wgs = tiles * S;
             // two workgroups of the two-block shared-slab tiles fit a compute unit; measured, they pay while all
             // of them are resident at once (1024^3: 512 workgroups, 19.3 us) and not beyond (648 x 3072 x 752:
@@ -306,11 +327,16 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             // and fewer fixed costs is still the faster: a small share of the compute cost breaks the tie)
             cost = std::max(cost, hbm_us) + 0.02 * cost;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
+            // the strip runs beside the tiles (measured: about half a microsecond on the launch); a tile that
+            // fills a compute unit's registers leaves it no room, and it runs after the tiles
+            if (S == 1 && strip > 0) cost += (sh.bm * sh.bn >= 256 * 256) ? 6.0 + 0.002 * (double)K : 0.5;
             if (S == 1) cost -= plan_tail_split(hooks, c.id, batch, tiles, K).benefit_us;
             // equal cost (the two orientations of a tile on the same number of rounds): the one that
             // computes less padding
             const double area = (double)wgs * sh.bm * sh.bn;
-            if (best_cost < 0 || cost < best_cost || (cost == best_cost && area < best_area)) {
+            // (a later candidate has to be more than 1 % cheaper: the model is no more exact than that, and
+            // the candidates come largest tile first, fewest K ranges first, which move the fewest bytes)
+            if (best_cost < 0 || cost < 0.99 * best_cost || (cost == best_cost && area < best_area)) {
                 best_cost = cost;
                 best_area = area;
                 best = {c.id, S};
@@ -345,6 +371,7 @@ struct Plan {
     bool vec;
     int thin;            // 0: tiles; 1: at most 8 rows, B streamed by the vector-unit kernel; 2: at most 8 columns, A streamed
     size_t workspace_bytes;   // what the launch needs besides the operands (0: nothing)
+    int strip;                // columns of C computed by the strip workgroups (0: none)
     KArgs args;
 };
 
@@ -464,7 +491,8 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     }
     if (pl.thin != 0) pl.split = 1;             // the arguments below stay those of the whole product
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
-    const int64_t tiles_m = cdiv(M, bm), tiles_n = cdiv(N, bn);
+    const int strip = (pl.split == 1 && pl.thin == 0 && strip_fits(K, ldb, bmode)) ? strip_cols(hooks, pl.tile, batch, N, bmode, amode) : 0;
+    const int64_t tiles_m = cdiv(M, bm), tiles_n = strip > 0 ? N / bn : cdiv(N, bn);
     const int64_t total = (pl.split > 1 ? pl.split : batch) * tiles_m * tiles_n;
     if (total > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
 
@@ -476,7 +504,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     pl.user_ldc = ldc;
     KArgs &a = pl.args;
     a.A = A; a.B = B; a.C = C;
-    a.M = (int)M; a.N = (int)N; a.K = (int)K;
+    a.M = (int)M; a.N = (int)(N - strip); a.K = (int)K;        // with a strip the tiles end where it begins
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.sA = sA; a.sB = sB; a.sC = sC;
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
@@ -526,6 +554,17 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
         if (pl.split == 1) {
             a.K = (int)K; a.k_total = 0; a.sA = a.sB = a.sC = 0; a.ldc = ldc; a.alpha = alpha; a.beta = beta;
         }
+    }
+    a.strip_first = a.total_tiles;
+    pl.strip = strip;
+    if (strip > 0) {
+        a.strip_cols = strip;
+        a.strip_n0 = (int)(N - strip);
+        // as many strip workgroups as compute units where the rows allow it: 1, 2 or 4 rows per wave
+        a.strip_r = M <= 1024 ? 1 : (M <= 2048 ? 2 : 4);
+        const int64_t strip_wgs = cdiv(M, 4 * a.strip_r);
+        if ((int64_t)a.total_tiles + strip_wgs > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
+        a.total_tiles += (int)strip_wgs;
     }
     if (pl.split > 1) pl.workspace_bytes = (size_t)pl.split * (size_t)M * (size_t)N * sizeof(float);
     else if (pl.tail_tiles > 0 && a.quad == 0)
@@ -848,7 +887,7 @@ int gemm_f32_noalloc(int64_t M, int64_t N, int64_t K, const float *A, int64_t ld
 
 int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)
 {
-    const gemmf32_test_hooks off = {-1, 0, 0, 0, 0, 0, 0};
+    const gemmf32_test_hooks off = {-1, 0, 0, 0, 0, 0, 0, 0};
     if (h == nullptr) h = &off;
     if (h->force_tile < -1 || h->force_tile >= NUM_TILES || h->force_split < 0 || h->force_split > 256) return GEMMF32_EINVAL;
     g_hooks.force_tile.store(h->force_tile);
@@ -858,6 +897,7 @@ int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)
     g_hooks.no_kshare.store(h->no_kshare != 0);
     g_hooks.no_thin.store(h->no_thin != 0);
     g_hooks.force_thin.store(h->force_thin != 0);
+    g_hooks.no_strip.store(h->no_strip != 0);
     return GEMMF32_OK;
 }
 
@@ -871,20 +911,19 @@ const char *gemm_f32_variant_name(int64_t M, int64_t N, int64_t K, const float *
     Plan pl = make_plan(1, M, N, K, a, lda, 0, b, ldb, 0, c, ldc, 0, transB ? B_NT : B_NN);
     if (pl.status != GEMMF32_OK) return "invalid";
     if (!pl.launch) return "empty";
-    if (pl.thin != 0)
+    if (pl.thin != 0) {
         std::snprintf(g_variant_buf, sizeof(g_variant_buf), "thin%dx%d/nt", (int)(pl.thin == 1 ? M : N), kThinRows);
-    else if (pl.tail_tiles > 0 && pl.args.quad != 0)
-        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/quad%d", kShapes[pl.tile].name,
-                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles);
-    else if (pl.tail_tiles > 0)
-        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/tail%dx%d", kShapes[pl.tile].name,
-                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.tail_tiles, pl.args.tail_split);
-    else if (pl.split > 1)
-        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s/splitk%d", kShapes[pl.tile].name,
-                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4", pl.split);
-    else
-        std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
-                      pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4");
+        return g_variant_buf;
+    }
+    int n = std::snprintf(g_variant_buf, sizeof(g_variant_buf), "%s/%s/%s", kShapes[pl.tile].name,
+                          pl.bmode == B_NT ? "nt" : "nn", pl.vec ? "a16" : "a4");
+    const auto append = [&](const char *fmt, int x, int y) {
+        if (n > 0 && n < (int)sizeof(g_variant_buf)) n += std::snprintf(g_variant_buf + n, sizeof(g_variant_buf) - n, fmt, x, y);
+    };
+    if (pl.tail_tiles > 0 && pl.args.quad != 0) append("/quad%d", pl.tail_tiles, 0);
+    else if (pl.tail_tiles > 0) append("/tail%dx%d", pl.tail_tiles, pl.args.tail_split);
+    else if (pl.split > 1) append("/splitk%d", pl.split, 0);
+    if (pl.strip > 0) append("/strip%d", pl.strip, 0);
     return g_variant_buf;
 }
 

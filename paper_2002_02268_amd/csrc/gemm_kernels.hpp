@@ -74,6 +74,12 @@ struct KArgs {
     // (tail_split = their number) and a whole workgroup computes one block, its four waves sharing
     // every slab along k and adding up through LDS: a quarter of the tile's time, no second pass.
     int quad;
+    // Strip: when N leaves at most kStripMax columns beyond whole tiles, the tiles cover columns [0, strip_n0)
+    // (N above is strip_n0 then) and the strip_cols columns behind them are computed in the vector unit by
+    // extra workgroups (ids >= strip_first; strip_r = 1, 2 or 4 rows per wave, four waves) that run beside
+    // the tiles: a tile column of matrix work for a handful of columns would cost a whole round.
+    // strip_cols == 0: off, and strip_first is the grid size.
+    int strip_first, strip_cols, strip_n0, strip_r;
     // Epilogue: C = alpha * (A*B) + beta * C_old.  beta == 0: C_old is never read.  The paper's
     // product is alpha = 1, beta = 0.
     float alpha, beta;
@@ -382,8 +388,8 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     auto range_bytes = [&](const float *org, const float *end) {
         const uint64_t d = (uint64_t)((end - org) * 4);                  // never negative
         unsigned hi = (unsigned)(d >> 32);
-        asm volatile("" : "+s"(hi));      // keeps the test on the high word: a 32-bit scalar compare (there is no
-                                          // scalar ordered compare of 64-bit values, and a vector one costs the matrix pipe)
+        hi = __builtin_amdgcn_readfirstlane(hi);   // keeps the test on the high word: a 32-bit scalar compare (there is no
+                                                   // scalar ordered compare of 64-bit values, and a vector one costs the matrix pipe)
         return hi != 0 ? 0xFFFFFFFFu : (unsigned)d;
     };
     // where slot r stands now, as a pointer (for the ragged last slab)
@@ -645,6 +651,58 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     typedef std::integral_constant<int, 1> i1;
     if (nkf > 0) {
         const int last = nkf - 1;
+        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  Their loads are
+        // requested ahead of slabs 0 .. PF, they pass through LDS buffer 1 and are multiplied while
+        // slab 0 is still on its way, so that the ragged part costs one barrier instead of a load
+        // latency of its own at the end.  Every slot is one 16-byte load from a position that lies inside
+        // the operand (columns at or beyond kleft re-read column 0, rows re-read row 0; K >= kleft + BK
+        // here, so the 16 bytes never reach past column K); what lies at or beyond kleft is zeroed in
+        // both operands before it reaches LDS.
+        [[maybe_unused]] v4f ta[A_ITERS], tb[B_ITERS];
+        if (kleft > 0) {
+            static_for<A_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                // k index of the slot's first element, and how far back (in elements) the load moves
+                const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
+                const int64_t back = (k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
+                v4f v;
+                if constexpr (RANGED) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4), range_bytes(org_a, end_a));
+                else if constexpr (BUF) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4));
+                else if constexpr (A_ELEMENTWISE) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (pa[r] - back)[a_d[r][e]];
+                } else v = load4(pa[r] - back);
+                ta[r] = v;
+            });
+            static_for<B_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
+                const int64_t kstride = (T::BMODE == B_NT) ? 1 : (T::BMODE == B_NN ? p.ldb : (int64_t)kPanel);
+                const int64_t back = (k0 < kleft) ? 0 : (int64_t)k0 * kstride;
+                v4f v;
+                if constexpr (RANGED && T::BMODE != B_NN) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4), range_bytes(org_b, end_b));
+                else if constexpr (BUF) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4));
+                else if constexpr (B_ELEMENTWISE) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (pb[r] - back)[b_d[r][e]];
+                } else v = load4(pb[r] - back);
+                tb[r] = v;
+            });
+            // the whole slabs start kleft columns further along k
+            const int64_t a_skip = A_KMAJOR ? (int64_t)kleft : (int64_t)kleft * p.lda;
+            const int64_t b_skip = (T::BMODE == B_NT) ? (int64_t)kleft : (T::BMODE == B_NN ? (int64_t)kleft * p.ldb : (int64_t)kleft * kPanel);
+            if constexpr (BUF) {
+                org_a = uniform_pointer(org_a + a_skip);
+                org_b = uniform_pointer(org_b + b_skip);
+            } else {
+#pragma unroll
+                for (int r = 0; r < A_ITERS; ++r) pa[r] += a_skip;
+#pragma unroll
+                for (int r = 0; r < B_ITERS; ++r) pb[r] += b_skip;
+            }
+        }
         // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
         // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
         typedef std::integral_constant<int, PF> first_set;
@@ -653,6 +711,35 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             constexpr int j = decltype(j_tag)::value + 1;       // slab min(j, last); then on to min(j + 1, last)
             load_slab(std::integral_constant<int, j % PF>{}, j < last);
         });
+        if (kleft > 0) {
+            float *As = lds + T::STAGE_FLOATS, *Bs = As + T::A_TILE;          // buffer 1
+            static_for<A_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
+                v4f v = masked_slot(r_tag, ta[r]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = ((A_KMAJOR ? k0 + e : k0) < kleft) ? v[e] : 0.f;
+                *reinterpret_cast<v4f *>(&As[sa_off[r]]) = v;
+            });
+            static_for<B_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
+                v4f v = masked_slot(std::integral_constant<int, A_ITERS + r>{}, tb[r]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = ((B_KMAJOR ? k0 + e : k0) < kleft) ? v[e] : 0.f;
+                *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = v;
+            });
+            lds_barrier();
+#pragma unroll
+            for (int g = 0; g < GQ; ++g) {
+                if (8 * (GQ * kq + g) < kleft) {
+                    read_frag(f0, 1, g);
+                    mfma_group(f0);
+                }
+            }
+        }
         store_slab(0, first_set{});
         lds_barrier();
         read_frag(f0, 0, 0);
@@ -671,9 +758,9 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             }
         });
     }
-    // ---- ragged last slab (K % BK columns), not pipelined -------------------------------------
-    if (kleft > 0) {
-        load_tail(nkf > 0, kleft);
+    // ---- a K shorter than one slab: its K % BK columns, not pipelined ----------------------------
+    if (kleft > 0 && nkf == 0) {
+        load_tail(false, kleft);
         __syncthreads();                           // everyone is done reading both buffers
         store_slab(0, i0{});
         __syncthreads();
@@ -700,7 +787,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     if constexpr (BUF)
         c_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(uniform_pointer(C + (int64_t)m0 * p.ldc + n0)), 0, -1,
                                                    0x00020000);
-    [[maybe_unused]] const int ldc32 = (int)p.ldc;
+    [[maybe_unused]] const int ldc32 = __builtin_amdgcn_readfirstlane((int)p.ldc);   // uniform; said so, as the row offsets below must be scalar
     // element(s) at row `crow` (uniform), lane byte offset `off`: C = alpha * value (+ beta * C_old)
     auto put = [&](auto old_tag, int crow, unsigned off, auto value) {
         typedef decltype(value) V;
@@ -913,21 +1000,164 @@ __device__ __forceinline__ void run_tile(const KArgs &q, float *lds, int batch, 
 template <class T, bool = (T::BM * T::BN <= 128 * 64 && T::THREADS == 256 && T::WGK == 1)> struct QuadOf { typedef void type; };
 template <class T> struct QuadOf<T, true> { typedef Tile<32, 32, 64, 1, 1, T::BMODE, T::OCC, 2, T::AMODE, 4> type; };
 
+// The strip of a product (see KArgs): C[i][n0 + s] = sum_k A[i][k] * opB[k][n0 + s] for s < S <= kStripMax, A
+// stored M x K.  A wave takes R consecutive rows of C; its lanes stride over k 16 bytes of A at a time, each
+// lane multiplies its four k against the S columns of B (read straight from global memory: 16 bytes along a
+// row of B stored K x N, 16 bytes along k of B stored N x K), and at the end the 64 partial sums of every
+// (row, column) are added across the lanes in a fixed order, so the result does not depend on the launch.
+// No LDS, no barrier: waves are independent.
+// The workgroup shares its compute unit with a tile whose waves issue one matrix instruction after the
+// other; measured, a wave beside them gets to issue about one vector instruction per matrix instruction
+// (64 cycles), whatever its priority, and a round trip to memory takes several microseconds.  So the strip
+// is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows), a wave executes a
+// few hundred instructions in all, and the loads of up to 1024 k are requested before the first is used.
+constexpr int kStripMax = 8;
+template <int BMODE, int R>
+__device__ __forceinline__ void strip_rows(const KArgs &p, const int wg)
+{
+    __builtin_amdgcn_s_setprio(3);                 // its few instructions go first where they can
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int S = p.strip_cols, n0 = p.strip_n0, K = p.K, M = p.M;
+    const int r0 = (wg * 4 + wave) * R;
+    if (r0 >= M) return;
+    const float *x[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int r = (r0 + j < M) ? (r0 + j) : (M - 1);          // rows past the end repeat the last one; not stored
+        x[j] = p.A + (int64_t)r * p.lda + 4 * lane;
+    }
+    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+    float acc[kStripMax][R];
+#pragma unroll
+    for (int s = 0; s < kStripMax; ++s)
+#pragma unroll
+        for (int j = 0; j < R; ++j) acc[s][j] = 0.f;
+    // 16 bytes from src, of which only the first `valid` floats may be touched (the rest read as zero)
+    auto load_some = [&](const float *src, int valid) {
+        v4f v = zero4;
+        if (valid >= 4) v = load4(src);
+        else {
+#pragma unroll
+            for (int e = 0; e < 3; ++e)
+                if (e < valid) v[e] = src[e];
+        }
+        return v;
+    };
+    constexpr int BATCH = (R == 4) ? 2 : 4;        // groups of 256 k requested together (what the registers hold)
+    // (B stored K x N is addressed with 32-bit offsets from its first strip column: the plan sends a product
+    // here only if K * ldb * 4 fits 32 bits)
+    [[maybe_unused]] const int ldb32 = __builtin_amdgcn_readfirstlane((int)p.ldb);
+    for (int k0 = 0; k0 < K; k0 += 256 * BATCH) {
+        [[maybe_unused]] const float *y_org = nullptr;
+        [[maybe_unused]] unsigned y_lane = 0;
+        if constexpr (BMODE == B_NN) {
+            y_org = uniform_pointer(p.B + (int64_t)k0 * p.ldb + n0);
+            y_lane = (unsigned)(4 * lane * ldb32) * 4u;
+        }
+        v4f xv[BATCH][R];
+        v4f yv[BATCH][kStripMax];                  // B stored N x K: [column s];  K x N: [2 * e + h]: row k + e, columns 4h ..
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it) {
+            const int kk = k0 + 256 * it + 4 * lane;              // this lane's four k of the group
+#pragma unroll
+            for (int j = 0; j < R; ++j) xv[it][j] = (kk < K) ? load_some(x[j] + k0 + 256 * it, K - kk) : zero4;
+            if constexpr (BMODE == B_NT) {
+#pragma unroll
+                for (int s = 0; s < kStripMax; ++s)
+                    yv[it][s] = (s < S && kk < K) ? load_some(p.B + (int64_t)(n0 + s) * p.ldb + kk, K - kk) : zero4;
+            } else {
+                // rows kk .. kk + 3 of B, columns n0 .. n0 + 7: the lane's offset is one register, the row's and the
+                // group's offsets are scalar (a vector instruction per address would cost more than the product).
+                // The 16 bytes may run past column N into the next row of B, which exists for every row but the
+                // last: that one is read element by element.
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        v4f v = zero4;
+                        if (4 * h < S) {                                  // uniform
+                            if (kk + e + 1 < K) v = buffer_load4(y_org, y_lane + (unsigned)((256 * it + e) * ldb32 + 4 * h) * 4u);
+                            else if (kk + e < K) v = load_some(p.B + (int64_t)(kk + e) * p.ldb + n0 + 4 * h, S - 4 * h);
+                        }
+                        yv[it][2 * e + h] = v;
+                    }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it) {
+            if (k0 + 256 * it < K) {                                      // uniform
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int s = 0; s < kStripMax; ++s) {
+                        if (s < S) {                                      // uniform
+                            const float yy = (BMODE == B_NT) ? yv[it][s][e] : yv[it][2 * e + (s >> 2)][s & 3];
+#pragma unroll
+                            for (int j = 0; j < R; ++j) acc[s][j] = __builtin_fmaf(xv[it][j][e], yy, acc[s][j]);
+                        }
+                    }
+            }
+        }
+    }
+    // Sum over the lanes: value v = R * s + j, NV = 8 * R of them.  Each of the first log2(NV) steps halves the
+    // number of values a lane carries: the lanes whose bit is clear keep the lower half and receive their
+    // partner's partial sums of it, the others the upper half; then a lane carries value
+    // lane >> (6 - log2(NV)), and the remaining steps add the lanes that carry the same value.  A fixed
+    // order of additions, and NV - 1 + (6 - log2(NV)) exchanges instead of 6 per value.
+    constexpr int NV = kStripMax * R;
+    float vals[NV];
+#pragma unroll
+    for (int s = 0; s < kStripMax; ++s)
+#pragma unroll
+        for (int j = 0; j < R; ++j) vals[R * s + j] = acc[s][j];
+    int bit = 32;
+#pragma unroll
+    for (int half = NV / 2; half >= 1; half >>= 1, bit >>= 1) {
+        const bool upper = (lane & bit) != 0;
+#pragma unroll
+        for (int i = 0; i < half; ++i) {
+            const float keep = upper ? vals[i + half] : vals[i];
+            const float send = upper ? vals[i] : vals[i + half];
+            vals[i] = keep + __shfl_xor(send, bit, 64);
+        }
+    }
+    float total = vals[0];
+    constexpr int SAME = 64 / NV;                  // lanes that carry the same value
+#pragma unroll
+    for (int off = SAME / 2; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
+    const int v = lane / SAME, s = v / R, j = v % R;
+    if (lane % SAME == 0 && s < S && r0 + j < M) {
+        float *dst = p.C + (int64_t)(r0 + j) * p.ldc + n0 + s;
+        float out = p.alpha * total;
+        if (p.beta != 0.f) out += p.beta * *dst;
+        *dst = out;
+    }
+}
+
 template <class T>
 __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 {
     extern __shared__ __align__(16) float lds[];
+    if constexpr (T::THREADS == 256 && T::WGK == 1 && T::AMODE == A_MK && T::BMODE != B_PACKED) {
+        if ((int)blockIdx.x >= p.strip_first) {
+            const int wg = (int)blockIdx.x - p.strip_first;
+            if (p.strip_r == 1) strip_rows<T::BMODE, 1>(p, wg);
+            else if (p.strip_r == 2) strip_rows<T::BMODE, 2>(p, wg);
+            else strip_rows<T::BMODE, 4>(p, wg);
+            return;
+        }
+    }
     int batch, tm, tn;
     KArgs q = p;
     // whole tiles first, then the pieces of the split tail; each kind is spread over the XCDs separately
     const bool is_piece = p.tail_split > 1 && (int)blockIdx.x >= p.tail_first;
-    const int logical = is_piece ? 0 : xcd_contiguous_id(blockIdx.x, p.tail_split > 1 ? p.tail_first : p.total_tiles);
+    const int logical = is_piece ? 0 : xcd_contiguous_id(blockIdx.x, p.tail_split > 1 ? p.tail_first : p.strip_first);
     if constexpr (!std::is_void<typename QuadOf<T>::type>::value) {
         if (is_piece && p.quad != 0) {
             // one 32 x 32 block of one tile of the last round, by the whole workgroup
             typedef typename QuadOf<T>::type QT;
             constexpr int SUB_N = T::BN / 32;
-            const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.total_tiles - p.tail_first);
+            const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.strip_first - p.tail_first);
             const int t = piece / p.tail_split, sub = piece - t * p.tail_split;
             tile_coords(p, p.tail_first + t, tm, tn);
             const int qm = tm * (T::BM / 32) + sub / SUB_N, qn = tn * SUB_N + sub % SUB_N;
@@ -938,7 +1168,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     }
     if (is_piece) {
         // one K range of one tile of the last round -> its slot
-        const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.total_tiles - p.tail_first);
+        const int piece = xcd_contiguous_id(blockIdx.x - p.tail_first, p.strip_first - p.tail_first);
         const int t = piece / p.tail_split, s = piece - t * p.tail_split;
         tile_coords(p, p.tail_first + t, tm, tn);
         batch = 0;

@@ -62,7 +62,7 @@ def force_tile():
         else:
             binding.set_test_hooks(force_tile=TILES[name])
     yield _set
-    binding.set_test_hooks(force_tile=None)
+    binding.set_test_hooks()
 
 
 SMALL_SHAPES = [(1, 1, 1), (33, 65, 17), (64, 64, 64), (130, 257, 70), (300, 513, 129), (257, 130, 1), (5, 700, 33)]
@@ -559,16 +559,17 @@ def test_split_tail_bit_exact(force_tile, tile, how, transB):
     whole workgroup whose waves share the slabs along k and add up through LDS.  Exact on integer
     operands; ragged edges (blocks of edge tiles that lie outside the matrix), a K tail, padded C."""
     force_tile(tile)
+    binding.set_test_hooks(no_strip=True)          # these shapes would hand their last columns to the strip
     if how == "tail":
         binding.set_test_hooks(no_quad=True)
-    shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1100, 1100, 1100)],
-              "tb64": [(1000, 1030, 999), (1100, 1100, 1100)], "t128x64": [(2100, 1090, 700), (2200, 1000, 333)],
-              "t64x128": [(1090, 2100, 700)], "tq32": [(520, 530, 3000), (576, 570, 4100)], "tq64x32": [(770, 760, 2100), (1030, 520, 3000)],
+    shapes = {"t128": [(2100, 2200, 1000)], "t64": [(1000, 1030, 999), (1030, 1100, 1100)],
+              "tb64": [(1000, 1030, 999), (1030, 1100, 1100)], "t128x64": [(2000, 1090, 1100), (2200, 1000, 333)],
+              "t64x128": [(1090, 2000, 1100)], "tq32": [(520, 530, 3000), (576, 570, 4100)], "tq64x32": [(770, 760, 2100), (1030, 520, 3000)],
               "tq32x64": [(770, 760, 2100), (1030, 520, 3000)]}[tile]
     try:
         _split_tail_cases(shapes, how, transB)
     finally:
-        binding.set_test_hooks(no_quad=None)
+        binding.set_test_hooks()
 
 
 def _split_tail_cases(shapes, how, transB):
@@ -589,6 +590,7 @@ def _split_tail_cases(shapes, how, transB):
 def test_split_tail_ragged_workload_parity_determinism_and_packed():
     """The ragged workload (272 tiles of 64x64) takes this path: 32 x 32 blocks by default, K ranges
     when those are switched off, whole tiles when both are."""
+    binding.set_test_hooks(no_strip=True)          # (by default the six columns behind 16 tile columns are a strip)
     assert "/quad16" in binding.variant_name(1000, 1030, 999)
     A, B = synth.make_operands("ragged")
     ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
@@ -623,7 +625,70 @@ def test_split_tail_ragged_workload_parity_determinism_and_packed():
         binding.gemm_f32(dA, dB, dC)
         check_close(dC.cpu().numpy(), ref, 999)
     finally:
-        binding.set_test_hooks(no_tail_split=None)
+        binding.set_test_hooks()
+
+
+STRIP_TILES = ["t64", "tb64", "t128", "t128x64", "t64x128", "t128x32", "t32x128", "t256", "t256x128", "t128x256"]
+
+
+@pytest.mark.parametrize("tile", STRIP_TILES)
+@pytest.mark.parametrize("transB", [False, True])
+def test_strip_columns_bit_exact(force_tile, tile, transB):
+    """N a few columns (1..8) more than whole tiles: the tiles stop at the last tile boundary and the columns
+    behind it are computed in the vector unit by extra workgroups of the same launch.  Row counts that are not
+    multiples of the 16 rows a strip workgroup takes, K below one request, ragged, and longer than what the strip
+    stages in LDS at a time; integer operands (exact), NaN in old C and in the padding of all three matrices."""
+    force_tile(tile)
+    binding.set_test_hooks(force_split=1)          # (a long K with a small output would otherwise be split into ranges)
+    BM, BN = TILE_DIMS[tile]
+    cases = [(BM * 2 + 5, BN + 1, 77), (37, BN + 3, 300), (16, 2 * BN + 4, 1), (130, BN + 5, 2500), (BM + 17, BN + 8, 1031),
+             (70, BN + 3, 0)]
+    for idx, (M, N, K) in enumerate(cases):
+        name = binding.variant_name(M, N, K, transB=transB)
+        print(f"strip case tile={tile} transB={transB} M={M} N={N} K={K} {name}", flush=True)
+        assert f"/strip{N % BN}" in name, name
+        A = synth.small_ints((M, K), 600 + idx, synth.TENSOR_A)
+        B = synth.small_ints((N, K) if transB else (K, N), 600 + idx, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+        dA, _ = padded_dev(A, 3)
+        dB, _ = padded_dev(B, 5)
+        dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), 2)
+        binding.gemm_f32(dA, dB, dC, transB=transB)
+        whole = bufC.cpu().numpy()
+        assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+        assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+    binding.set_test_hooks()
+
+
+def test_strip_uniform_operands_scalings_and_switch():
+    """The ragged workload's own shape takes the strip (6 columns behind 16 whole tile columns): within
+    tolerance on U(-1,1) operands, the same bits on every launch, alpha and beta applied, and the same product
+    with the strip switched off (an edge tile column instead) agrees within tolerance."""
+    M, N, K = 1000, 1030, 999
+    assert binding.variant_name(M, N, K).endswith("/strip6")
+    A, B = synth.make_operands("ragged")
+    ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+    dA, dB = dev(A), dev(B)
+    outs = []
+    for _ in range(3):
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(dA, dB, dC)
+        outs.append(dC.cpu().numpy())
+    check_close(outs[0], ref, K)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    C0 = synth.uniform((M, N), 77, synth.TENSOR_X)
+    dC = dev(C0)
+    binding.gemm_f32_ex(dA, dB, dC, alpha=-2.0, beta=0.5)
+    want = -2.0 * ref + 0.5 * C0.astype(np.float64)
+    assert np.abs(dC.cpu().numpy().astype(np.float64) - want).max() <= 2.5e-3
+    binding.set_test_hooks(no_strip=True)
+    try:
+        assert "/strip" not in binding.variant_name(M, N, K)
+        dC = torch.full((M, N), float("nan"), device="cuda")
+        binding.gemm_f32(dA, dB, dC)
+        check_close(dC.cpu().numpy(), ref, K)
+    finally:
+        binding.set_test_hooks(no_strip=None)
 
 
 def test_mfma_rate_probe_runs_and_validates_its_arguments():

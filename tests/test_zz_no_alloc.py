@@ -35,7 +35,7 @@ def test_noalloc_matches_gemm_f32_and_the_oracle_on_calls_in_a_row():
     binding.set_test_hooks()
     lib.gemm_f32_set_stream(None)
     assert binding.gemm_f32_noalloc_scratch_bytes() == 32 << 20
-    expect_scratch = ["splitk", "splitk", "tail", "splitk", "quad", ""]
+    expect_scratch = ["splitk", "splitk", "tail", "splitk", "strip", ""]
     for idx, (M, N, K, transB) in enumerate(SEQUENCE):
         name = binding.variant_name(M, N, K, transB=transB)
         print(f"noalloc case {idx}: M={M} N={N} K={K} transB={transB} {name}", flush=True)
