@@ -108,10 +108,20 @@ struct Tile {
     static constexpr int MB = WM / 32, NB = WN / 32;
     static constexpr int G = BK / 8;                           // 8-column groups per slab
     static constexpr int GQ = G / WGK;                         // of which one wave multiplies this many
-    static constexpr int SA = (AMODE == A_KM) ? BM : BK + 4;   // A in LDS: [BM][SA], or [BK][BM] when stored K x M
+    // Slabs with k contiguous ([row][k]: A stored M x K, B stored N x K): rows padded by 4 floats when a row
+    // holds at least 32 columns of k (the 16-byte fragment reads of 8 consecutive rows and the 16-byte writes of
+    // a row's 8 chunks then fall into distinct banks).  With 16 columns a padded row is 80 bytes and the writes
+    // of four rows (4 chunks each) overlap in some banks (measured: 16.3 instead of 13.6 cycles per 16-byte
+    // write instruction, a fifth of the kernel's LDS cycles spent in conflicts): those slabs are unpadded
+    // instead and the 16-byte chunk c of row r sits at chunk position c ^ ((r / 4) % 4).  The LDS serves 16
+    // lanes of a 16-byte access at a time from 64 banks: the writes of four rows are 256 contiguous bytes, and
+    // 16 consecutive rows reading the same c hit 16 distinct 16-byte bank groups (measured 6.7 cycles per
+    // read instruction, as for linear addresses; 16.3 without the XOR, 8.6 with (r / 2) % 4).
+    static constexpr bool SWZ = (BK == 16);
+    static constexpr int SA = (AMODE == A_KM) ? BM : (SWZ ? BK : BK + 4);   // A in LDS: [BM][SA], or [BK][BM] when stored K x M
     // B in LDS: [BN][SB] (NT) or [BK][SB] with SB >= BN; rows at least 64 floats apart keep the
     // fragment reads (one float from each of several rows) within reach of one address register
-    static constexpr int SB = (BMODE == B_NT) ? (BK + 4) : (BN < 64 ? 64 : BN);
+    static constexpr int SB = (BMODE == B_NT) ? (SWZ ? BK : BK + 4) : (BN < 64 ? 64 : BN);
     static constexpr int A_TILE = (AMODE == A_KM) ? BK * BM : BM * SA;
     static constexpr int B_TILE = (BMODE == B_NT) ? BN * SB : BK * SB;
     static constexpr int STAGE_FLOATS = A_TILE + B_TILE;
@@ -295,8 +305,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // slot r of a thread lies a fixed number of rows below its slot 0: the LDS addresses of all slots
     // are one register plus constants
     static_assert(NTHR % A_F4_ROW == 0 && NTHR % B_F4_ROW == 0, "slots of a thread share their column");
-    const int sa_base = (tid / A_F4_ROW) * SA + (tid % A_F4_ROW) * 4;
-    const int sb_base = (tid / B_F4_ROW) * SB + (tid % B_F4_ROW) * 4;
+    static_assert(!T::SWZ || ((NTHR / 4) % 16 == 0), "slots of a thread share their swizzle");
+    // (k-contiguous slabs of 16 columns: chunk position XORed with (row / 4) % 4, see Tile::SWZ)
+    const int sa_base = (tid / A_F4_ROW) * SA +
+                        ((T::SWZ && T::AMODE == A_MK) ? ((tid % A_F4_ROW) ^ (((tid / A_F4_ROW) >> 2) & 3)) : (tid % A_F4_ROW)) * 4;
+    const int sb_base = (tid / B_F4_ROW) * SB +
+                        ((T::SWZ && T::BMODE == B_NT) ? ((tid % B_F4_ROW) ^ (((tid / B_F4_ROW) >> 2) & 3)) : (tid % B_F4_ROW)) * 4;
 #pragma unroll
     for (int r = 0; r < A_ITERS; ++r) {
         const int f = tid + r * NTHR;
@@ -548,17 +562,22 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         bfrag_t b[NBV];
     };
     // (group g of this wave is group kq * GQ + g of the slab)
-    const int a_frag_off = (A_KMAJOR ? ((wm0 + l32) * SA + 4 * half) : (4 * half * SA + wm0 + MB * l32)) +
+    // k-contiguous slabs: the lane's row, and where the 16 bytes of group g lie in it (columns 8g + 4 * half ..;
+    // swizzled slabs: chunk 2g + half at position (2g + half) ^ ((row / 4) % 4), one offset per group)
+    const int a_frag_off = (A_KMAJOR ? ((wm0 + l32) * SA + (T::SWZ ? 0 : 4 * half)) : (4 * half * SA + wm0 + MB * l32)) +
                            8 * GQ * kq * (A_KMAJOR ? 1 : SA);
-    const int b_frag_off = ((T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + 4 * half)
+    const int b_frag_off = ((T::BMODE == B_NT) ? (T::A_TILE + (wn0 + l32) * SB + (T::SWZ ? 0 : 4 * half))
                                                : (T::A_TILE + 4 * half * SB + wn0 + NB * l32)) +
                            8 * GQ * kq * (T::BMODE == B_NT ? 1 : SB);
+    int k_off[G];                                     // offset of group g's 16 bytes within a k-contiguous row
+#pragma unroll
+    for (int g = 0; g < G; ++g) k_off[g] = T::SWZ ? 4 * ((2 * g + half) ^ ((l32 >> 2) & 3)) : 8 * g;
     auto read_frag = [&](Frag &fr, int stage, int g) {
         const float *base = lds + stage * T::STAGE_FLOATS;
         if constexpr (A_KMAJOR) {
 #pragma unroll
             for (int i = 0; i < MB; ++i)   // row of block i: wm0 + 32*i + l32
-                fr.a[i] = *reinterpret_cast<const v4f *>(base + a_frag_off + 32 * i * SA + 8 * g);
+                fr.a[i] = *reinterpret_cast<const v4f *>(base + a_frag_off + 32 * i * SA + k_off[g]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)    // row of block i: wm0 + MB*l32 + i
@@ -567,7 +586,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         if constexpr (T::BMODE == B_NT) {
 #pragma unroll
             for (int j = 0; j < NB; ++j)   // column of block j: wn0 + 32*j + l32
-                fr.b[j] = *reinterpret_cast<const v4f *>(base + b_frag_off + 32 * j * SB + 8 * g);
+                fr.b[j] = *reinterpret_cast<const v4f *>(base + b_frag_off + 32 * j * SB + k_off[g]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)    // column of block j: wn0 + NB*l32 + j

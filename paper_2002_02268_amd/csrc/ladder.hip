@@ -57,15 +57,15 @@ int gemm_f32_ladder(int level, int64_t M, int64_t N, int64_t K, const float *A, 
     a.A = A; a.B = packed ? Bp : B; a.C = C;
     a.M = (int)M; a.N = (int)N; a.K = (int)K;
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
-    const int tile = (level == 0) ? 16 : (level == 5 ? 128 : 32);
+    const int tile = (level == 0) ? 16 : (level == 5 ? 128 : 64);
     const dim3 grid(cdiv(N, tile), cdiv(M, tile));
     if (grid.y > 65535u * 16u) return GEMMF32_EINVAL;
     switch (level) {
     case 0: hipLaunchKernelGGL(level0_baseline, grid, dim3(256), 0, g_ladder_stream, a); break;
     case 1: hipLaunchKernelGGL(level1_blocking, grid, dim3(256), 0, g_ladder_stream, a); break;
-    case 2: hipLaunchKernelGGL(level2_vectorization, grid, dim3(64), 0, g_ladder_stream, a); break;
-    case 3: hipLaunchKernelGGL(level34_permuted<false>, grid, dim3(64), 0, g_ladder_stream, a); break;
-    case 4: hipLaunchKernelGGL(level34_permuted<true>, grid, dim3(64), 0, g_ladder_stream, a); break;
+    case 2: hipLaunchKernelGGL(level2_vectorization, grid, dim3(256), 0, g_ladder_stream, a); break;
+    case 3: hipLaunchKernelGGL(level34_permuted<false>, grid, dim3(256), 0, g_ladder_stream, a); break;
+    case 4: hipLaunchKernelGGL(level34_permuted<true>, grid, dim3(256), 0, g_ladder_stream, a); break;
     default: hipLaunchKernelGGL(level5_cache_blocks, grid, dim3(256), 0, g_ladder_stream, a); break;
     }
     return hipGetLastError() == hipSuccess ? GEMMF32_OK : GEMMF32_ELAUNCH;

@@ -4,8 +4,8 @@
 // permutation, array packing, cache blocks, parallel.  What each class becomes on this chip:
 //
 //   0 baseline          one thread per element of C, operands straight from global memory
-//   1 blocking          32x32 tile of C per workgroup (the paper's tile), K in slabs held in LDS
-//   2 vectorization     the 32x32 inner product runs on the matrix unit (fp32 MFMA), one wave per tile
+//   1 blocking          64x64 tile of C per workgroup of four waves, K in slabs of 32 held in LDS, scalar FMAs
+//   2 vectorization     the same workgroup; each wave's 32x32 block runs on the matrix unit (fp32 MFMA)
 //   3 loop permutation  k-major operand order in LDS: padded rows, a lane reads 16 bytes = 4 MFMA steps
 //   4 array packing     B comes from packed panels (packedB[N/P][K][P]); its rows are linear in memory
 //   5 cache blocks      accumulators blocked in registers (64x64 per wave, 128x128 per workgroup),
@@ -58,31 +58,39 @@ __global__ void __launch_bounds__(256) level0_baseline(const Args p)
     p.C[(int64_t)i * p.ldc + j] = acc;
 }
 
+// Levels 1 to 4 share one decomposition, so that each differs from the one before in a single respect:
+// a 64x64 tile of C per workgroup of 256 threads (four waves), K in slabs of 32 held in LDS, one barrier
+// pair per slab, nothing in flight while a slab is multiplied.
+
 // ---- 1: blocking --------------------------------------------------------------------------------
-// 32x32 tile, K slabs of 32 in LDS, 256 threads, each thread a 2x2 patch; scalar FMAs.
+// Each thread a 4x4 patch of the tile; scalar FMAs in the vector unit.
 __global__ void __launch_bounds__(256) level1_blocking(const Args p)
 {
-    __shared__ float As[32][33], Bs[32][33];
+    __shared__ float As[64][33], Bs[32][65];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
-    float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4];
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
     for (int k0 = 0; k0 < p.K; k0 += 32) {
-        for (int e = threadIdx.x; e < 1024; e += 256) {
-            const int r = e >> 5, c = e & 31;
-            As[r][c] = load_a(p, m0 + r, k0 + c);
-            Bs[r][c] = load_b<false>(p, k0 + r, n0 + c);
+        for (int e = threadIdx.x; e < 2048; e += 256) {
+            As[e >> 5][e & 31] = load_a(p, m0 + (e >> 5), k0 + (e & 31));
+            Bs[e >> 6][e & 63] = load_b<false>(p, k0 + (e >> 6), n0 + (e & 63));
         }
         __syncthreads();
         for (int k = 0; k < 32; ++k) {
-            const float a0 = As[ty][k], a1 = As[ty + 16][k];
-            const float b0 = Bs[k][tx], b1 = Bs[k][tx + 16];
-            acc[0][0] += a0 * b0; acc[0][1] += a0 * b1;
-            acc[1][0] += a1 * b0; acc[1][1] += a1 * b1;
+            float a[4], b[4];
+            for (int i = 0; i < 4; ++i) {
+                a[i] = As[ty + 16 * i][k];
+                b[i] = Bs[k][tx + 16 * i];
+            }
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
         }
         __syncthreads();
     }
-    for (int a = 0; a < 2; ++a)
-        for (int b = 0; b < 2; ++b) {
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b) {
             const int i = m0 + ty + 16 * a, j = n0 + tx + 16 * b;
             if (i < p.M && j < p.N) p.C[(int64_t)i * p.ldc + j] = acc[a][b];
         }
@@ -98,28 +106,28 @@ __device__ __forceinline__ void store_block(const Args &p, const v16f &acc, int 
 }
 
 // ---- 2: vectorization -----------------------------------------------------------------------------
-// One wave per 32x32 tile; operands in LDS in their memory order (A[i][k], B[k][j]); each MFMA step
-// reads one float of A and one of B per lane.  A is read down a column of the slab: every lane
-// hits the same bank.
-__global__ void __launch_bounds__(64) level2_vectorization(const Args p)
+// The same tile and slabs; each wave's 32x32 block runs on the matrix unit (fp32 MFMA) instead of 1024
+// scalar FMAs per k.  Operands lie in LDS in their memory order (A[i][k], B[k][j]); each MFMA step reads
+// one float of A and one of B per lane.  A is read down a column of the slab: every lane hits the same bank.
+__global__ void __launch_bounds__(256) level2_vectorization(const Args p)
 {
-    __shared__ float As[32][32], Bs[32][32];
-    const int lane = threadIdx.x, l32 = lane & 31, half = lane >> 5;
-    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    __shared__ float As[64][32], Bs[32][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
     v16f acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     for (int k0 = 0; k0 < p.K; k0 += 32) {
-        for (int e = lane; e < 1024; e += 64) {
-            const int r = e >> 5, c = e & 31;
-            As[r][c] = load_a(p, m0 + r, k0 + c);
-            Bs[r][c] = load_b<false>(p, k0 + r, n0 + c);
+        for (int e = threadIdx.x; e < 2048; e += 256) {
+            As[e >> 5][e & 31] = load_a(p, m0 + (e >> 5), k0 + (e & 31));
+            Bs[e >> 6][e & 63] = load_b<false>(p, k0 + (e >> 6), n0 + (e & 63));
         }
         __syncthreads();
         for (int s = 0; s < 16; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[l32][2 * s + half], Bs[2 * s + half][l32], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[wm0 + l32][2 * s + half], Bs[2 * s + half][wn0 + l32], acc, 0, 0, 0);
         __syncthreads();
     }
-    store_block(p, acc, m0, n0, l32, half);
+    store_block(p, acc, m0 + wm0, n0 + wn0, l32, half);
 }
 
 // ---- 3 and 4: loop permutation, array packing -------------------------------------------------------
@@ -127,29 +135,29 @@ __global__ void __launch_bounds__(64) level2_vectorization(const Args p)
 // that a lane's four A operands are 16 contiguous bytes (step e pairs columns e and 4+e).
 // PACKED: B is read from the packed panels.
 template <bool PACKED>
-__global__ void __launch_bounds__(64) level34_permuted(const Args p)
+__global__ void __launch_bounds__(256) level34_permuted(const Args p)
 {
-    __shared__ __align__(16) float As[32][36];
-    __shared__ float Bs[32][32];
-    const int lane = threadIdx.x, l32 = lane & 31, half = lane >> 5;
-    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    __shared__ __align__(16) float As[64][36];
+    __shared__ float Bs[32][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
     v16f acc;
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     for (int k0 = 0; k0 < p.K; k0 += 32) {
-        for (int e = lane; e < 1024; e += 64) {
-            const int r = e >> 5, c = e & 31;
-            As[r][c] = load_a(p, m0 + r, k0 + c);
-            Bs[r][c] = load_b<PACKED>(p, k0 + r, n0 + c);
+        for (int e = threadIdx.x; e < 2048; e += 256) {
+            As[e >> 5][e & 31] = load_a(p, m0 + (e >> 5), k0 + (e & 31));
+            Bs[e >> 6][e & 63] = load_b<PACKED>(p, k0 + (e >> 6), n0 + (e & 63));
         }
         __syncthreads();
         for (int g = 0; g < 4; ++g) {
-            const v4f a = *reinterpret_cast<const v4f *>(&As[l32][8 * g + 4 * half]);
+            const v4f a = *reinterpret_cast<const v4f *>(&As[wm0 + l32][8 * g + 4 * half]);
             for (int e = 0; e < 4; ++e)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], Bs[8 * g + 4 * half + e][l32], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], Bs[8 * g + 4 * half + e][wn0 + l32], acc, 0, 0, 0);
         }
         __syncthreads();
     }
-    store_block(p, acc, m0, n0, l32, half);
+    store_block(p, acc, m0 + wm0, n0 + wn0, l32, half);
 }
 
 // ---- 5: cache blocks ----------------------------------------------------------------------------
