@@ -101,6 +101,19 @@ int elevate_schedule_filter(const char *strategy, int *form, char *program, size
 int elevate_default_strategy(int64_t M, int64_t N, int64_t K, char *strategy, size_t cap);
 
 /*
+ * The library's own dispatch goes through this layer (Section 3.4, left choice; Section 6.5, one schedule per
+ * version): for every new shape of a single product it applies
+ *     (lChoice (seq admissible_t cheapest_t schedule_t) ...)        one candidate per tile shape t
+ * to the plain nest, where admissible_t (may this tile compete for the nest's extents: the dispatch's measured
+ * rules) and cheapest_t (does the cost model rank it first) are guards that leave the nest as it is or fail,
+ * and schedule_t is the strategy elevate_default_strategy prints; the kernel configuration lowered from the
+ * rewritten nest is what the launch is planned from.  applied: how often that happened since the library was
+ * loaded; failed: how often no candidate applied or the nest could not be lowered (the cost model's answer
+ * was then used as it stood).  Either pointer may be NULL.
+ */
+void elevate_dispatch_stats(int64_t *applied, int64_t *failed);
+
+/*
  * C = A * op(B) (as gemm_f32: DEVICE pointers, the library's stream, same argument checks and
  * status codes) run with the kernel shape and K split of `s` instead of the library's own choice.
  * GEMMF32_EINVAL if s names a shape no kernel was built for or a split that does not fit K.

@@ -54,6 +54,7 @@ SYMBOLS = {
     "elevate_schedule_filter": (ctypes.c_int, [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int), ctypes.c_char_p,
                                                ctypes.c_size_t]),
     "elevate_default_strategy": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_char_p, ctypes.c_size_t]),
+    "elevate_dispatch_stats": (None, [ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
     "gemm_f32_scheduled": (ctypes.c_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, ctypes.c_int]),
 }
 
@@ -394,6 +395,13 @@ def elevate_default_strategy(M: int, N: int, K: int) -> str:
     if rc != 0:
         raise ValueError(f"elevate_default_strategy: code {rc}")
     return buf.value.decode()
+
+
+def elevate_dispatch_stats():
+    """(applied, failed): how often the dispatch planned a launch from a lowered nest, and how often that failed."""
+    a, f = ctypes.c_int64(0), ctypes.c_int64(0)
+    lib().elevate_dispatch_stats(ctypes.byref(a), ctypes.byref(f))
+    return int(a.value), int(f.value)
 
 
 def gemm_f32_scheduled(sched: Schedule, A, B, C, transB: bool = False) -> None:

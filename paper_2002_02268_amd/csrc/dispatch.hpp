@@ -6,6 +6,21 @@
 namespace gemmf32_host {
 
 struct TileChoice { int bm, bn, bk, waves_m, waves_n, waves_k, split; };   // waves_m x waves_n x waves_k waves per workgroup
+struct ShapeQuery { int64_t batch, M, N, K; int bmode, amode; };           // bmode: 0 K x N, 1 N x K, 2 packed; amode: 0 M x K, 1 K x M
+
+// the tile shapes kernels were built for
+int tile_count();
+TileChoice tile_shape(int tile);
+// may this tile compete for the shape at all (the dispatch's measured rules)?
+bool admissible_tile(int tile, const ShapeQuery &q);
+// Implemented by the strategy layer, called by the dispatch once per new shape: rewrites the product's loop
+// nest with a left choice over the tiles, each guarded by "may compete" and "is the one the cost model ranks
+// first (`cheapest`)", and lowers the rewritten nest.  false: no guarded schedule applied or the nest could
+// not be lowered.
+bool dispatch_by_strategy(const ShapeQuery &q, const TileChoice &cheapest, TileChoice &lowered);
+// how often the dispatch built its plan from a lowered nest, and how often that failed (the cost model's
+// answer was used as it stood)
+void strategy_dispatch_stats(long long *applied, long long *failed);
 
 // tile shape and K split the cost model picks for one product
 TileChoice choose(int64_t M, int64_t N, int64_t K);

@@ -56,18 +56,27 @@ template <class P> struct RewriteResult {
     static RewriteResult failure(std::string who) { return RewriteResult{false, P(), std::move(who)}; }
 };
 
+// (name and function live behind a shared pointer: combinators capture their arguments by value, and a
+// chain of n of them would otherwise copy closures of closures n^2 / 2 times)
 template <class P> class Strategy {
 public:
     typedef std::function<RewriteResult<P>(const P &)> Fn;
     Strategy() {}
-    Strategy(std::string name, Fn fn) : name_(std::move(name)), fn_(std::move(fn)) {}
-    RewriteResult<P> operator()(const P &p) const { return fn_(p); }
-    const std::string &name() const { return name_; }
-    explicit operator bool() const { return (bool)fn_; }
+    Strategy(std::string name, Fn fn) : impl_(std::make_shared<const Impl>(Impl{std::move(name), std::move(fn)})) {}
+    RewriteResult<P> operator()(const P &p) const { return impl_->fn(p); }
+    const std::string &name() const
+    {
+        static const std::string none;
+        return impl_ ? impl_->name : none;
+    }
+    explicit operator bool() const { return impl_ && (bool)impl_->fn; }
 
 private:
-    std::string name_;
-    Fn fn_;
+    struct Impl {
+        std::string name;
+        Fn fn;
+    };
+    std::shared_ptr<const Impl> impl_;
 };
 
 // Every successful application of a rewrite rule is recorded here (rule name, the sub-term it

@@ -113,9 +113,82 @@ std::string default_strategy(long long M, long long N, long long K, const gemmf3
     return s + ")";
 }
 
+// reads M, N, K off a plain product nest (loop M m seq (loop N n seq (loop K k seq mac)))
+bool plain_extents(const TermP &p, long long &M, long long &N, long long &K)
+{
+    const TermP *t = &p;
+    long long *out[3] = {&M, &N, &K};
+    const char *axes[3] = {"M", "N", "K"};
+    for (int i = 0; i < 3; ++i) {
+        if (!is_node(*t, "loop", 4) || !is_atom((*t)->args[0]) || (*t)->args[0]->head != axes[i] || !is_atom((*t)->args[1])) return false;
+        *out[i] = std::atoll((*t)->args[1]->head.c_str());
+        t = &(*t)->args[3];
+    }
+    return true;
+}
+
 }  // namespace
 
+namespace gemmf32_host {
+
+// The dispatch as a strategy: (lChoice c0 c1 ...), one candidate per tile shape, each
+//     c = (seq admissible(tile) cheapest(tile) schedule(tile, split))
+// where the first two are guards (they leave the nest as it is, or fail) and the third is the schedule of
+// default_strategy for that tile.  Applied to the plain nest of the product; the result is lowered.
+bool dispatch_by_strategy(const ShapeQuery &q, const TileChoice &cheapest, TileChoice &lowered)
+{
+    Strategy<TermP> dispatch = fail<TermP>();
+    for (int tile = tile_count() - 1; tile >= 0; --tile) {
+        const TileChoice shape = tile_shape(tile);
+        const Strategy<TermP> may_compete("admissible", [tile, q](const TermP &p) {
+            long long M, N, K;
+            if (!plain_extents(p, M, N, K)) return RewriteResult<TermP>::failure("admissible");
+            ShapeQuery here = q;
+            here.M = M; here.N = N; here.K = K;
+            return admissible_tile(tile, here) ? RewriteResult<TermP>::success(p) : RewriteResult<TermP>::failure("admissible");
+        });
+        const Strategy<TermP> is_cheapest("cheapest", [shape, cheapest](const TermP &p) {
+            const bool same = shape.bm == cheapest.bm && shape.bn == cheapest.bn && shape.bk == cheapest.bk &&
+                              shape.waves_m == cheapest.waves_m && shape.waves_n == cheapest.waves_n &&
+                              shape.waves_k == cheapest.waves_k;
+            return same ? RewriteResult<TermP>::success(p) : RewriteResult<TermP>::failure("cheapest");
+        });
+        const Strategy<TermP> schedule("schedule", [shape, cheapest](const TermP &p) {
+            long long M, N, K;
+            if (!plain_extents(p, M, N, K)) return RewriteResult<TermP>::failure("schedule");
+            TileChoice c = shape;
+            c.split = cheapest.split;
+            std::string err;
+            const TermP expr = parse(default_strategy(M, N, K, c), err);
+            if (!expr) return RewriteResult<TermP>::failure("schedule");
+            const Strategy<TermP> s = compile_strategy(expr, err);
+            if (!s) return RewriteResult<TermP>::failure("schedule");
+            return s(p);
+        });
+        dispatch = lChoice(seq(may_compete, seq(is_cheapest, schedule)), dispatch);
+    }
+    const RewriteResult<TermP> r = dispatch(product_nest(q.M, q.N, q.K));
+    if (!r.ok) return false;
+    LoweredSchedule ls;
+    std::string err;
+    if (!lower_nest(r.p, q.M, q.N, q.K, ls, err)) return false;
+    const long long big = 2147483647LL;
+    if (ls.bm > big || ls.bn > big || ls.bk > big || ls.waves_m > big || ls.waves_n > big || ls.waves_k > big || ls.split_k > big) return false;
+    lowered = TileChoice{(int)ls.bm, (int)ls.bn, (int)ls.bk, (int)ls.waves_m, (int)ls.waves_n, (int)ls.waves_k, (int)ls.split_k};
+    return true;
+}
+
+}  // namespace gemmf32_host
+
 extern "C" {
+
+void elevate_dispatch_stats(int64_t *applied, int64_t *failed)
+{
+    long long a = 0, f = 0;
+    gemmf32_host::strategy_dispatch_stats(&a, &f);
+    if (applied) *applied = a;
+    if (failed) *failed = f;
+}
 
 int elevate_rewrite(const char *strategy, const char *program, char *out, size_t out_cap, int *steps, char *trace_buf,
                     size_t trace_cap)

@@ -14,6 +14,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 using namespace gemmf32;
@@ -184,6 +185,7 @@ TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t t
     TailSplit t = {tiles % 256, 1, 0, 0.0, false};
     if (batch != 1 || tiles <= 256 || t.tail == 0 || t.tail > 128 || hooks.no_tail_split) return t;
     const int64_t units = cdiv(K, bk);
+    if (units < 2) return t;                             // nothing to cut (K = 0 included)
     int64_t S = 256 / t.tail;
     if (S > 8) S = 8;     // shorter pieces than an eighth of K cost more in the second pass than they save
     if (S > units) S = units;
@@ -237,6 +239,23 @@ struct ChoiceKey {
     }
 };
 struct ChoiceSlot { ChoiceKey key; Choice choice; bool valid; };
+std::atomic<long long> g_strategy_applied{0}, g_strategy_failed{0};
+// Behind the per-thread slots, one table for the process: realising a choice through the strategy layer
+// costs about 0.1 ms, which a shape should pay once, not once per thread or per eviction.
+struct ChoiceKeyHash {
+    size_t operator()(const ChoiceKey &k) const
+    {
+        uint64_t h = (uint64_t)k.M * 0x9E3779B97F4A7C15ull;
+        h = (h ^ (uint64_t)k.N) * 0xC2B2AE3D27D4EB4Full;
+        h = (h ^ (uint64_t)k.K) * 0x165667B19E3779F9ull;
+        h = (h ^ (uint64_t)k.batch) * 0x27D4EB2F165667C5ull;
+        h ^= (uint64_t)(k.bmode | (k.amode << 2) | (k.flags << 4)) ^ ((uint64_t)(uint32_t)k.forced_tile << 16) ^ ((uint64_t)(uint32_t)k.forced_split << 32);
+        return (size_t)(h ^ (h >> 29));
+    }
+};
+std::mutex g_choice_mutex;
+std::unordered_map<ChoiceKey, Choice, ChoiceKeyHash> g_choice_table;
+constexpr size_t kChoiceTableMax = 1u << 16;
 thread_local ChoiceSlot g_choice_cache[64];
 
 Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int64_t K, int bmode = B_NN, int amode = A_MK)
@@ -249,10 +268,86 @@ Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int6
                        ((uint64_t)K * 0x165667B19E3779F9ull) ^ ((uint64_t)batch * 0x27D4EB2F165667C5ull);
     ChoiceSlot &slot = g_choice_cache[h >> 58];
     if (slot.valid && slot.key == key) return slot.choice;
+    {
+        std::lock_guard<std::mutex> lock(g_choice_mutex);
+        const auto it = g_choice_table.find(key);
+        if (it != g_choice_table.end()) {
+            slot.key = key;
+            slot.choice = it->second;
+            slot.valid = true;
+            return slot.choice;
+        }
+    }
+    slot.valid = false;
     slot.key = key;
     slot.choice = evaluate_candidates(hooks, forced_tile, forced_split, batch, M, N, K, bmode, amode);
+    // The choice is then realised by the strategy layer: a left choice over the tiles, each guarded by "may
+    // compete" and "is the cheapest", whose schedule rewrites the product's loop nest; the configuration
+    // lowered from the rewritten nest is what the plan is built from.  (Forced tiles and splits are explicit
+    // schedules of the caller's; batched products are one nest per batch and keep the model's answer.)
+    if (forced_tile < 0 && forced_split < 1 && batch == 1 && M >= 1 && N >= 1 && K >= 1) {
+        const TileShape &sh = kShapes[slot.choice.tile];
+        const ShapeQuery q = {batch, M, N, K, bmode, amode};
+        const TileChoice want = {sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, sh.waves_k, slot.choice.split};
+        TileChoice got;
+        int tile = -1;
+        if (dispatch_by_strategy(q, want, got))
+            for (int t = 0; t < NUM_TILES; ++t)
+                if (kShapes[t].bm == got.bm && kShapes[t].bn == got.bn && kShapes[t].bk == got.bk &&
+                    kShapes[t].waves_m == got.waves_m && kShapes[t].waves_n == got.waves_n && kShapes[t].waves_k == got.waves_k)
+                    tile = t;
+        // (the lowered nest counts the K ranges that are not empty; the plan derives the same count from the split)
+        const int64_t k_range = cdiv(cdiv(K, slot.choice.split), sh.bk) * sh.bk;
+        if (tile >= 0 && got.split == (slot.choice.split > 1 ? (int)cdiv(K, k_range) : 1)) {
+            slot.choice = {tile, slot.choice.split};
+            g_strategy_applied.fetch_add(1, std::memory_order_relaxed);
+        } else {
+            g_strategy_failed.fetch_add(1, std::memory_order_relaxed);     // the model's answer stands
+        }
+    }
     slot.valid = true;
+    {
+        std::lock_guard<std::mutex> lock(g_choice_mutex);
+        if (g_choice_table.size() >= kChoiceTableMax) g_choice_table.clear();
+        g_choice_table.emplace(key, slot.choice);
+    }
     return slot.choice;
+}
+
+// Which tiles may compete for a shape at all (measured rules; the cost model ranks the rest).
+bool admissible(const Hooks &hooks, int tile, int64_t batch, int64_t M, int64_t N, int64_t K, int bmode, int amode)
+{
+    // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
+    // are for outputs that are no wider, where the others would compute padding
+    // (measured: beyond one round of workgroups they still pay where their tile count fits the chip better,
+    // 1100^3 25 against 30 us; they stay out of outputs of more than 2048 tiles, where the traffic counts)
+    if (((tile == T128x32 && N > 32) || (tile == T32x128 && M > 32)) &&
+        cdiv(M, kShapes[tile].bm) * cdiv(N, kShapes[tile].bn) > 2048) return false;
+    // One 32 x 32 block per workgroup with the slab shared between its waves: for outputs at most 32
+    // wide whose operands need no element-wise masking (a B stored K x N with fewer than 32 columns
+    // does, and so does an A stored K x M with fewer than 32 rows).  Where it
+    // applies it replaces the other 32-wide tiles (fewer or no K ranges over workgroups, so no or
+    // a smaller second pass): measured 5-20 % faster on such shapes.
+    const bool narrow_n = N <= 32 && amode == A_MK && (bmode != B_NN || N == 32) && M >= 1024;
+    // (a B stored K x N is read in panels of 32 columns, 128 bytes per row: fine from the memory-side
+    // cache, slower than the 128-column tile once B is larger than that cache and streams from HBM:
+    // 32 x 32000 x 4096: 125 us against 96)
+    const bool b_streams_narrow = bmode == B_NN && M <= 32 && 4.0 * (double)K * (double)N > 268435456.0;
+    const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024 && !b_streams_narrow;
+    const bool kshare = batch == 1 && (narrow_n || narrow_m);
+    if (tile != TQ32 && kshare) return false;
+    // It also competes on any product at least 32 x 32: a few hundred blocks occupy the chip
+    // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
+    // 11.7 instead of 19.4 us).
+    // (batched products too: they cannot split K; and batches of products no larger than one block,
+    // where a 64 x 64 tile would compute four times the padding: 4096 x 16x16x64 29 -> 20 us)
+    const bool kshare_general = ((M >= 32 && N >= 32) || (batch > 1 && M <= 32 && N <= 32)) && !hooks.no_kshare;
+    if (tile == TQ32 && ((!kshare && !kshare_general) || b_streams_narrow)) return false;
+    // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
+    // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
+    // 21 -> 18.3 us).
+    if ((tile == TQ64x32 || tile == TQ32x64) && (kshare || !kshare_general || b_streams_narrow)) return false;
+    return true;
 }
 
 Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split, int64_t batch, int64_t M, int64_t N,
@@ -261,37 +356,7 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
     Choice best = {TB64, 1};
     double best_cost = -1, best_area = 0;
     for (const auto &c : kCandidates) {
-        if (forced_tile >= 0 && c.id != forced_tile) continue;
-        // the 32-wide tiles move a quarter more operand bytes per flop than the 64-wide ones: they
-        // are for outputs that are no wider, where the others would compute padding
-        // (measured: beyond one round of workgroups they still pay where their tile count fits the chip better,
-        // 1100^3 25 against 30 us; they stay out of outputs of more than 2048 tiles, where the traffic counts)
-        if (forced_tile < 0 && ((c.id == T128x32 && N > 32) || (c.id == T32x128 && M > 32)) &&
-            cdiv(M, kShapes[c.id].bm) * cdiv(N, kShapes[c.id].bn) > 2048) continue;
-        // One 32 x 32 block per workgroup with the slab shared between its waves: for outputs at most 32
-        // wide whose operands need no element-wise masking (a B stored K x N with fewer than 32 columns
-        // does, and so does an A stored K x M with fewer than 32 rows).  Where it
-        // applies it replaces the other 32-wide tiles (fewer or no K ranges over workgroups, so no or
-        // a smaller second pass): measured 5-20 % faster on such shapes.
-        const bool narrow_n = N <= 32 && amode == A_MK && (bmode != B_NN || N == 32) && M >= 1024;
-        // (a B stored K x N is read in panels of 32 columns, 128 bytes per row: fine from the memory-side
-        // cache, slower than the 128-column tile once B is larger than that cache and streams from HBM:
-        // 32 x 32000 x 4096: 125 us against 96)
-        const bool b_streams_narrow = bmode == B_NN && M <= 32 && 4.0 * (double)K * (double)N > 268435456.0;
-        const bool narrow_m = M <= 32 && (amode == A_MK || M == 32) && N >= 1024 && !b_streams_narrow;
-        const bool kshare = batch == 1 && (narrow_n || narrow_m);
-        if (forced_tile < 0 && c.id != TQ32 && kshare) continue;
-        // It also competes on any product at least 32 x 32: a few hundred blocks occupy the chip
-        // where the same output in 64-wide tiles needs K ranges and a second pass (640 x 640 x 1024:
-        // 11.7 instead of 19.4 us).
-        // (batched products too: they cannot split K; and batches of products no larger than one block,
-        // where a 64 x 64 tile would compute four times the padding: 4096 x 16x16x64 29 -> 20 us)
-        const bool kshare_general = ((M >= 32 && N >= 32) || (batch > 1 && M <= 32 && N <= 32)) && !hooks.no_kshare;
-        if (forced_tile < 0 && c.id == TQ32 && ((!kshare && !kshare_general) || b_streams_narrow)) continue;
-        // The same with two blocks per workgroup (a quarter fewer operand bytes per flop, half the
-        // workgroups): where the output has enough of them (640 x 640 x 2048 with B stored N x K:
-        // 21 -> 18.3 us).
-        if (forced_tile < 0 && (c.id == TQ64x32 || c.id == TQ32x64) && (kshare || !kshare_general || b_streams_narrow)) continue;
+        if (forced_tile >= 0 ? c.id != forced_tile : !admissible(hooks, c.id, batch, M, N, K, bmode, amode)) continue;
         const TileShape &sh = kShapes[c.id];
         const int strip = strip_cols(hooks, c.id, batch, N, bmode, amode);       // only without K ranges (and taken to fit: see strip_fits)
         const int64_t tiles_whole = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
@@ -708,6 +773,25 @@ TileChoice choose(int64_t M, int64_t N, int64_t K)
         split = (int)cdiv(K, k_range);
     }
     return TileChoice{sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, sh.waves_k, split};
+}
+
+int tile_count() { return NUM_TILES; }
+
+TileChoice tile_shape(int tile)
+{
+    const TileShape &sh = kShapes[tile];
+    return TileChoice{sh.bm, sh.bn, sh.bk, sh.waves_m, sh.waves_n, sh.waves_k, 1};
+}
+
+bool admissible_tile(int tile, const ShapeQuery &q)
+{
+    return admissible(read_hooks(), tile, q.batch, q.M, q.N, q.K, q.bmode, q.amode);
+}
+
+void strategy_dispatch_stats(long long *applied, long long *failed)
+{
+    if (applied) *applied = g_strategy_applied.load();
+    if (failed) *failed = g_strategy_failed.load();
 }
 
 bool has_kernel(int bm, int bn, int bk, int waves_m, int waves_n, int waves_k)

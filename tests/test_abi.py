@@ -215,3 +215,11 @@ def test_test_hooks_validate_and_reset():
         os.environ.pop("GEMMF32_FORCE_TILE")
     assert lib.gemm_f32_noalloc_scratch_bytes() == 32 << 20
     assert lib.gemm_f32_strerror(-6).decode().startswith("the product needs more scratch")
+
+
+def test_planning_an_empty_sum_over_many_tiles():
+    """K = 0 with more tiles than one round and a remainder: the plan of the split last round has nothing to
+    cut (this divided by zero once)."""
+    for M, N in [(5000, 4000), (1000, 1030), (4100, 4100)]:
+        name = binding.variant_name(M, N, 0)
+        assert name not in ("invalid", "empty") and "/tail" not in name and "/quad" not in name, name

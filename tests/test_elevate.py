@@ -417,3 +417,44 @@ def test_blocking_and_loop_permutation_schedules_give_the_loop_orders_of_section
     assert rw(f"(seq {blocking} (bodyN 3 interchange))", nest)[1] == out
     # parallelising the outermost loop (the tutorial's last version) is topDown(mark grid)
     assert rw(f"(seq {permuted} (topDown (mark grid)))", nest)[1].startswith("(loop M 32 grid (loop N 32 seq")
+
+
+def test_dispatch_plans_from_the_lowered_nest_on_the_survey_shapes():
+    """The production dispatch realises every choice through the strategy layer: for the 92 shapes of the
+    benchmark's survey (52 fixed, 40 seeded random, either layout of B) the plan is built from the configuration
+    lowered from the nest that (lChoice (seq admissible cheapest schedule) ...) rewrote, never from the cost
+    model's answer as it stood; and where the layer can be asked from outside (B stored K x N), the strategy
+    text it prints lowers to the tile and split of the plan."""
+    import importlib.util
+    import math
+    import os
+    import random
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module_for_elevate", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    rng = random.Random(3)
+    shapes = list(bench.SURVEY_SHAPES)
+    while len(shapes) < len(bench.SURVEY_SHAPES) + 40:
+        M, N, K = (int(round(math.exp(rng.uniform(math.log(a), math.log(b))))) for a, b in ((32, 4096), (32, 4096), (64, 8192)))
+        if 2.0 * M * N * K <= 4e10:
+            shapes.append((M, N, K, rng.random() < 0.5))
+    assert len(shapes) == 92
+    b.set_test_hooks()
+    applied0, failed0 = b.elevate_dispatch_stats()
+    # shapes nobody has asked about yet in this process: shifted by a prime so that the process-wide table misses
+    fresh = [(M + 7, N, K, tB) for (M, N, K, tB) in shapes]
+    names = [b.variant_name(M, N, K, transB=tB) for (M, N, K, tB) in shapes + fresh]
+    applied1, failed1 = b.elevate_dispatch_stats()
+    assert failed1 == failed0 == 0
+    assert applied1 - applied0 >= len(set(fresh))
+    for (M, N, K, tB), name in zip(shapes + fresh, names):
+        if tB or name.startswith("thin"):
+            continue
+        rc, sched, _ = b.elevate_schedule_gemm(M, N, K, b.elevate_default_strategy(M, N, K))
+        assert rc == 0, (M, N, K)
+        parts = name.split("/")
+        tile = f"t{sched.bm}x{sched.bn}x{sched.bk}" + (f"k{sched.waves_k}" if sched.waves_k > 1 else "")
+        assert parts[0] == tile, (M, N, K, name, sched.as_dict())
+        split = [int(x[len("splitk"):]) for x in parts if x.startswith("splitk")]
+        assert sched.split_k == (split[0] if split else 1), (M, N, K, name, sched.as_dict())
