@@ -388,6 +388,100 @@ def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.
             "mean_ratio": round(sum(ratios) / len(ratios), 3), "worst_ratio": max(ratios), "failures": failures}
 
 
+TIMELINE_CASES = [
+    dict(label="square1024", M=1024, N=1024, K=1024),
+    dict(label="square1024, 64x32x64 tile whose four waves share the slabs", M=1024, N=1024, K=1024, hooks={"force_tile": 11}),
+    dict(label="ragged", M=1000, N=1030, K=999),
+    dict(label="ragged, strip off (last columns as 32x32 blocks of an edge tile column)", M=1000, N=1030, K=999, hooks={"no_strip": True}),
+    dict(label="1100^3", M=1100, N=1100, K=1100),
+    dict(label="transb2048", M=2048, N=2048, K=2048, transB=True),
+    dict(label="square4096", M=4096, N=4096, K=4096),
+]
+TIMELINE_SLOTS = ["start", "first slab in LDS", "last whole slab multiplied", "epilogue begins", "sums of the slab-sharing waves in LDS",
+                  "stores issued"]
+
+
+def timeline(torch, binding):
+    """Per-phase breakdown of product launches from the measurement build (libgemmf32_timeline.so: the product's
+    sources with -DGEMMF32_TIMELINE, thread 0 of every workgroup writes the constant 100 MHz clock at six points).
+    Per case: the time of a launch from events with the stamps off and on, then from the last of 500 stamped
+    launches the phases of the workgroups (mean, median, max in us; tiles and the workgroups of blocks or strips
+    separately), the span from the first workgroup's start to the last one's last store, the rest of the launch
+    (event time minus span: completion of the stores, end of kernel, start of the next), and how many workgroups
+    shared a compute unit."""
+    import collections
+    import ctypes
+    import numpy as np
+    lib = binding.lib()
+    lib.gemm_f32_timeline_set.argtypes = [ctypes.c_void_p]
+    lib.gemm_f32_timeline_set.restype = ctypes.c_int
+    nwg = 4096
+    out = {"timeline": []}
+    for case in TIMELINE_CASES:
+        M, N, K, tB = case["M"], case["N"], case["K"], case.get("transB", False)
+        binding.set_test_hooks(**case.get("hooks", {})) if case.get("hooks") else binding.set_test_hooks()
+        A = torch.rand(M, K, device="cuda") * 2 - 1
+        B = (torch.rand(N, K, device="cuda") if tB else torch.rand(K, N, device="cuda")) * 2 - 1
+        C = torch.empty(M, N, device="cuda")
+        fn = lambda: binding.gemm_f32(A, B, C, transB=tB)
+
+        def event_us(reps=500):
+            for _ in range(300):
+                fn()
+            torch.cuda.synchronize()
+            best = 1e9
+            for _ in range(3):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                best = min(best, a.elapsed_time(b) / reps * 1e3)
+            return best
+
+        lib.gemm_f32_timeline_set(None)
+        plain = event_us()
+        st = torch.zeros(nwg * 8, dtype=torch.int64, device="cuda")
+        lib.gemm_f32_timeline_set(st.data_ptr())
+        stamped = event_us()
+        raw = st.cpu().numpy().reshape(nwg, 8)
+        lib.gemm_f32_timeline_set(None)
+        h = raw[:, :6].astype(np.float64) * 0.01                    # us
+        used = raw[:, 0] > 0
+        t0 = h[used, 0].min()
+        done = used & (raw[:, 5] > 0)                                # (blocks of an edge tile outside the matrix return early)
+        rel = h - t0
+        res = {"label": case["label"], "M": M, "N": N, "K": K, "transB": tB,
+               "variant": binding.variant_name(M, N, K, transB=tB), "event_us": round(plain, 2),
+               "event_us_with_stamps": round(stamped, 2), "workgroups": int(used.sum()),
+               "span_us": round(float(rel[done, 5].max()), 2)}
+        res["rest_of_launch_us"] = round(stamped - res["span_us"], 2)
+        kinds = {"tiles": done & (raw[:, 1] > 0) & (raw[:, 4] == 0), "slab-sharing workgroups": done & (raw[:, 4] > 0),
+                 "strip workgroups": done & (raw[:, 1] == 0)}
+        res["phases_us_mean_median_max"] = {}
+        for kind, mask in kinds.items():
+            if not mask.any():
+                continue
+            cols = [c for c in range(6) if (raw[mask, c] > 0).all()]
+            ph = {"workgroups": int(mask.sum())}
+            for a, b in zip(cols[:-1], cols[1:]):
+                d = rel[mask, b] - rel[mask, a]
+                ph[f"{TIMELINE_SLOTS[a]} -> {TIMELINE_SLOTS[b]}"] = [round(float(d.mean()), 2), round(float(np.median(d)), 2), round(float(d.max()), 2)]
+            ph["end"] = [round(float(rel[mask, 5].mean()), 2), round(float(np.median(rel[mask, 5])), 2), round(float(rel[mask, 5].max()), 2)]
+            res["phases_us_mean_median_max"][kind] = ph
+        ids = raw[:, 6][done]
+        hw, xcc = ids & 0xFFFFFFFF, (ids >> 32) & 0xF
+        key = xcc * 100000 + ((hw >> 13) & 7) * 1000 + ((hw >> 12) & 1) * 100 + ((hw >> 8) & 0xF)
+        per_cu = collections.Counter(int(k) for k in key)
+        res["compute_units_used"] = len(per_cu)
+        res["workgroups_per_compute_unit"] = dict(sorted(collections.Counter(per_cu.values()).items()))
+        out["timeline"].append(res)
+        del A, B, C, st
+    binding.set_test_hooks()
+    return out
+
+
 def protocol(torch, binding, synth):
     """Every workload timed the long way: 10 warm-up launches, then windows of R back-to-back launches
     between two events on the launch stream (R sized for a window of at least 50 ms, at least 100
@@ -495,6 +589,9 @@ def main() -> int:
     ap.add_argument("--audit", action="store_true",
                     help="guard of the cost model: on about 34 shapes, the dispatch's choice against every tile forced in "
                          "turn; one JSON object; exit status 3 if a choice is more than 10 %% and 1 us behind the best tile")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-phase breakdown of product launches from the measurement build of the library "
+                         "(libgemmf32_timeline.so, built with -DGEMMF32_TIMELINE; built here if missing); one JSON object")
     ap.add_argument("--sources-sha256", action="store_true", help="print the kernel source hash and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run pack_b on a 4096x4096 row-major B (a plain 64 MiB -> 64 MiB copy) "
@@ -512,8 +609,18 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     from paper_2002_02268_amd import binding, synth
+    if args.timeline:
+        # the measurement build stands in for the product library in this process
+        from paper_2002_02268_amd import build as lib_build
+        if not os.path.exists(lib_build.TIMELINE_LIB):
+            lib_build.build_timeline()
+        binding.LIB_PATH = lib_build.TIMELINE_LIB
     binding.lib()
     torch.cuda.set_device(0)
+
+    if args.timeline:
+        print(json.dumps(timeline(torch, binding)))
+        return 0
 
     if args.copy_calibration:
         B = torch.rand(4096, 4096, device="cuda")

@@ -29,6 +29,9 @@ namespace {
 // disturb each other.
 thread_local hipStream_t g_stream = nullptr;
 thread_local int g_last_hip_error = 0;
+#ifdef GEMMF32_TIMELINE
+unsigned long long *g_timeline_stamps = nullptr;   // measurement build only (see the kernel header)
+#endif
 
 constexpr int64_t kMaxDim = 2147483647LL;
 constexpr int64_t kMaxElems = 1LL << 40;
@@ -173,8 +176,6 @@ int strip_cols(const Hooks &hooks, int tile, int64_t batch, int64_t N, int bmode
     const int64_t rest = N % sh.bn;
     return (N >= sh.bn && rest >= 1 && rest <= kStripMax) ? (int)rest : 0;
 }
-// (the strip addresses a B stored K x N with 32-bit byte offsets)
-bool strip_fits(int64_t K, int64_t ldb, int bmode) { return bmode != B_NN || (K + 1024) * ldb < (1LL << 30); }
 
 struct TailSplit { int64_t tail; int64_t pieces; int64_t piece_k; double benefit_us; bool quad; };
 
@@ -358,7 +359,7 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
     for (const auto &c : kCandidates) {
         if (forced_tile >= 0 ? c.id != forced_tile : !admissible(hooks, c.id, batch, M, N, K, bmode, amode)) continue;
         const TileShape &sh = kShapes[c.id];
-        const int strip = strip_cols(hooks, c.id, batch, N, bmode, amode);       // only without K ranges (and taken to fit: see strip_fits)
+        const int strip = strip_cols(hooks, c.id, batch, N, bmode, amode);       // only without K ranges
         const int64_t tiles_whole = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
         for (int S : kSplits) {
@@ -556,7 +557,7 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     }
     if (pl.thin != 0) pl.split = 1;             // the arguments below stay those of the whole product
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
-    const int strip = (pl.split == 1 && pl.thin == 0 && strip_fits(K, ldb, bmode)) ? strip_cols(hooks, pl.tile, batch, N, bmode, amode) : 0;
+    const int strip = (pl.split == 1 && pl.thin == 0) ? strip_cols(hooks, pl.tile, batch, N, bmode, amode) : 0;
     const int64_t tiles_m = cdiv(M, bm), tiles_n = strip > 0 ? N / bn : cdiv(N, bn);
     const int64_t total = (pl.split > 1 ? pl.split : batch) * tiles_m * tiles_n;
     if (total > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
@@ -586,6 +587,9 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.quad = 0;
     a.alpha = alpha;
     a.beta = beta;
+#ifdef GEMMF32_TIMELINE
+    a.stamps = g_timeline_stamps;
+#endif
     pl.tail_tiles = 0;
     // Split tail: when the last round of tiles would leave most compute units idle, its tiles are
     // cut along K so that the round fills the chip (272 tiles = one full round + 16 tiles -> those
@@ -865,6 +869,15 @@ int gemm_f32_ex_batched(int64_t batch, int64_t M, int64_t N, int64_t K, float al
     return run_plan(make_plan(batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC,
                               transB ? B_NT : B_NN, transA ? A_KM : A_MK, alpha, beta));
 }
+
+#ifdef GEMMF32_TIMELINE
+// measurement build only: DEVICE buffer of 8 * 4096 64-bit slots that later launches stamp (NULL: off)
+int gemm_f32_timeline_set(void *stamps)
+{
+    g_timeline_stamps = reinterpret_cast<unsigned long long *>(stamps);
+    return GEMMF32_OK;
+}
+#endif
 
 int64_t pack_b_panel_width(void) { return kPanel; }
 

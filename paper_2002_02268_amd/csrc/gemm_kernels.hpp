@@ -83,7 +83,26 @@ struct KArgs {
     // Epilogue: C = alpha * (A*B) + beta * C_old.  beta == 0: C_old is never read.  The paper's
     // product is alpha = 1, beta = 0.
     float alpha, beta;
+#ifdef GEMMF32_TIMELINE
+    unsigned long long *stamps;   // measurement build only: 8 slots per workgroup, see GEMMF32_STAMP
+#endif
 };
+
+// Measurement build (-DGEMMF32_TIMELINE, a library of its own that bench.py --timeline loads): thread 0 of
+// every workgroup writes the constant 100 MHz clock into slot i of its row of `stamps` as it passes:
+//   0 kernel entry   1 first slab in LDS (before the first matrix instruction)   2 last whole slab multiplied
+//   3 epilogue begins   4 (waves that share the slabs) sums in LDS   5 stores issued   6 hardware id
+// The product library is built without the macro and contains none of this.
+#ifdef GEMMF32_TIMELINE
+constexpr int kTimelineMaxWorkgroups = 4096;
+__device__ __forceinline__ void timeline_stamp(const KArgs &p, int i)
+{
+    if (p.stamps != nullptr && threadIdx.x == 0 && blockIdx.x < kTimelineMaxWorkgroups) p.stamps[blockIdx.x * 8 + i] = wall_clock64();
+}
+#define GEMMF32_STAMP(p, i) timeline_stamp(p, i)
+#else
+#define GEMMF32_STAMP(p, i) ((void)0)
+#endif
 
 template <int N> struct VecOf;
 template <> struct VecOf<1> { typedef float type; typedef float gtype; };
@@ -761,6 +780,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         }
         store_slab(0, first_set{});
         lds_barrier();
+        GEMMF32_STAMP(p, 1);
         read_frag(f0, 0, 0);
         // the loop is unrolled PF times so that the register set of every slab is a compile-time choice
         int t = 0;
@@ -777,6 +797,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
             }
         });
     }
+    GEMMF32_STAMP(p, 2);
     // ---- a K shorter than one slab: its K % BK columns, not pipelined ----------------------------
     if (kleft > 0 && nkf == 0) {
         load_tail(false, kleft);
@@ -792,6 +813,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         }
     }
 
+    GEMMF32_STAMP(p, 3);
     // ---- epilogue: accumulators -> C (overwrite; predicated at the M / N edges) ---------------
     auto row_ok = [&](int gi) { return SHIFTED ? gi >= m_own : (EDGE == 0 || gi < M); };
     auto cols_ok = [&](int gj, int n) { return SHIFTED ? gj >= n_own : (EDGE == 0 || gj + n <= N); };
@@ -844,6 +866,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                     red[kq * RW + r * RS + c] = acc[i][j][v];
                 }
         __syncthreads();
+        GEMMF32_STAMP(p, 4);
         constexpr int PASS_ROWS = NTHR / BN;                  // rows one pass of all threads covers
         const int li = tid / BN, lj = tid % BN;
         if constexpr (BUF) {
@@ -1020,25 +1043,28 @@ template <class T, bool = (T::BM * T::BN <= 128 * 64 && T::THREADS == 256 && T::
 template <class T> struct QuadOf<T, true> { typedef Tile<32, 32, 64, 1, 1, T::BMODE, T::OCC, 2, T::AMODE, 4> type; };
 
 // The strip of a product (see KArgs): C[i][n0 + s] = sum_k A[i][k] * opB[k][n0 + s] for s < S <= kStripMax, A
-// stored M x K.  A wave takes R consecutive rows of C; its lanes stride over k 16 bytes of A at a time, each
-// lane multiplies its four k against the S columns of B (read straight from global memory: 16 bytes along a
-// row of B stored K x N, 16 bytes along k of B stored N x K), and at the end the 64 partial sums of every
-// (row, column) are added across the lanes in a fixed order, so the result does not depend on the launch.
-// No LDS, no barrier: waves are independent.
+// stored M x K.  A wave takes R consecutive rows of C, a workgroup of four waves 4R; its lanes stride over k 16
+// bytes of A at a time, each lane multiplies its four k against the S columns of B, and at the end the 64
+// partial sums of every (row, column) are added across the lanes in a fixed order, so the result does not
+// depend on the launch.  K is walked in chunks of 256 * BATCH; per chunk the workgroup brings the S columns of
+// B into LDS once for its four waves (zero-filled beyond K).
 // The workgroup shares its compute unit with a tile whose waves issue one matrix instruction after the
 // other; measured, a wave beside them gets to issue about one vector instruction per matrix instruction
-// (64 cycles), whatever its priority, and a round trip to memory takes several microseconds.  So the strip
-// is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows), a wave executes a
-// few hundred instructions in all, and the loads of up to 1024 k are requested before the first is used.
+// (64 cycles), whatever its priority, a round trip to memory takes several microseconds, and every cache line
+// a load instruction touches costs the compute unit's cache a lookup that the tile's own loads then wait
+// behind (a wave that gathered B's rows by itself, 64 lines per instruction, delayed the tiles' first slab by
+// 4 us).  So the strip is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows),
+// a wave executes a few hundred instructions in all, B's columns are fetched once per workgroup with two
+// lanes per row, and all loads of a chunk are requested before the first is used.  (Letting the strip sleep for
+// 2 or 3 us so that the tiles' first slabs go ahead of its requests was measured and is no faster.)
 constexpr int kStripMax = 8;
 template <int BMODE, int R>
-__device__ __forceinline__ void strip_rows(const KArgs &p, const int wg)
+__device__ __forceinline__ void strip_rows(const KArgs &p, float *lds, const int wg)
 {
     __builtin_amdgcn_s_setprio(3);                 // its few instructions go first where they can
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = p.strip_cols, n0 = p.strip_n0, K = p.K, M = p.M;
     const int r0 = (wg * 4 + wave) * R;
-    if (r0 >= M) return;
     const float *x[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -1062,62 +1088,78 @@ __device__ __forceinline__ void strip_rows(const KArgs &p, const int wg)
         }
         return v;
     };
-    constexpr int BATCH = (R == 4) ? 2 : 4;        // groups of 256 k requested together (what the registers hold)
-    // (B stored K x N is addressed with 32-bit offsets from its first strip column: the plan sends a product
-    // here only if K * ldb * 4 fits 32 bits)
-    [[maybe_unused]] const int ldb32 = __builtin_amdgcn_readfirstlane((int)p.ldb);
-    for (int k0 = 0; k0 < K; k0 += 256 * BATCH) {
-        [[maybe_unused]] const float *y_org = nullptr;
-        [[maybe_unused]] unsigned y_lane = 0;
-        if constexpr (BMODE == B_NN) {
-            y_org = uniform_pointer(p.B + (int64_t)k0 * p.ldb + n0);
-            y_lane = (unsigned)(4 * lane * ldb32) * 4u;
-        }
+    constexpr int BATCH = (R == 4) ? 2 : 4;        // groups of 256 k per chunk (what the registers hold)
+    constexpr int KC = 256 * BATCH, QUARTER = KC / 4;
+    // LDS word address of (k, s) within a chunk: (((s / 4) * 4 + k % 4) * QUARTER + k / 4) * 4 + s % 4: the 64 lanes
+    // of a wave, which hold consecutive groups of four k, read consecutive 16-byte pieces
+    for (int k0 = 0; k0 < K; k0 += KC) {
+        const int len = (K - k0 < KC) ? (K - k0) : KC;
+        // ---- requests: the wave's rows of A ...
         v4f xv[BATCH][R];
-        v4f yv[BATCH][kStripMax];                  // B stored N x K: [column s];  K x N: [2 * e + h]: row k + e, columns 4h ..
 #pragma unroll
         for (int it = 0; it < BATCH; ++it) {
-            const int kk = k0 + 256 * it + 4 * lane;              // this lane's four k of the group
+            const int kk = 256 * it + 4 * lane;                   // this lane's four k of the group, within the chunk
 #pragma unroll
-            for (int j = 0; j < R; ++j) xv[it][j] = (kk < K) ? load_some(x[j] + k0 + 256 * it, K - kk) : zero4;
-            if constexpr (BMODE == B_NT) {
+            for (int j = 0; j < R; ++j) xv[it][j] = (kk < len) ? load_some(x[j] + k0 + 256 * it, len - kk) : zero4;
+        }
+        // ... and B's columns, once for the four waves
+        constexpr int NY = (BMODE == B_NT) ? kStripMax : KC / 128;
+        v4f yv[NY];
+        if constexpr (BMODE == B_NT) {
+            // column s, k = 4 * tid ..: 16 bytes along k
 #pragma unroll
-                for (int s = 0; s < kStripMax; ++s)
-                    yv[it][s] = (s < S && kk < K) ? load_some(p.B + (int64_t)(n0 + s) * p.ldb + kk, K - kk) : zero4;
-            } else {
-                // rows kk .. kk + 3 of B, columns n0 .. n0 + 7: the lane's offset is one register, the row's and the
-                // group's offsets are scalar (a vector instruction per address would cost more than the product).
-                // The 16 bytes may run past column N into the next row of B, which exists for every row but the
-                // last: that one is read element by element.
+            for (int sy = 0; sy < kStripMax; ++sy)
+                yv[sy] = (sy < S && 4 * tid < KC) ? load_some(p.B + (int64_t)(n0 + sy) * p.ldb + k0 + 4 * tid, len - 4 * tid) : zero4;
+        } else {
+            // two lanes per row of B: row tid / 2 + 128 u, columns 4 (tid % 2) ..  The 16 bytes may run past column
+            // N into the next row of B, which exists for every row but the last.
+            const int h = tid & 1;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        v4f v = zero4;
-                        if (4 * h < S) {                                  // uniform
-                            if (kk + e + 1 < K) v = buffer_load4(y_org, y_lane + (unsigned)((256 * it + e) * ldb32 + 4 * h) * 4u);
-                            else if (kk + e < K) v = load_some(p.B + (int64_t)(kk + e) * p.ldb + n0 + 4 * h, S - 4 * h);
-                        }
-                        yv[it][2 * e + h] = v;
-                    }
+            for (int u = 0; u < NY; ++u) {
+                const int ky = (tid >> 1) + 128 * u;
+                yv[u] = (ky < len && 4 * h < S) ? load_some(p.B + (int64_t)(k0 + ky) * p.ldb + n0 + 4 * h, (k0 + ky + 1 < K) ? 4 : S - 4 * h) : zero4;
             }
         }
+        // ---- B's columns into LDS
+        if constexpr (BMODE == B_NT) {
+#pragma unroll
+            for (int sy = 0; sy < kStripMax; ++sy)
+                if (sy < S && 4 * tid < KC) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lds[((((sy >> 2) << 2) + e) * QUARTER + tid) * 4 + (sy & 3)] = yv[sy][e];
+                }
+        } else {
+            const int h = tid & 1;
+#pragma unroll
+            for (int u = 0; u < NY; ++u) {
+                const int ky = (tid >> 1) + 128 * u;
+                if (4 * h < S) *reinterpret_cast<v4f *>(lds + (((h << 2) + (ky & 3)) * QUARTER + (ky >> 2)) * 4) = yv[u];
+            }
+        }
+        __syncthreads();
 #pragma unroll
         for (int it = 0; it < BATCH; ++it) {
-            if (k0 + 256 * it < K) {                                      // uniform
+            if (256 * it < len) {                                         // uniform
+                const int q4 = lane + 64 * it;                            // (this lane's k of the group) / 4
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < 4; ++e) {
+                    const v4f y0 = *reinterpret_cast<const v4f *>(lds + (e * QUARTER + q4) * 4);
+                    v4f y1 = zero4;
+                    if (S > 4) y1 = *reinterpret_cast<const v4f *>(lds + ((4 + e) * QUARTER + q4) * 4);
 #pragma unroll
                     for (int s = 0; s < kStripMax; ++s) {
                         if (s < S) {                                      // uniform
-                            const float yy = (BMODE == B_NT) ? yv[it][s][e] : yv[it][2 * e + (s >> 2)][s & 3];
+                            const float yy = (s < 4) ? y0[s & 3] : y1[s & 3];
 #pragma unroll
                             for (int j = 0; j < R; ++j) acc[s][j] = __builtin_fmaf(xv[it][j][e], yy, acc[s][j]);
                         }
                     }
+                }
             }
         }
+        __syncthreads();
     }
+    GEMMF32_STAMP(p, 2);
     // Sum over the lanes: value v = R * s + j, NV = 8 * R of them.  Each of the first log2(NV) steps halves the
     // number of values a lane carries: the lanes whose bit is clear keep the lower half and receive their
     // partner's partial sums of it, the others the upper half; then a lane carries value
@@ -1157,12 +1199,20 @@ template <class T>
 __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
 {
     extern __shared__ __align__(16) float lds[];
+#ifdef GEMMF32_TIMELINE
+    if (p.stamps != nullptr && threadIdx.x == 0 && blockIdx.x < kTimelineMaxWorkgroups) {
+        p.stamps[blockIdx.x * 8] = wall_clock64();
+        // XCC_ID (hardware register 20) and HW_ID (4): which compute unit the workgroup ran on
+        p.stamps[blockIdx.x * 8 + 6] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) | (unsigned)__builtin_amdgcn_s_getreg(63492);
+    }
+#endif
     if constexpr (T::THREADS == 256 && T::WGK == 1 && T::AMODE == A_MK && T::BMODE != B_PACKED) {
         if ((int)blockIdx.x >= p.strip_first) {
             const int wg = (int)blockIdx.x - p.strip_first;
-            if (p.strip_r == 1) strip_rows<T::BMODE, 1>(p, wg);
-            else if (p.strip_r == 2) strip_rows<T::BMODE, 2>(p, wg);
-            else strip_rows<T::BMODE, 4>(p, wg);
+            if (p.strip_r == 1) strip_rows<T::BMODE, 1>(p, lds, wg);
+            else if (p.strip_r == 2) strip_rows<T::BMODE, 2>(p, lds, wg);
+            else strip_rows<T::BMODE, 4>(p, lds, wg);
+            GEMMF32_STAMP(p, 5);
             return;
         }
     }
@@ -1182,6 +1232,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
             const int qm = tm * (T::BM / 32) + sub / SUB_N, qn = tn * SUB_N + sub % SUB_N;
             if (qm * 32 >= p.M || qn * 32 >= p.N) return;      // a block of an edge tile that lies outside the matrix
             run_tile<QT>(p, lds, 0, qm, qn);
+            GEMMF32_STAMP(p, 5);
             return;
         }
     }
@@ -1206,6 +1257,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
     }
     run_tile<T>(q, lds, batch, tm, tn);
+    GEMMF32_STAMP(p, 5);
 }
 
 // Products with at most 8 rows (or columns) whose two operands both have k contiguous (A stored M x K, B

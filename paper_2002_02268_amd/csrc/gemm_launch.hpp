@@ -84,8 +84,9 @@ template <class T> int launch(const KArgs &a)
     // waves that share the slabs add their accumulators through LDS at the end
     constexpr int kSumBytes = (T::WGK > 1) ? T::WGK * T::BM * (T::BN + 1) * 4 : 0;
     if (lds_bytes < kSumBytes) lds_bytes = kSumBytes;
-    // the strip workgroups need the kernel that contains them
+    // the strip workgroups need the kernel that contains them, and 32 KB of LDS for B's columns
     if (a.strip_cols > 0 && !(T::THREADS == 256 && T::WGK == 1 && T::AMODE == A_MK && T::BMODE != B_PACKED)) return GEMMF32_EINVAL;
+    if (a.strip_cols > 0 && lds_bytes < 32768) lds_bytes = 32768;
     const KArgs &b = a;
     hipLaunchKernelGGL(kern, dim3((unsigned)b.total_tiles), dim3(T::THREADS), lds_bytes, current_stream(), b);
     hipError_t e = hipGetLastError();
