@@ -124,9 +124,12 @@ class Runner:
         # After idling the chip takes about 30 ms of matrix work to reach its steady clock (the first
         # launches of square4096 take 1.08 ms, the thirtieth 0.92 ms): the device is brought to speed
         # before the W warm-up steps, however few those are; none of this is timed.
+        # Launched back to back in groups of 20 (a wait after every launch would leave the chip idle half of
+        # the time on the small workloads, and its clock short of where the timed launches then take it).
         t_settle = time.perf_counter()
         while time.perf_counter() - t_settle < SETTLE_S:
-            self.step()
+            for _ in range(20):
+                self.step()
             torch.cuda.synchronize()
         for _ in range(warmup):
             self.step()
@@ -402,6 +405,7 @@ TIMELINE_CASES = [
 ]
 TIMELINE_SLOTS = ["start", "first slab in LDS", "last whole slab multiplied", "epilogue begins", "sums of the slab-sharing waves in LDS",
                   "stores issued"]
+TIMELINE_STRIP_SLOTS = ["start", "", "B's columns of the first chunk in LDS", "products summed over k", "", "sums over the lanes stored"]
 
 
 def timeline(torch, binding):
@@ -470,7 +474,8 @@ def timeline(torch, binding):
             ph = {"workgroups": int(mask.sum())}
             for a, b in zip(cols[:-1], cols[1:]):
                 d = rel[mask, b] - rel[mask, a]
-                ph[f"{TIMELINE_SLOTS[a]} -> {TIMELINE_SLOTS[b]}"] = [round(float(d.mean()), 2), round(float(np.median(d)), 2), round(float(d.max()), 2)]
+                names = TIMELINE_STRIP_SLOTS if kind == "strip workgroups" else TIMELINE_SLOTS
+                ph[f"{names[a]} -> {names[b]}"] = [round(float(d.mean()), 2), round(float(np.median(d)), 2), round(float(d.max()), 2)]
             ph["end"] = [round(float(rel[mask, 5].mean()), 2), round(float(np.median(rel[mask, 5])), 2), round(float(rel[mask, 5].max()), 2)]
             res["phases_us_mean_median_max"][kind] = ph
         ids = raw[:, 6][done]

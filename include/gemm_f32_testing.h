@@ -26,6 +26,10 @@ extern "C" {
  *   no_thin        never the vector-unit kernel for products with at most 4 rows or columns
  *   force_thin     that kernel wherever it can run (at most 8 rows or columns, both operands with k contiguous)
  *   no_strip       never the vector-unit strip for the last few columns of C: they take an edge tile column
+ *   force_strip    that strip wherever it can run (by default the cost model weighs it against the edge tile column)
+ *   strip_rows     0, or 1, 2, 4: rows of C per wave of a strip workgroup, in place of the library's own figure
+ *   strip_wait     0, or 1 + the number of 1024-cycle pauses the strip workgroups take before their first load
+ *                  (1: none; at most 65), in place of the library's own figure
  * gemm_f32_set_test_hooks(NULL) restores production.  Returns GEMMF32_EINVAL for values out of range
  * (nothing is changed then).  Changing the hooks while another thread is inside a call is a race in the
  * sense that the call may see the old or the new setting, never a mixture that is invalid.
@@ -40,6 +44,9 @@ typedef struct {
     int32_t no_thin;
     int32_t force_thin;
     int32_t no_strip;
+    int32_t strip_wait;
+    int32_t force_strip;
+    int32_t strip_rows;
 } gemmf32_test_hooks;
 
 int gemm_f32_set_test_hooks(const gemmf32_test_hooks *hooks);

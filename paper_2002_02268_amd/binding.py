@@ -155,7 +155,8 @@ class HookSettings(ctypes.Structure):
     """gemmf32_test_hooks (include/gemm_f32_testing.h)"""
     _fields_ = [("force_tile", ctypes.c_int32), ("force_split", ctypes.c_int32), ("no_tail_split", ctypes.c_int32),
                 ("no_quad", ctypes.c_int32), ("no_kshare", ctypes.c_int32), ("no_thin", ctypes.c_int32),
-                ("force_thin", ctypes.c_int32), ("no_strip", ctypes.c_int32)]
+                ("force_thin", ctypes.c_int32), ("no_strip", ctypes.c_int32), ("strip_wait", ctypes.c_int32),
+                ("force_strip", ctypes.c_int32), ("strip_rows", ctypes.c_int32)]
 
 
 _hooks = {}
@@ -175,7 +176,7 @@ def set_test_hooks(**changes) -> None:
         else:
             _hooks[key] = int(value)
     h = HookSettings(force_tile=_hooks.get("force_tile", -1), force_split=_hooks.get("force_split", 0),
-                  **{k: _hooks.get(k, 0) for k in ("no_tail_split", "no_quad", "no_kshare", "no_thin", "force_thin", "no_strip")})
+                  **{k: _hooks.get(k, 0) for k in ("no_tail_split", "no_quad", "no_kshare", "no_thin", "force_thin", "no_strip", "strip_wait", "force_strip", "strip_rows")})
     _check(lib().gemm_f32_set_test_hooks(ctypes.byref(h)))
 
 

@@ -114,7 +114,7 @@ int launch_batched64(int64_t batch, const float *A, int64_t lda, int64_t sA, con
 constexpr double kCuFlopsPerUs = 157.3e6 / 256.0;
 constexpr int64_t kMaxWorkspaceBytes = 256LL << 20;
 
-struct Choice { int tile; int split; };
+struct Choice { int tile; int split; int strip; };   // strip: last columns of C left to the strip workgroups (0: none)
 
 // What each variant sustains, fitted to measurements: the fraction of a compute unit's MFMA peak when
 // the launch is a single round of workgroups (`single`) and when several workgroups per compute unit
@@ -152,17 +152,21 @@ struct Hooks {
     bool no_tail_split, no_quad, no_kshare, no_thin, force_thin;
     int force_tile, force_split;       // -1: not forced
     bool no_strip;
+    int strip_wait;                    // -1: the library's own
+    bool force_strip;
+    int strip_rows;                    // 0: the library's own
 };
 struct HookState {
     std::atomic<int> force_tile{-1}, force_split{-1};
-    std::atomic<int> no_tail_split{0}, no_quad{0}, no_kshare{0}, no_thin{0}, force_thin{0}, no_strip{0};
+    std::atomic<int> no_tail_split{0}, no_quad{0}, no_kshare{0}, no_thin{0}, force_thin{0}, no_strip{0}, strip_wait{0}, force_strip{0}, strip_rows{0};
 } g_hooks;
 Hooks read_hooks()
 {
     const auto get = [](const std::atomic<int> &a) { return a.load(std::memory_order_relaxed); };
     return Hooks{get(g_hooks.no_tail_split) != 0, get(g_hooks.no_quad) != 0, get(g_hooks.no_kshare) != 0,
                  get(g_hooks.no_thin) != 0,       get(g_hooks.force_thin) != 0, get(g_hooks.force_tile),
-                 get(g_hooks.force_split),        get(g_hooks.no_strip) != 0};
+                 get(g_hooks.force_split),        get(g_hooks.no_strip) != 0,   get(g_hooks.strip_wait) - 1,
+                 get(g_hooks.force_strip) != 0,   get(g_hooks.strip_rows)};
 }
 
 // Columns of C left to the strip workgroups (kernel header, KArgs): when N is at most kStripMax columns more
@@ -264,7 +268,7 @@ Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int6
     const int forced_tile = hooks.force_tile >= 0 ? hooks.force_tile : g_forced_tile;
     const int forced_split = hooks.force_split >= 1 ? hooks.force_split : g_forced_split;
     const ChoiceKey key = {batch, M, N, K, bmode, amode, forced_tile, forced_split,
-                           (hooks.no_tail_split ? 1 : 0) | (hooks.no_quad ? 2 : 0) | (hooks.no_kshare ? 4 : 0) | (hooks.no_strip ? 8 : 0)};
+                           (hooks.no_tail_split ? 1 : 0) | (hooks.no_quad ? 2 : 0) | (hooks.no_kshare ? 4 : 0) | (hooks.no_strip ? 8 : 0) | (hooks.force_strip ? 16 : 0)};
     const uint64_t h = ((uint64_t)M * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)N * 0xC2B2AE3D27D4EB4Full) ^
                        ((uint64_t)K * 0x165667B19E3779F9ull) ^ ((uint64_t)batch * 0x27D4EB2F165667C5ull);
     ChoiceSlot &slot = g_choice_cache[h >> 58];
@@ -300,7 +304,7 @@ Choice choose_tile(const Hooks &hooks, int64_t batch, int64_t M, int64_t N, int6
         // (the lowered nest counts the K ranges that are not empty; the plan derives the same count from the split)
         const int64_t k_range = cdiv(cdiv(K, slot.choice.split), sh.bk) * sh.bk;
         if (tile >= 0 && got.split == (slot.choice.split > 1 ? (int)cdiv(K, k_range) : 1)) {
-            slot.choice = {tile, slot.choice.split};
+            slot.choice = {tile, slot.choice.split, slot.choice.strip};
             g_strategy_applied.fetch_add(1, std::memory_order_relaxed);
         } else {
             g_strategy_failed.fetch_add(1, std::memory_order_relaxed);     // the model's answer stands
@@ -354,16 +358,21 @@ bool admissible(const Hooks &hooks, int tile, int64_t batch, int64_t M, int64_t 
 Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split, int64_t batch, int64_t M, int64_t N,
                            int64_t K, int bmode, int amode)
 {
-    Choice best = {TB64, 1};
+    Choice best = {TB64, 1, 0};
     double best_cost = -1, best_area = 0;
     for (const auto &c : kCandidates) {
         if (forced_tile >= 0 ? c.id != forced_tile : !admissible(hooks, c.id, batch, M, N, K, bmode, amode)) continue;
         const TileShape &sh = kShapes[c.id];
-        const int strip = strip_cols(hooks, c.id, batch, N, bmode, amode);       // only without K ranges
+        const int strip_max = strip_cols(hooks, c.id, batch, N, bmode, amode);   // only without K ranges
         const int64_t tiles_whole = batch * cdiv(M, sh.bm) * cdiv(N, sh.bn);
         static const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512};
-        for (int S : kSplits) {
+        // (a shape that allows a strip is tried with it and, its last columns an edge tile column, without)
+        for (int si = (strip_max > 0 ? -1 : 0); si < (int)(sizeof(kSplits) / sizeof(kSplits[0])); ++si) {
+            int S = si < 0 ? 1 : kSplits[si];
             if (forced_split >= 1) S = forced_split;
+            const int strip = (si < 0 && S == 1) ? strip_max : 0;
+            if (si < 0 && S != 1) continue;
+            if (hooks.force_strip && strip_max > 0 && si >= 0 && S == 1) continue;
             if (S > 1) {
                 // every range holds whole slabs and at least two of them; one product only
                 if (batch != 1 || K < (int64_t)S * 2 * sh.bk) break;
@@ -393,9 +402,11 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             // and fewer fixed costs is still the faster: a small share of the compute cost breaks the tie)
             cost = std::max(cost, hbm_us) + 0.02 * cost;
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
-            // the strip runs beside the tiles (measured: about half a microsecond on the launch); a tile that
-            // fills a compute unit's registers leaves it no room, and it runs after the tiles
-            if (S == 1 && strip > 0) cost += (sh.bm * sh.bn >= 256 * 256) ? 6.0 + 0.002 * (double)K : 0.5;
+            // the strip runs beside the tiles, most of it while they wait for their first slab, which it delays
+            // (measured against the same product without the last columns: 1.3 us at K = 1000), so it pays where
+            // it saves a round of tiles or a split one, not where the edge tile column fits the last round
+            // anyway.  A tile that fills a compute unit's registers leaves it no room, and it runs after the tiles.
+            if (strip > 0) cost += (sh.bm * sh.bn >= 256 * 256) ? 6.0 + 0.002 * (double)K : 1.5;
             if (S == 1) cost -= plan_tail_split(hooks, c.id, batch, tiles, K).benefit_us;
             // equal cost (the two orientations of a tile on the same number of rounds): the one that
             // computes less padding
@@ -405,13 +416,13 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             if (best_cost < 0 || cost < 0.99 * best_cost || (cost == best_cost && area < best_area)) {
                 best_cost = cost;
                 best_area = area;
-                best = {c.id, S};
+                best = {c.id, S, strip};
             }
-            if (forced_split >= 1) break;
+            if (forced_split >= 1 && si >= 0) break;
         }
     }
-    if (best_cost < 0 && forced_tile >= 0) best = {forced_tile, 1};   // forced split did not fit: no split
-    if (batch == 1 && M <= 64 && N <= 64 && K <= 64 && forced_tile < 0) best = {TB64, 1};
+    if (best_cost < 0 && forced_tile >= 0) best = {forced_tile, 1, 0};   // forced split did not fit: no split
+    if (batch == 1 && M <= 64 && N <= 64 && K <= 64 && forced_tile < 0) best = {TB64, 1, 0};
     return best;
 }
 
@@ -557,7 +568,9 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     }
     if (pl.thin != 0) pl.split = 1;             // the arguments below stay those of the whole product
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;
-    const int strip = (pl.split == 1 && pl.thin == 0) ? strip_cols(hooks, pl.tile, batch, N, bmode, amode) : 0;
+    // (the strip addresses a row of A and a chunk of 1024 rows of B through 32-bit offsets)
+    const bool strip_fits = K < (1LL << 30) && (bmode != B_NN || ldb < (1LL << 20));
+    const int strip = (pl.split == 1 && pl.thin == 0 && strip_fits) ? ch.strip : 0;
     const int64_t tiles_m = cdiv(M, bm), tiles_n = strip > 0 ? N / bn : cdiv(N, bn);
     const int64_t total = (pl.split > 1 ? pl.split : batch) * tiles_m * tiles_n;
     if (total > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
@@ -629,8 +642,11 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     if (strip > 0) {
         a.strip_cols = strip;
         a.strip_n0 = (int)(N - strip);
-        // as many strip workgroups as compute units where the rows allow it: 1, 2 or 4 rows per wave
-        a.strip_r = M <= 1024 ? 1 : (M <= 2048 ? 2 : 4);
+        // 1, 2 or 4 rows per wave (measured: one row up to 512 rows of C, two up to 2048: 1024 x 1028 x 1024 19.1 us
+        // against 19.6 with one, 1536 x 1541 x 1536 56.5 against 60.8; four beyond: 4096 x 4100 x 4096 910 against 916)
+        a.strip_r = M <= 512 ? 1 : (M <= 2048 ? 2 : 4);
+        if (hooks.strip_rows > 0) a.strip_r = hooks.strip_rows;
+        a.strip_wait = hooks.strip_wait >= 0 ? hooks.strip_wait : 0;
         const int64_t strip_wgs = cdiv(M, 4 * a.strip_r);
         if ((int64_t)a.total_tiles + strip_wgs > kMaxDim) { pl.status = GEMMF32_EINVAL; return pl; }
         a.total_tiles += (int)strip_wgs;
@@ -984,9 +1000,11 @@ int gemm_f32_noalloc(int64_t M, int64_t N, int64_t K, const float *A, int64_t ld
 
 int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)
 {
-    const gemmf32_test_hooks off = {-1, 0, 0, 0, 0, 0, 0, 0};
+    const gemmf32_test_hooks off = {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     if (h == nullptr) h = &off;
-    if (h->force_tile < -1 || h->force_tile >= NUM_TILES || h->force_split < 0 || h->force_split > 256) return GEMMF32_EINVAL;
+    if (h->force_tile < -1 || h->force_tile >= NUM_TILES || h->force_split < 0 || h->force_split > 256 ||
+        h->strip_wait < 0 || h->strip_wait > 65 || (h->strip_rows != 0 && h->strip_rows != 1 && h->strip_rows != 2 && h->strip_rows != 4))
+        return GEMMF32_EINVAL;
     g_hooks.force_tile.store(h->force_tile);
     g_hooks.force_split.store(h->force_split >= 1 ? h->force_split : -1);
     g_hooks.no_tail_split.store(h->no_tail_split != 0);
@@ -995,6 +1013,9 @@ int gemm_f32_set_test_hooks(const gemmf32_test_hooks *h)
     g_hooks.no_thin.store(h->no_thin != 0);
     g_hooks.force_thin.store(h->force_thin != 0);
     g_hooks.no_strip.store(h->no_strip != 0);
+    g_hooks.strip_wait.store(h->strip_wait);
+    g_hooks.force_strip.store(h->force_strip != 0);
+    g_hooks.strip_rows.store(h->strip_rows);
     return GEMMF32_OK;
 }
 

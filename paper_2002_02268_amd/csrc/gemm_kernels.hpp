@@ -80,6 +80,7 @@ struct KArgs {
     // the tiles: a tile column of matrix work for a handful of columns would cost a whole round.
     // strip_cols == 0: off, and strip_first is the grid size.
     int strip_first, strip_cols, strip_n0, strip_r;
+    int strip_wait;                 // pauses of 1024 cycles a strip workgroup takes before its first load
     // Epilogue: C = alpha * (A*B) + beta * C_old.  beta == 0: C_old is never read.  The paper's
     // product is alpha = 1, beta = 0.
     float alpha, beta;
@@ -1044,131 +1045,135 @@ template <class T> struct QuadOf<T, true> { typedef Tile<32, 32, 64, 1, 1, T::BM
 
 // The strip of a product (see KArgs): C[i][n0 + s] = sum_k A[i][k] * opB[k][n0 + s] for s < S <= kStripMax, A
 // stored M x K.  A wave takes R consecutive rows of C, a workgroup of four waves 4R; its lanes stride over k 16
-// bytes of A at a time, each lane multiplies its four k against the S columns of B, and at the end the 64
+// bytes of A at a time, each lane multiplies its four k against the columns of B, and at the end the 64
 // partial sums of every (row, column) are added across the lanes in a fixed order, so the result does not
-// depend on the launch.  K is walked in chunks of 256 * BATCH; per chunk the workgroup brings the S columns of
-// B into LDS once for its four waves (zero-filled beyond K).
+// depend on the launch.  K is walked in chunks of 256 * BATCH.
 // The workgroup shares its compute unit with a tile whose waves issue one matrix instruction after the
-// other; measured, a wave beside them gets to issue about one vector instruction per matrix instruction
-// (64 cycles), whatever its priority, a round trip to memory takes several microseconds, and every cache line
-// a load instruction touches costs the compute unit's cache a lookup that the tile's own loads then wait
-// behind (a wave that gathered B's rows by itself, 64 lines per instruction, delayed the tiles' first slab by
-// 4 us).  So the strip is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows),
-// a wave executes a few hundred instructions in all, B's columns are fetched once per workgroup with two
-// lanes per row, and all loads of a chunk are requested before the first is used.  (Letting the strip sleep for
-// 2 or 3 us so that the tiles' first slabs go ahead of its requests was measured and is no faster.)
+// other; measured, a wave beside them gets to issue about one instruction of any kind per matrix instruction
+// (64 cycles), whatever its priority: what the strip costs is the number of instructions a wave executes.
+// So the code is straight-line: four (S <= 4) or eight columns are carried whatever S is, in groups of four
+// that end at column N (columns n0 + S - 4 .. N - 1, and for S > 4 also n0 .. n0 + 3; a column carried twice or
+// one that belongs to the tiles is computed and not stored), so that every 16 bytes read from a row of B lie
+// inside that row, and the ragged ends along k are left to the range check of buffer descriptors (a dword at or
+// beyond the range reads as zero, dword by dword, without a branch or a select).  With B stored N x K a lane
+// reads its columns straight from memory (16 bytes along k, as for A); with B stored K x N the workgroup brings
+// the columns of a chunk into LDS once for its four waves, two lanes per row of B (one per row for S <= 4).
+// The strip is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows).
 constexpr int kStripMax = 8;
-template <int BMODE, int R>
+template <int BMODE, int R, bool WIDE>
 __device__ __forceinline__ void strip_rows(const KArgs &p, float *lds, const int wg)
 {
     __builtin_amdgcn_s_setprio(3);                 // its few instructions go first where they can
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = 0; i < p.strip_wait; ++i) __builtin_amdgcn_s_sleep(16);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int S = p.strip_cols, n0 = p.strip_n0, K = p.K, M = p.M;
     const int r0 = (wg * 4 + wave) * R;
-    const float *x[R];
+    constexpr int NS = WIDE ? 8 : 4;               // columns carried
+    constexpr int FLAGS = 0x00020000;              // 32-bit data
+    // carried column s is column c0 + s (s < 4) or c1 + s - 4 of C
+    const int c0 = (S >= 4) ? n0 : n0 + S - 4, c1 = n0 + S - 4;
+    const unsigned row_bytes = 4u * (unsigned)K;   // (K < 2^30 where a strip is planned)
+    __amdgpu_buffer_rsrc_t xr[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int r = (r0 + j < M) ? (r0 + j) : (M - 1);          // rows past the end repeat the last one; not stored
-        x[j] = p.A + (int64_t)r * p.lda + 4 * lane;
+        xr[j] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(uniform_pointer(p.A + (int64_t)r * p.lda)), 0, (int)row_bytes, FLAGS);
     }
-    const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
-    float acc[kStripMax][R];
+    float acc[NS][R];
 #pragma unroll
-    for (int s = 0; s < kStripMax; ++s)
+    for (int s = 0; s < NS; ++s)
 #pragma unroll
         for (int j = 0; j < R; ++j) acc[s][j] = 0.f;
-    // 16 bytes from src, of which only the first `valid` floats may be touched (the rest read as zero)
-    auto load_some = [&](const float *src, int valid) {
-        v4f v = zero4;
-        if (valid >= 4) v = load4(src);
-        else {
-#pragma unroll
-            for (int e = 0; e < 3; ++e)
-                if (e < valid) v[e] = src[e];
-        }
-        return v;
+    auto load16 = [&](const __amdgpu_buffer_rsrc_t &rsrc, unsigned byte_offset) {
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 0));
     };
-    constexpr int BATCH = (R == 4) ? 2 : 4;        // groups of 256 k per chunk (what the registers hold)
-    constexpr int KC = 256 * BATCH, QUARTER = KC / 4;
-    // LDS word address of (k, s) within a chunk: (((s / 4) * 4 + k % 4) * QUARTER + k / 4) * 4 + s % 4: the 64 lanes
-    // of a wave, which hold consecutive groups of four k, read consecutive 16-byte pieces
-    for (int k0 = 0; k0 < K; k0 += KC) {
-        const int len = (K - k0 < KC) ? (K - k0) : KC;
-        // ---- requests: the wave's rows of A ...
-        v4f xv[BATCH][R];
+    if constexpr (BMODE == B_NT) {
+        constexpr int BATCH = 2, KC = 256 * BATCH;
+        __amdgpu_buffer_rsrc_t yr[NS];
 #pragma unroll
-        for (int it = 0; it < BATCH; ++it) {
-            const int kk = 256 * it + 4 * lane;                   // this lane's four k of the group, within the chunk
-#pragma unroll
-            for (int j = 0; j < R; ++j) xv[it][j] = (kk < len) ? load_some(x[j] + k0 + 256 * it, len - kk) : zero4;
+        for (int s = 0; s < NS; ++s) {
+            const int col = (s < 4) ? c0 + s : c1 + s - 4;
+            yr[s] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(uniform_pointer(p.B + (int64_t)col * p.ldb)), 0, (int)row_bytes, FLAGS);
         }
-        // ... and B's columns, once for the four waves
-        constexpr int NY = (BMODE == B_NT) ? kStripMax : KC / 128;
-        v4f yv[NY];
-        if constexpr (BMODE == B_NT) {
-            // column s, k = 4 * tid ..: 16 bytes along k
+        for (int k0 = 0; k0 < K; k0 += KC) {
+            const unsigned off = 4u * (unsigned)(k0 + 4 * lane);
+            v4f xv[BATCH][R], yv[BATCH][NS];
 #pragma unroll
-            for (int sy = 0; sy < kStripMax; ++sy)
-                yv[sy] = (sy < S && 4 * tid < KC) ? load_some(p.B + (int64_t)(n0 + sy) * p.ldb + k0 + 4 * tid, len - 4 * tid) : zero4;
-        } else {
-            // two lanes per row of B: row tid / 2 + 128 u, columns 4 (tid % 2) ..  The 16 bytes may run past column
-            // N into the next row of B, which exists for every row but the last.
-            const int h = tid & 1;
+            for (int it = 0; it < BATCH; ++it) {
 #pragma unroll
-            for (int u = 0; u < NY; ++u) {
-                const int ky = (tid >> 1) + 128 * u;
-                yv[u] = (ky < len && 4 * h < S) ? load_some(p.B + (int64_t)(k0 + ky) * p.ldb + n0 + 4 * h, (k0 + ky + 1 < K) ? 4 : S - 4 * h) : zero4;
+                for (int j = 0; j < R; ++j) xv[it][j] = load16(xr[j], off + 1024u * it);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) yv[it][s] = load16(yr[s], off + 1024u * it);
             }
+            if (k0 == 0) GEMMF32_STAMP(p, 2);
+#pragma unroll
+            for (int it = 0; it < BATCH; ++it)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int s = 0; s < NS; ++s)
+#pragma unroll
+                        for (int j = 0; j < R; ++j) acc[s][j] = __builtin_fmaf(xv[it][j][e], yv[it][s][e], acc[s][j]);
         }
-        // ---- B's columns into LDS
-        if constexpr (BMODE == B_NT) {
+    } else {
+        constexpr int BATCH = (R == 4) ? 2 : 4;    // groups of 256 k per chunk (what the registers hold)
+        constexpr int KC = 256 * BATCH, QUARTER = KC / 4;
+        // LDS word address of (k, s) within a chunk: (((s / 4) * 4 + k % 4) * QUARTER + k / 4) * 4 + s % 4: the 64 lanes
+        // of a wave, which hold consecutive groups of four k, read consecutive 16-byte pieces
+        constexpr int ROWS = WIDE ? 128 : 256;     // rows of B the workgroup fetches per request
+        constexpr int NY = KC / ROWS;
+        const int h = WIDE ? (tid & 1) : 0, ky0 = WIDE ? (tid >> 1) : tid;
+        // the lane's position in a chunk of B, from the chunk's first row at column c0
+        const unsigned y_off = 4u * ((unsigned)ky0 * (unsigned)p.ldb + (unsigned)(h ? c1 - c0 : 0));
+        const unsigned y_step = 4u * (unsigned)ROWS * (unsigned)p.ldb;       // (ldb < 2^20 where a strip is planned)
+        float *y_dst = lds + (((h << 2) + (ky0 & 3)) * QUARTER + (ky0 >> 2)) * 4;
+        const float *y_src = lds + lane * 4;
+        for (int k0 = 0; k0 < K; k0 += KC) {
+            const unsigned off = 4u * (unsigned)(k0 + 4 * lane);
+            v4f xv[BATCH][R];
 #pragma unroll
-            for (int sy = 0; sy < kStripMax; ++sy)
-                if (sy < S && 4 * tid < KC) {
+            for (int it = 0; it < BATCH; ++it)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) lds[((((sy >> 2) << 2) + e) * QUARTER + tid) * 4 + (sy & 3)] = yv[sy][e];
-                }
-        } else {
-            const int h = tid & 1;
+                for (int j = 0; j < R; ++j) xv[it][j] = load16(xr[j], off + 1024u * it);
+            // B from row k0 on: its range ends behind column N of row K - 1, so rows from K on read as zeros
+            const int64_t left = ((int64_t)(K - 1 - k0) * p.ldb + (n0 + S - c0)) * 4;
+            const __amdgpu_buffer_rsrc_t br = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float *>(uniform_pointer(p.B + (int64_t)k0 * p.ldb + c0)), 0,
+                (int)(unsigned)(left < 0xFFFFFFFFLL ? left : 0xFFFFFFFFLL), FLAGS);
+            v4f yv[NY];
 #pragma unroll
-            for (int u = 0; u < NY; ++u) {
-                const int ky = (tid >> 1) + 128 * u;
-                if (4 * h < S) *reinterpret_cast<v4f *>(lds + (((h << 2) + (ky & 3)) * QUARTER + (ky >> 2)) * 4) = yv[u];
-            }
-        }
-        __syncthreads();
+            for (int u = 0; u < NY; ++u) yv[u] = load16(br, y_off + y_step * u);
+            if (k0 > 0) __syncthreads();           // the chunk before has been read
 #pragma unroll
-        for (int it = 0; it < BATCH; ++it) {
-            if (256 * it < len) {                                         // uniform
-                const int q4 = lane + 64 * it;                            // (this lane's k of the group) / 4
+            for (int u = 0; u < NY; ++u) *reinterpret_cast<v4f *>(y_dst + u * (ROWS / 4) * 4) = yv[u];
+            __syncthreads();
+            if (k0 == 0) GEMMF32_STAMP(p, 2);
+#pragma unroll
+            for (int it = 0; it < BATCH; ++it)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const v4f y0 = *reinterpret_cast<const v4f *>(lds + (e * QUARTER + q4) * 4);
-                    v4f y1 = zero4;
-                    if (S > 4) y1 = *reinterpret_cast<const v4f *>(lds + ((4 + e) * QUARTER + q4) * 4);
+                    v4f y[NS / 4];
 #pragma unroll
-                    for (int s = 0; s < kStripMax; ++s) {
-                        if (s < S) {                                      // uniform
-                            const float yy = (s < 4) ? y0[s & 3] : y1[s & 3];
+                    for (int g = 0; g < NS / 4; ++g)
+                        y[g] = *reinterpret_cast<const v4f *>(y_src + (((g << 2) + e) * QUARTER + 64 * it) * 4);
 #pragma unroll
-                            for (int j = 0; j < R; ++j) acc[s][j] = __builtin_fmaf(xv[it][j][e], yy, acc[s][j]);
-                        }
-                    }
+                    for (int s = 0; s < NS; ++s)
+#pragma unroll
+                        for (int j = 0; j < R; ++j) acc[s][j] = __builtin_fmaf(xv[it][j][e], y[s >> 2][s & 3], acc[s][j]);
                 }
-            }
         }
-        __syncthreads();
     }
-    GEMMF32_STAMP(p, 2);
-    // Sum over the lanes: value v = R * s + j, NV = 8 * R of them.  Each of the first log2(NV) steps halves the
+    GEMMF32_STAMP(p, 3);
+    // Sum over the lanes: value v = R * s + j, NV = NS * R of them.  Each of the first log2(NV) steps halves the
     // number of values a lane carries: the lanes whose bit is clear keep the lower half and receive their
     // partner's partial sums of it, the others the upper half; then a lane carries value
     // lane >> (6 - log2(NV)), and the remaining steps add the lanes that carry the same value.  A fixed
     // order of additions, and NV - 1 + (6 - log2(NV)) exchanges instead of 6 per value.
-    constexpr int NV = kStripMax * R;
+    constexpr int NV = NS * R;
     float vals[NV];
 #pragma unroll
-    for (int s = 0; s < kStripMax; ++s)
+    for (int s = 0; s < NS; ++s)
 #pragma unroll
         for (int j = 0; j < R; ++j) vals[R * s + j] = acc[s][j];
     int bit = 32;
@@ -1177,8 +1182,11 @@ __device__ __forceinline__ void strip_rows(const KArgs &p, float *lds, const int
         const bool upper = (lane & bit) != 0;
 #pragma unroll
         for (int i = 0; i < half; ++i) {
-            const float keep = upper ? vals[i + half] : vals[i];
-            const float send = upper ? vals[i] : vals[i + half];
+            // both values are read before the choice: with the reads inside the two arms the compiler selects
+            // the index instead and walks the whole array for every access
+            const float lo = vals[i], hi = vals[i + half];
+            const float keep = upper ? hi : lo;
+            const float send = upper ? lo : hi;
             vals[i] = keep + __shfl_xor(send, bit, 64);
         }
     }
@@ -1187,8 +1195,10 @@ __device__ __forceinline__ void strip_rows(const KArgs &p, float *lds, const int
 #pragma unroll
     for (int off = SAME / 2; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
     const int v = lane / SAME, s = v / R, j = v % R;
-    if (lane % SAME == 0 && s < S && r0 + j < M) {
-        float *dst = p.C + (int64_t)(r0 + j) * p.ldc + n0 + s;
+    const int col = (s < 4) ? c0 + s : c1 + s - 4;
+    const bool own = (s < 4) ? (col >= n0) : (col >= n0 + 4);   // not a column of the tiles, and not carried twice
+    if (lane % SAME == 0 && own && r0 + j < M) {
+        float *dst = p.C + (int64_t)(r0 + j) * p.ldc + col;
         float out = p.alpha * total;
         if (p.beta != 0.f) out += p.beta * *dst;
         *dst = out;
@@ -1209,9 +1219,10 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
     if constexpr (T::THREADS == 256 && T::WGK == 1 && T::AMODE == A_MK && T::BMODE != B_PACKED) {
         if ((int)blockIdx.x >= p.strip_first) {
             const int wg = (int)blockIdx.x - p.strip_first;
-            if (p.strip_r == 1) strip_rows<T::BMODE, 1>(p, lds, wg);
-            else if (p.strip_r == 2) strip_rows<T::BMODE, 2>(p, lds, wg);
-            else strip_rows<T::BMODE, 4>(p, lds, wg);
+            const bool wide = p.strip_cols > 4;
+            if (p.strip_r == 1) { if (wide) strip_rows<T::BMODE, 1, true>(p, lds, wg); else strip_rows<T::BMODE, 1, false>(p, lds, wg); }
+            else if (p.strip_r == 2) { if (wide) strip_rows<T::BMODE, 2, true>(p, lds, wg); else strip_rows<T::BMODE, 2, false>(p, lds, wg); }
+            else { if (wide) strip_rows<T::BMODE, 4, true>(p, lds, wg); else strip_rows<T::BMODE, 4, false>(p, lds, wg); }
             GEMMF32_STAMP(p, 5);
             return;
         }

@@ -639,7 +639,9 @@ def test_strip_columns_bit_exact(force_tile, tile, transB):
     multiples of the 16 rows a strip workgroup takes, K below one request, ragged, and longer than what the strip
     stages in LDS at a time; integer operands (exact), NaN in old C and in the padding of all three matrices."""
     force_tile(tile)
-    binding.set_test_hooks(force_split=1)          # (a long K with a small output would otherwise be split into ranges)
+    # (a long K with a small output would otherwise be split into ranges; and where the edge tile column fits the
+    # round the cost model would keep it)
+    binding.set_test_hooks(force_split=1, force_strip=True)
     BM, BN = TILE_DIMS[tile]
     cases = [(BM * 2 + 5, BN + 1, 77), (37, BN + 3, 300), (16, 2 * BN + 4, 1), (130, BN + 5, 2500), (BM + 17, BN + 8, 1031),
              (70, BN + 3, 0)]
@@ -658,6 +660,33 @@ def test_strip_columns_bit_exact(force_tile, tile, transB):
         assert np.array_equal(whole[:, :N].astype(np.float64), ref)
         assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     binding.set_test_hooks()
+
+
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("rows", [1, 2, 4])
+def test_strip_rows_per_wave_and_pause(rows, transB):
+    """The strip with one, two and four rows of C per wave (the library picks by M), with and without the pause
+    before its first load, narrow (S <= 4) and wide: integer operands, exact; row counts that leave the last
+    workgroup partly empty; K of several chunks with a ragged end."""
+    try:
+        for wait in (0, 3):
+            binding.set_test_hooks(force_tile=3, force_strip=True, force_split=1, strip_rows=rows, strip_wait=wait)  # the 64x64x64 tile
+            for idx, (M, N, K) in enumerate([(4 * rows * 5 + 3, 64 + 3, 2100), (97, 128 + 7, 1025), (8, 64 + 8, 513)]):
+                name = binding.variant_name(M, N, K, transB=transB)
+                print(f"strip rows={rows} wait={wait} transB={transB} M={M} N={N} K={K} {name}", flush=True)
+                assert "/strip" in name, name
+                A = synth.small_ints((M, K), 650 + idx, synth.TENSOR_A)
+                B = synth.small_ints((N, K) if transB else (K, N), 650 + idx, synth.TENSOR_B)
+                ref = oracle.gemm_f32(A, B, transB=transB, nthreads=NTHREADS)
+                dA, _ = padded_dev(A, 3)
+                dB, _ = padded_dev(B, 5)
+                dC, bufC = padded_dev(np.full((M, N), np.nan, np.float32), 2)
+                binding.gemm_f32(dA, dB, dC, transB=transB)
+                whole = bufC.cpu().numpy()
+                assert np.array_equal(whole[:, :N].astype(np.float64), ref)
+                assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
+    finally:
+        binding.set_test_hooks()
 
 
 def test_strip_uniform_operands_scalings_and_switch():
