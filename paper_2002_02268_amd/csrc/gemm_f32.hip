@@ -555,16 +555,17 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     pl.tile = ch.tile;
     pl.split = ch.split;
     // At most 4 rows or columns, both operands with k contiguous, a long side too short to give 256 blocks of
-    // 32 and a long operand of at least 128 MB: streamed by the vector-unit kernel instead of 32-wide tiles
-    // with K ranges and a second pass (4 x 4096 x 11008: 28.4 instead of 32.4 us).  Measured slower for
-    // shorter operands (the tiles' second pass is cheap against the launch) and for 5 to 8 rows (the short
-    // operand's loads through the caches then outweigh the stream).
+    // 32 and a long operand of at least 160 MB: streamed by the vector-unit kernel instead of 32-wide tiles
+    // with K ranges and a second pass.  Measured on both sides of each bound: 4 x 4096 x 11008 (180 MB) 28.5 us
+    // this way against 32.9 with tiles, 4 x 4096 x 8192 (134 MB) 29.6 against 23.5; 8192 or more rows in the
+    // long operand (256 blocks without K ranges) 48-53 against 39-42; 6 and 8 rows 48-74 against 23-42 (the
+    // short operand's loads through the caches then outweigh the stream).
     pl.thin = 0;
     if (batch == 1 && bmode == B_NT && amode == A_MK && K >= 1 && !hooks.no_thin && hooks.force_tile < 0 &&
         hooks.force_split < 0 && g_forced_tile < 0 && g_forced_split < 0) {
         const bool force_thin = hooks.force_thin;       // test hook: whenever it can run
-        if (M <= 8 && N >= 64 && (force_thin || (M <= 4 && N < 8192 && N * K >= (32LL << 20)))) pl.thin = 1;
-        else if (N <= 8 && M >= 64 && (force_thin || (N <= 4 && M < 8192 && M * K >= (32LL << 20)))) pl.thin = 2;
+        if (M <= 8 && N >= 64 && (force_thin || (M <= 4 && N < 8192 && N * K >= (40LL << 20)))) pl.thin = 1;
+        else if (N <= 8 && M >= 64 && (force_thin || (N <= 4 && M < 8192 && M * K >= (40LL << 20)))) pl.thin = 2;
     }
     if (pl.thin != 0) pl.split = 1;             // the arguments below stay those of the whole product
     const int bm = kShapes[pl.tile].bm, bn = kShapes[pl.tile].bn;

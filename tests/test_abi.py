@@ -132,11 +132,11 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     assert binding.variant_name(32, 4096, 4096).startswith("t32x32x64k4")
     for M, N, K in [(32, 4096, 4096), (1, 8192, 8192), (16, 11008, 4096)]:
         assert binding.variant_name(M, N, K, transB=True).startswith("t32x32x64k4"), (M, N, K)
-    # at most 4 rows or columns, k-contiguous operands, a long operand of at least 128 MB too short for 256
+    # at most 4 rows or columns, k-contiguous operands, a long operand of at least 160 MB too short for 256
     # blocks: the vector-unit kernel; otherwise the tiles
     assert binding.variant_name(4, 4096, 11008, transB=True) == "thin4x4/nt"
     assert binding.variant_name(4096, 2, 14336, transB=True) == "thin2x4/nt"
-    for M, N, K in [(4, 4096, 4096), (5, 4096, 11008), (4, 8192, 8192)]:
+    for M, N, K in [(4, 4096, 4096), (4, 4096, 8192), (5, 4096, 11008), (4, 8192, 8192)]:
         assert not binding.variant_name(M, N, K, transB=True).startswith("thin"), (M, N, K)
     assert not binding.variant_name(4, 4096, 11008).startswith("thin")              # B stored K x N
 
