@@ -28,14 +28,14 @@ HBM_GBS = 8000.0
 # hash of the kernel headers below no longer matches, or the dispatch now picks another variant for the
 # workload, traffic is reported as null.
 TRAFFIC = {
-    "sources_sha256": "b68d92ceda242a4a549b82831564a6412c14e2ac1008c1674250f19e809eda73",
-    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196745.1, "write_kib": 65536.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "square1024": {"variant": "t64x64x64/nn/a16", "fetch_kib": 12383.0, "write_kib": 4096.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "ragged": {"variant": "t64x64x64/nn/a4/strip6", "fetch_kib": 14103.4, "write_kib": 4097.9, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "transb2048": {"variant": "t128x128x16/nt/a16", "fetch_kib": 49239.0, "write_kib": 16384.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135245.7, "write_kib": 1024.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
-    "wide8192": {"variant": "t32x32x64k4/nt/a16", "fetch_kib": 135239.0, "write_kib": 1024.0, "copy_fetch_kib": 32817.9, "copy_write_kib": 65536.0},
+    "sources_sha256": "949a897fb1cf121265f7817d941059fd0ff85ea676af7a3fc128f3e1f88508d5",
+    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196746.1, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "square1024": {"variant": "t64x64x64/nn/a16", "fetch_kib": 12383.5, "write_kib": 4096.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "ragged": {"variant": "t64x64x64/nn/a4/strip6", "fetch_kib": 14111.1, "write_kib": 4097.9, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "transb2048": {"variant": "t128x128x16/nt/a16", "fetch_kib": 49241.0, "write_kib": 16384.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135292.1, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "wide8192": {"variant": "t32x32x64k4/nt/a16", "fetch_kib": 135314.6, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 # What FETCH_SIZE / WRITE_SIZE see: requests of the eight L2 caches to the fabric.  Whether the 256 MB memory-side
@@ -47,7 +47,7 @@ TRAFFIC_KIND = "bytes the L2 caches request from the fabric (memory-side cache o
 SETTLE_S = 0.08        # untimed launches before the warm-up steps, see Runner.time
 
 
-KERNEL_SOURCES = ("gemm_launch.hpp", "gemm_kernels.hpp")    # the device code the measured kernels are built from
+KERNEL_SOURCES = ("gemm_launch.hpp", "gemm_kernels.hpp", "fast_div.hpp")    # the device code the measured kernels are built from
 
 
 def kernel_sources_sha256() -> str:
@@ -325,6 +325,14 @@ def survey(torch, binding, synth, random_shapes=40, seed=3):
             "geomean_ratio": round(geo, 3), "worst_ratio": max(ratios), "best_ratio": min(ratios)}
 
 
+def variant_with_tile(binding, M, N, K, tB, tile):
+    """variant name of a shape with one tile forced (the hooks are left at production)"""
+    binding.set_test_hooks(force_tile=tile)
+    name = binding.variant_name(M, N, K, transB=tB)
+    binding.set_test_hooks()
+    return name
+
+
 AUDIT_FIXED = [(1024, 1024, 1024, False), (1000, 1030, 999, False), (2048, 2048, 2048, True), (4096, 4096, 4096, False),
                (1100, 1100, 1100, False), (1536, 1536, 1536, False), (640, 640, 2048, False), (8192, 32, 8192, False)]
 NUM_TILES = 13
@@ -334,7 +342,7 @@ def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.
     """Guard of the dispatch's cost model: for the fixed shapes above and seeded random ones (M, N log-uniform in
     32..4096, K in 64..8192, either layout of B) the time of the dispatch's own choice against every tile forced
     in turn (each with the split the model picks for it).  A shape fails when the choice takes more than
-    `tolerance` times the best forced tile and more than `slack_us` longer.  Best of three windows each."""
+    `tolerance` times the best forced tile and more than `slack_us` longer, twice in a row.  Best of three windows each."""
     import math
     import random
     rng = random.Random(seed)
@@ -388,10 +396,24 @@ def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.
             best_name = min(forced, key=forced.get)
             t_best = min(forced[best_name], t_chosen)
             ok = t_chosen <= tolerance * t_best or t_chosen - t_best <= slack_us
+            retimed = False
+            if not ok:
+                # Launches of a few microseconds are timed at the rate the host issues them, which wanders by a
+                # microsecond from one window to the next: a failing pair is timed once more, the choice and the
+                # best forced tile one after the other, and fails only if it fails again.
+                retimed = True
+                tile_of_best = [t for t in range(NUM_TILES) if variant_with_tile(binding, M, N, K, tB, t) == best_name][0]
+                t_chosen = min(t_chosen, best_us(fn, 2.0 * M * N * K))
+                binding.set_test_hooks(force_tile=tile_of_best)
+                forced[best_name] = round(min(forced[best_name], best_us(fn, 2.0 * M * N * K)), 2)
+                binding.set_test_hooks()
+                t_chosen = min(t_chosen, best_us(fn, 2.0 * M * N * K))
+                t_best = min(forced[best_name], t_chosen)
+                ok = t_chosen <= tolerance * t_best or t_chosen - t_best <= slack_us
             failures += 0 if ok else 1
             rows.append({"M": M, "N": N, "K": K, "transB": tB, "chosen": chosen, "us": round(t_chosen, 2),
                          "best": best_name, "best_us": forced[best_name], "ratio": round(t_chosen / t_best, 3), "ok": ok,
-                         "forced": forced})
+                         "retimed": retimed, "forced": forced})
             del A, B, C
     finally:
         binding.set_test_hooks()
@@ -411,8 +433,9 @@ TIMELINE_CASES = [
     dict(label="square4096", M=4096, N=4096, K=4096),
 ]
 TIMELINE_SLOTS = ["start", "first slab in LDS", "last whole slab multiplied", "epilogue begins", "sums of the slab-sharing waves in LDS",
-                  "stores issued"]
-TIMELINE_STRIP_SLOTS = ["start", "", "B's columns of the first chunk in LDS", "products summed over k", "", "sums over the lanes stored"]
+                  "stores issued", "", "first slabs requested"]
+TIMELINE_STRIP_SLOTS = ["start", "", "B's columns of the first chunk in LDS", "products summed over k", "", "sums over the lanes stored", "", ""]
+TIMELINE_ORDER = [0, 7, 1, 2, 3, 4, 5]          # slots in the order a workgroup passes them (6 holds the hardware id)
 
 
 def timeline(torch, binding):
@@ -461,7 +484,7 @@ def timeline(torch, binding):
         stamped = event_us()
         raw = st.cpu().numpy().reshape(nwg, 8)
         lib.gemm_f32_timeline_set(None)
-        h = raw[:, :6].astype(np.float64) * 0.01                    # us
+        h = raw[:, :8].astype(np.float64) * 0.01                    # us
         used = raw[:, 0] > 0
         t0 = h[used, 0].min()
         done = used & (raw[:, 5] > 0)                                # (blocks of an edge tile outside the matrix return early)
@@ -477,7 +500,7 @@ def timeline(torch, binding):
         for kind, mask in kinds.items():
             if not mask.any():
                 continue
-            cols = [c for c in range(6) if (raw[mask, c] > 0).all()]
+            cols = [c for c in TIMELINE_ORDER if (raw[mask, c] > 0).all()]
             ph = {"workgroups": int(mask.sum())}
             for a, b in zip(cols[:-1], cols[1:]):
                 d = rel[mask, b] - rel[mask, a]

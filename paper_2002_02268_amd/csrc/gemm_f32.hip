@@ -587,10 +587,8 @@ Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, const float *A, i
     a.M = (int)M; a.N = (int)(N - strip); a.K = (int)K;        // with a strip the tiles end where it begins
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.sA = sA; a.sB = sB; a.sC = sC;
-    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
-    a.tiles_per_batch = (int)(tiles_m * tiles_n);
+    set_tile_walk(a, (int)tiles_m, (int)tiles_n, choose_group_m((int)tiles_m, (int)tiles_n, batch > 1 ? tiles_m * tiles_n : total));
     a.total_tiles = (int)total;
-    a.group_m = choose_group_m((int)tiles_m, (int)tiles_n, batch > 1 ? tiles_m * tiles_n : total);
     a.n_padded = (int)(cdiv(N, kPanel) * kPanel);
     a.k_total = 0;
     a.k_panel = (int)K;

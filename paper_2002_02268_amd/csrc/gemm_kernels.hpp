@@ -32,6 +32,8 @@
 #include <type_traits>
 #include <utility>
 
+#include "fast_div.hpp"
+
 namespace gemmf32 {
 
 typedef float v2f __attribute__((ext_vector_type(2)));
@@ -50,6 +52,12 @@ enum AMode : int { A_MK = 0, A_KM = 1 };
 
 constexpr int kPanel = 128;  // panel width P of the packed-B layout, in elements
 
+// (fast_div.hpp: division of a walk position by a divisor that is fixed for the launch)
+__device__ __forceinline__ int fast_div(int n, const FastDiv f)
+{
+    return f.magic == 0 ? n : (int)(__umulhi((unsigned)n, f.magic) >> f.shift);
+}
+
 struct KArgs {
     const float *A;
     const float *B;
@@ -60,6 +68,9 @@ struct KArgs {
     int tiles_m, tiles_n;    // tile grid of one product
     int group_m;             // tile rows per group in the tile walk
     int tiles_per_batch;     // tiles_m * tiles_n
+    // divisions by tiles_per_batch, by group_m * tiles_n, by group_m and by the rows of the last, shorter group
+    // (tiles_m % group_m, if any), see set_tile_walk
+    FastDiv div_batch, div_group, div_rows, div_last_rows;
     int total_tiles;         // tiles_per_batch * batch == gridDim.x
     int n_padded;            // packed B: number of columns present in the buffer
     int k_total;             // split-K: length of the whole reduction (0: no split).  The "batch" index
@@ -93,6 +104,8 @@ struct KArgs {
 // every workgroup writes the constant 100 MHz clock into slot i of its row of `stamps` as it passes:
 //   0 kernel entry   1 first slab in LDS (before the first matrix instruction)   2 last whole slab multiplied
 //   3 epilogue begins   4 (waves that share the slabs) sums in LDS   5 stores issued   6 hardware id
+//   7 slabs 0 .. PF requested (between 0 and 1)
+// (strip workgroups: 2 B's columns of the first chunk in LDS, 3 products summed over k, 5 sums over the lanes stored)
 // The product library is built without the macro and contains none of this.
 #ifdef GEMMF32_TIMELINE
 constexpr int kTimelineMaxWorkgroups = 4096;
@@ -177,12 +190,25 @@ __device__ __forceinline__ int xcd_contiguous_id(int wg, int total)
 __device__ __forceinline__ void tile_coords(const KArgs &p, int t, int &tm, int &tn)
 {
     const int gsz = p.group_m * p.tiles_n;
-    const int grp = t / gsz;
+    const int grp = fast_div(t, p.div_group);
     const int first_m = grp * p.group_m;
-    const int gm = (p.tiles_m - first_m < p.group_m) ? (p.tiles_m - first_m) : p.group_m;
+    const bool last = p.tiles_m - first_m < p.group_m;
+    const int gm = last ? (p.tiles_m - first_m) : p.group_m;
     const int r = t - grp * gsz;
-    tm = first_m + r % gm;
-    tn = r / gm;
+    tn = last ? fast_div(r, p.div_last_rows) : fast_div(r, p.div_rows);
+    tm = first_m + r - tn * gm;
+}
+// The tile grid of one product and the constants of its walk.
+inline void set_tile_walk(KArgs &a, int tiles_m, int tiles_n, int group_m)
+{
+    a.tiles_m = tiles_m;
+    a.tiles_n = tiles_n;
+    a.tiles_per_batch = tiles_m * tiles_n;
+    a.group_m = group_m;
+    a.div_batch = make_fast_div((unsigned)a.tiles_per_batch);
+    a.div_group = make_fast_div((unsigned)(group_m * tiles_n));
+    a.div_rows = make_fast_div((unsigned)group_m);
+    a.div_last_rows = make_fast_div((unsigned)(group_m > 0 ? tiles_m % group_m : 0));
 }
 
 // Barrier between LDS producers and consumers.  Only LDS traffic has to be complete: global
@@ -506,6 +532,77 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         const int64_t a_adv = advance ? a_step : 0, b_adv = advance ? b_step : 0;
         static_for<A_ITERS + B_ITERS>([&](auto slot_tag) { load_slot(slot_tag, set_tag, a_adv, b_adv); });
     };
+
+    // ---- the first requests go out before the rest of the set-up -----------------------------------
+    // A workgroup is alone on its SIMDs at this point and executes its set-up (fragment offsets, the
+    // accumulators' zeros, the epilogue's constants: some hundred instructions, one after the other)
+    // at about eight cycles each; with the requests first, that time runs under the memory latency.
+    const int nkf = __builtin_amdgcn_readfirstlane(K / BK);   // uniform; kept in a scalar register (see gemm_kernel)
+    const int kleft = K - nkf * BK;
+    typedef std::integral_constant<int, PF> first_set;
+    [[maybe_unused]] v4f ta[A_ITERS], tb[B_ITERS];
+    if (nkf > 0) {
+        const int last = nkf - 1;
+        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  Their loads are
+        // requested ahead of slabs 0 .. PF, they pass through LDS buffer 1 and are multiplied while
+        // slab 0 is still on its way, so that the ragged part costs one barrier instead of a load
+        // latency of its own at the end.  Every slot is one 16-byte load from a position that lies inside
+        // the operand (columns at or beyond kleft re-read column 0, rows re-read row 0; K >= kleft + BK
+        // here, so the 16 bytes never reach past column K); what lies at or beyond kleft is zeroed in
+        // both operands before it reaches LDS.
+        if (kleft > 0) {
+            static_for<A_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                // k index of the slot's first element, and how far back (in elements) the load moves
+                const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
+                const int64_t back = (k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
+                v4f v;
+                if constexpr (RANGED) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4), range_bytes(org_a, end_a));
+                else if constexpr (BUF) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4));
+                else if constexpr (A_ELEMENTWISE) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (pa[r] - back)[a_d[r][e]];
+                } else v = load4(pa[r] - back);
+                ta[r] = v;
+            });
+            static_for<B_ITERS>([&](auto r_tag) {
+                constexpr int r = decltype(r_tag)::value;
+                const int f = tid + r * NTHR;
+                const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
+                const int64_t kstride = (T::BMODE == B_NT) ? 1 : (T::BMODE == B_NN ? p.ldb : (int64_t)kPanel);
+                const int64_t back = (k0 < kleft) ? 0 : (int64_t)k0 * kstride;
+                v4f v;
+                if constexpr (RANGED && T::BMODE != B_NN) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4), range_bytes(org_b, end_b));
+                else if constexpr (BUF) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4));
+                else if constexpr (B_ELEMENTWISE) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (pb[r] - back)[b_d[r][e]];
+                } else v = load4(pb[r] - back);
+                tb[r] = v;
+            });
+            // the whole slabs start kleft columns further along k
+            const int64_t a_skip = A_KMAJOR ? (int64_t)kleft : (int64_t)kleft * p.lda;
+            const int64_t b_skip = (T::BMODE == B_NT) ? (int64_t)kleft : (T::BMODE == B_NN ? (int64_t)kleft * p.ldb : (int64_t)kleft * kPanel);
+            if constexpr (BUF) {
+                org_a = uniform_pointer(org_a + a_skip);
+                org_b = uniform_pointer(org_b + b_skip);
+            } else {
+#pragma unroll
+                for (int r = 0; r < A_ITERS; ++r) pa[r] += a_skip;
+#pragma unroll
+                for (int r = 0; r < B_ITERS; ++r) pb[r] += b_skip;
+            }
+        }
+        // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
+        // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
+        load_slab(first_set{}, 0 < last);                       // slab 0; the pointers move to slab min(1, last)
+        static_for<PF>([&](auto j_tag) {
+            constexpr int j = decltype(j_tag)::value + 1;       // slab min(j, last); then on to min(j + 1, last)
+            load_slab(std::integral_constant<int, j % PF>{}, j < last);
+        });
+        GEMMF32_STAMP(p, 7);
+    }
     // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain.  After
     // the main loop the pointers stand at the last whole slab (at slab 0 if there is none).
     auto load_tail = [&](bool after_whole_slabs, int kleft) {
@@ -642,8 +739,6 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // Issue order inside a slab is pinned with scheduling groups: the LDS reads, LDS writes and
     // global loads are spread one at a time between MFMAs instead of being issued in a burst
     // (a burst from all waves at once fills the LDS queue and stalls MFMA issue behind it).
-    const int nkf = __builtin_amdgcn_readfirstlane(K / BK);   // uniform; kept in a scalar register (see gemm_kernel)
-    const int kleft = K - nkf * BK;
     Frag f0, f1;
     constexpr int N_MFMA = 4 * MB * NB;            // MFMAs of one 8-column group
     constexpr int N_READ = NAV + NBV;              // LDS reads of one fragment set
@@ -689,67 +784,6 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     typedef std::integral_constant<int, 0> i0;
     typedef std::integral_constant<int, 1> i1;
     if (nkf > 0) {
-        const int last = nkf - 1;
-        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  Their loads are
-        // requested ahead of slabs 0 .. PF, they pass through LDS buffer 1 and are multiplied while
-        // slab 0 is still on its way, so that the ragged part costs one barrier instead of a load
-        // latency of its own at the end.  Every slot is one 16-byte load from a position that lies inside
-        // the operand (columns at or beyond kleft re-read column 0, rows re-read row 0; K >= kleft + BK
-        // here, so the 16 bytes never reach past column K); what lies at or beyond kleft is zeroed in
-        // both operands before it reaches LDS.
-        [[maybe_unused]] v4f ta[A_ITERS], tb[B_ITERS];
-        if (kleft > 0) {
-            static_for<A_ITERS>([&](auto r_tag) {
-                constexpr int r = decltype(r_tag)::value;
-                const int f = tid + r * NTHR;
-                // k index of the slot's first element, and how far back (in elements) the load moves
-                const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
-                const int64_t back = (k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
-                v4f v;
-                if constexpr (RANGED) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4), range_bytes(org_a, end_a));
-                else if constexpr (BUF) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4));
-                else if constexpr (A_ELEMENTWISE) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (pa[r] - back)[a_d[r][e]];
-                } else v = load4(pa[r] - back);
-                ta[r] = v;
-            });
-            static_for<B_ITERS>([&](auto r_tag) {
-                constexpr int r = decltype(r_tag)::value;
-                const int f = tid + r * NTHR;
-                const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
-                const int64_t kstride = (T::BMODE == B_NT) ? 1 : (T::BMODE == B_NN ? p.ldb : (int64_t)kPanel);
-                const int64_t back = (k0 < kleft) ? 0 : (int64_t)k0 * kstride;
-                v4f v;
-                if constexpr (RANGED && T::BMODE != B_NN) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4), range_bytes(org_b, end_b));
-                else if constexpr (BUF) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4));
-                else if constexpr (B_ELEMENTWISE) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (pb[r] - back)[b_d[r][e]];
-                } else v = load4(pb[r] - back);
-                tb[r] = v;
-            });
-            // the whole slabs start kleft columns further along k
-            const int64_t a_skip = A_KMAJOR ? (int64_t)kleft : (int64_t)kleft * p.lda;
-            const int64_t b_skip = (T::BMODE == B_NT) ? (int64_t)kleft : (T::BMODE == B_NN ? (int64_t)kleft * p.ldb : (int64_t)kleft * kPanel);
-            if constexpr (BUF) {
-                org_a = uniform_pointer(org_a + a_skip);
-                org_b = uniform_pointer(org_b + b_skip);
-            } else {
-#pragma unroll
-                for (int r = 0; r < A_ITERS; ++r) pa[r] += a_skip;
-#pragma unroll
-                for (int r = 0; r < B_ITERS; ++r) pb[r] += b_skip;
-            }
-        }
-        // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
-        // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
-        typedef std::integral_constant<int, PF> first_set;
-        load_slab(first_set{}, 0 < last);                       // slab 0; the pointers move to slab min(1, last)
-        static_for<PF>([&](auto j_tag) {
-            constexpr int j = decltype(j_tag)::value + 1;       // slab min(j, last); then on to min(j + 1, last)
-            load_slab(std::integral_constant<int, j % PF>{}, j < last);
-        });
         if (kleft > 0) {
             float *As = lds + T::STAGE_FLOATS, *Bs = As + T::A_TILE;          // buffer 1
             static_for<A_ITERS>([&](auto r_tag) {
@@ -771,13 +805,18 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 *reinterpret_cast<v4f *>(&Bs[sb_off[r]]) = v;
             });
             lds_barrier();
-#pragma unroll
-            for (int g = 0; g < GQ; ++g) {
+            // (the fragments of a group are read while the group before it is multiplied)
+            if (8 * GQ * kq < kleft) read_frag(f0, 1, 0);
+            static_for<GQ>([&](auto g_tag) {
+                constexpr int g = decltype(g_tag)::value;
                 if (8 * (GQ * kq + g) < kleft) {
-                    read_frag(f0, 1, g);
-                    mfma_group(f0);
+                    Frag &now = (g & 1) ? f1 : f0;
+                    if constexpr (g + 1 < GQ) {
+                        if (8 * (GQ * kq + g + 1) < kleft) read_frag((g & 1) ? f0 : f1, 1, g + 1);
+                    }
+                    mfma_group(now);
                 }
-            }
+            });
         }
         store_slab(0, first_set{});
         lds_barrier();
@@ -1216,6 +1255,14 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         p.stamps[blockIdx.x * 8 + 6] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) | (unsigned)__builtin_amdgcn_s_getreg(63492);
     }
 #endif
+    // All arguments are requested at once: left alone, the compiler fetches each group of them where it is
+    // first used, one round trip to the scalar cache after the other along the head of the kernel.
+    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.lda), "s"(p.ldb), "s"(p.ldc));
+    asm volatile("" ::"s"(p.sA), "s"(p.sB), "s"(p.sC), "s"(p.tiles_m), "s"(p.tiles_n), "s"(p.group_m), "s"(p.tiles_per_batch),
+                 "s"(p.total_tiles), "s"(p.k_total), "s"(p.tail_first), "s"(p.tail_split), "s"(p.quad), "s"(p.strip_first));
+    asm volatile("" ::"s"(p.div_batch.magic), "s"(p.div_batch.shift), "s"(p.div_group.magic), "s"(p.div_group.shift),
+                 "s"(p.div_rows.magic), "s"(p.div_rows.shift), "s"(p.div_last_rows.magic), "s"(p.div_last_rows.shift),
+                 "s"(p.alpha), "s"(p.beta));
     if constexpr (T::THREADS == 256 && T::WGK == 1 && T::AMODE == A_MK && T::BMODE != B_PACKED) {
         if ((int)blockIdx.x >= p.strip_first) {
             const int wg = (int)blockIdx.x - p.strip_first;
@@ -1264,7 +1311,7 @@ __global__ void __launch_bounds__(T::THREADS, T::OCC) gemm_kernel(const KArgs p)
         q.alpha = 1.f;                 // raw partial sums; the second pass scales
         q.beta = 0.f;
     } else {
-        batch = logical / p.tiles_per_batch;
+        batch = fast_div(logical, p.div_batch);
         tile_coords(p, logical - batch * p.tiles_per_batch, tm, tn);
     }
     run_tile<T>(q, lds, batch, tm, tn);

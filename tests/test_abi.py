@@ -217,6 +217,29 @@ def test_test_hooks_validate_and_reset():
     assert lib.gemm_f32_strerror(-6).decode().startswith("the product needs more scratch")
 
 
+def test_strip_is_weighed_against_the_edge_tile_column():
+    """The last few columns of C go to the strip workgroups where that saves a round of tiles (or a split
+    one), and stay an edge tile column where that column fits the last round anyway; the hooks force either."""
+    import ctypes
+    lib = binding.lib()
+    binding.set_test_hooks()
+    assert binding.variant_name(1000, 1030, 999).endswith("/strip6")            # 16 x 16 tiles + 6 columns: 272 tiles otherwise
+    assert binding.variant_name(4096, 4100, 4096).endswith("/strip4")
+    assert "/strip" not in binding.variant_name(700, 1286, 2000)                # 11 x 21 = 231 tiles: one round either way
+    try:
+        binding.set_test_hooks(force_strip=True, force_tile=3)
+        assert binding.variant_name(700, 1286, 2000).endswith("/strip6")
+        binding.set_test_hooks(force_strip=None, no_strip=True, force_tile=None)
+        assert "/strip" not in binding.variant_name(1000, 1030, 999)
+        # a strip needs 32-bit offsets along a row of A and over a chunk of B stored K x N
+        binding.set_test_hooks()
+        for rows, wait, ok in ((3, 0, False), (8, 0, False), (2, 66, False), (4, 65, True), (0, 0, True)):
+            h = binding.HookSettings(force_tile=-1, strip_rows=rows, strip_wait=wait)
+            assert (lib.gemm_f32_set_test_hooks(ctypes.byref(h)) == 0) == ok, (rows, wait)
+    finally:
+        binding.set_test_hooks()
+
+
 def test_planning_an_empty_sum_over_many_tiles():
     """K = 0 with more tiles than one round and a remainder: the plan of the split last round has nothing to
     cut (this divided by zero once)."""

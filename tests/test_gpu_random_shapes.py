@@ -165,7 +165,7 @@ def test_thin_products_vector_unit_kernel_bit_exact():
             assert np.isnan(whole[:, N:]).all(), "ldc padding was written"
     finally:
         binding.set_test_hooks(force_thin=None)
-    M, N, K = 3, 4100, 8200
+    M, N, K = 3, 4100, 10300
     assert binding.variant_name(M, N, K, transB=True) == "thin3x4/nt"
     A = synth.small_ints((M, K), 9900, synth.TENSOR_A)
     B = synth.small_ints((N, K), 9900, synth.TENSOR_B)
