@@ -540,23 +540,33 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     const int nkf = __builtin_amdgcn_readfirstlane(K / BK);   // uniform; kept in a scalar register (see gemm_kernel)
     const int kleft = K - nkf * BK;
     typedef std::integral_constant<int, PF> first_set;
+    // Late start.  Requesting slabs 0 .. PF before anything else keeps the workgroup's way to memory busy with
+    // slabs 1 .. PF (a compute unit takes in 64 bytes per cycle: 0.2 us per 32 KB slab) while slab 0, the only
+    // one the first matrix instruction waits for, queues with them: measured, a 64 x 64 x 64 tile issued its
+    // requests for 1.06 us and had slab 0 in LDS 0.24 us later.  Tiles with slabs of at least four 8-column groups
+    // and two slabs in registers request slab 0 alone and leave slabs 1 .. PF to the first half of slab 0's
+    // own matrix work (slab_body with FIRST), where their way to memory is idle anyway.
+    constexpr bool LATE_START = (T::GQ >= 4 && PF >= 2);
     [[maybe_unused]] v4f ta[A_ITERS], tb[B_ITERS];
     if (nkf > 0) {
         const int last = nkf - 1;
-        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  Their loads are
-        // requested ahead of slabs 0 .. PF, they pass through LDS buffer 1 and are multiplied while
-        // slab 0 is still on its way, so that the ragged part costs one barrier instead of a load
-        // latency of its own at the end.  Every slot is one 16-byte load from a position that lies inside
-        // the operand (columns at or beyond kleft re-read column 0, rows re-read row 0; K >= kleft + BK
-        // here, so the 16 bytes never reach past column K); what lies at or beyond kleft is zeroed in
-        // both operands before it reaches LDS.
+        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  They are requested
+        // ahead of slabs 0 .. PF, pass through LDS buffer 1 with everything at or beyond column kleft zeroed in
+        // both operands, and are multiplied while slab 0 is still on its way, so that the ragged part costs one
+        // barrier instead of a load latency of its own at the end.  Every slot is one 16-byte load.  With buffer
+        // addressing (IN_PLACE) the slots stand where those of a slab stand (columns 0 .. BK - 1 all exist: K >= kleft + BK
+        // here); per-lane pointers with clamped edges are moved back instead so that each load lies inside the
+        // operand (columns at or beyond kleft re-read column 0, rows re-read row 0).
+        // (So are the tiles of 16 blocks per wave: with their register file full, the plainer form made the
+        // register allocator spill.)
+        constexpr bool IN_PLACE = BUF && MB * NB < 16;
         if (kleft > 0) {
             static_for<A_ITERS>([&](auto r_tag) {
                 constexpr int r = decltype(r_tag)::value;
                 const int f = tid + r * NTHR;
                 // k index of the slot's first element, and how far back (in elements) the load moves
                 const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
-                const int64_t back = (k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
+                const int64_t back = (IN_PLACE || k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
                 v4f v;
                 if constexpr (RANGED) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4), range_bytes(org_a, end_a));
                 else if constexpr (BUF) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4));
@@ -571,7 +581,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 const int f = tid + r * NTHR;
                 const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
                 const int64_t kstride = (T::BMODE == B_NT) ? 1 : (T::BMODE == B_NN ? p.ldb : (int64_t)kPanel);
-                const int64_t back = (k0 < kleft) ? 0 : (int64_t)k0 * kstride;
+                const int64_t back = (IN_PLACE || k0 < kleft) ? 0 : (int64_t)k0 * kstride;
                 v4f v;
                 if constexpr (RANGED && T::BMODE != B_NN) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4), range_bytes(org_b, end_b));
                 else if constexpr (BUF) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4));
@@ -597,10 +607,13 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         // slabs 0 .. PF are all requested before the first of them is waited for: slab 0 into the
         // extra register set, slab j (1 <= j <= PF) into set j % PF, where the loop expects it
         load_slab(first_set{}, 0 < last);                       // slab 0; the pointers move to slab min(1, last)
-        static_for<PF>([&](auto j_tag) {
-            constexpr int j = decltype(j_tag)::value + 1;       // slab min(j, last); then on to min(j + 1, last)
-            load_slab(std::integral_constant<int, j % PF>{}, j < last);
-        });
+        // (late start, see slab_body: with more than PF slabs the loop's first round requests slabs 1 .. PF itself)
+        if (!(LATE_START && nkf > PF)) {
+            static_for<PF>([&](auto j_tag) {
+                constexpr int j = decltype(j_tag)::value + 1;   // slab min(j, last); then on to min(j + 1, last)
+                load_slab(std::integral_constant<int, j % PF>{}, j < last);
+            });
+        }
         GEMMF32_STAMP(p, 7);
     }
     // global -> registers (set 0) for the ragged last slab: kleft (< BK) columns of k remain.  After
@@ -748,9 +761,13 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     // Slab t: multiply it out of LDS buffer t % 2 while
     // slab t+1 goes from register set (t+1) % PF into the other buffer and slab t+1+PF is requested
     // into the same registers (past the end: a harmless re-request of the last full slab).
-    auto slab_body = [&](const int t, auto par_tag, auto more_tag) {
+    auto slab_body = [&](const int t, auto par_tag, auto more_tag, auto first_tag) {
         constexpr int PAR = decltype(par_tag)::value;      // t % PF (register set choice)
         constexpr bool MORE = decltype(more_tag)::value;
+        // the first slab of a late start: slabs 1 .. PF are requested in its first half (slab j into set j % PF,
+        // slab 1's slots first), the actions follow in its second half, when slab 1 has had time to arrive
+        constexpr bool FIRST = decltype(first_tag)::value;
+        static_assert(!FIRST || (MORE && PAR == 0), "the first slab of more than PF");
         const int cur = t & 1;
         typedef std::integral_constant<int, (PAR + 1) % PF> set_t;
         // this slab requests slab min(t + 1 + PF, nkf - 1); the pointers move on if the next request is a later one
@@ -767,14 +784,31 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 lds_barrier();                 // slab t+1 is complete in the other buffer
                 read_frag(next, cur ^ 1, 0);
             }
-            // action i runs in group i * MOVE_GROUPS / N_ACTIONS: spread as evenly as the counts allow
-            constexpr int FIRST = (g * N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
-            constexpr int END = ((g + 1) * N_ACTIONS + MOVE_GROUPS - 1) / MOVE_GROUPS;
-            constexpr int COUNT = (!MORE || g >= MOVE_GROUPS) ? 0 : END - FIRST;
-            constexpr int MOVE_MEM = 2 * COUNT;    // one LDS write and one global load per action
+            // early requests of a first slab: request e is slot e % N_ACTIONS of slab 1 + e / N_ACTIONS
+            constexpr int EARLY_GROUPS = FIRST ? GQ / 2 : 0;
+            constexpr int N_EARLY = PF * N_ACTIONS;
+            constexpr int E_FIRST = (g < EARLY_GROUPS) ? (g * N_EARLY + EARLY_GROUPS - 1) / (EARLY_GROUPS > 0 ? EARLY_GROUPS : 1) : 0;
+            constexpr int E_END = (g < EARLY_GROUPS) ? ((g + 1) * N_EARLY + EARLY_GROUPS - 1) / (EARLY_GROUPS > 0 ? EARLY_GROUPS : 1) : 0;
+            if constexpr (E_END > E_FIRST) {
+                static_for<E_END - E_FIRST>([&](auto i_tag) {
+                    constexpr int e = E_FIRST + decltype(i_tag)::value;
+                    constexpr int j = 1 + e / N_ACTIONS;            // slab min(j, nkf - 1); then on to min(j + 1, nkf - 1)
+                    const bool on = (j < nkf - 1);
+                    load_slot(std::integral_constant<int, e % N_ACTIONS>{}, std::integral_constant<int, j % PF>{},
+                              on ? a_step : 0, on ? b_step : 0);
+                });
+            }
+            // action i runs in group i * (groups with actions) / N_ACTIONS: spread as evenly as the counts allow
+            // over the groups that precede the barrier (a first slab: over the later ones of them)
+            constexpr int A_GROUPS = MOVE_GROUPS - EARLY_GROUPS;
+            constexpr int ga = g - EARLY_GROUPS;
+            constexpr int A_FIRST = (ga >= 0 && ga < A_GROUPS) ? (ga * N_ACTIONS + A_GROUPS - 1) / A_GROUPS : 0;
+            constexpr int A_END = (ga >= 0 && ga < A_GROUPS) ? ((ga + 1) * N_ACTIONS + A_GROUPS - 1) / A_GROUPS : 0;
+            constexpr int COUNT = MORE ? A_END - A_FIRST : 0;
+            constexpr int MOVE_MEM = 2 * COUNT + (E_END - E_FIRST);    // one LDS write and one global load per action
             if constexpr (COUNT > 0) {
                 static_for<COUNT>([&](auto i_tag) {
-                    do_action(std::integral_constant<int, FIRST + decltype(i_tag)::value>{}, cur ^ 1, set_t{}, a_adv, b_adv);
+                    do_action(std::integral_constant<int, A_FIRST + decltype(i_tag)::value>{}, cur ^ 1, set_t{}, a_adv, b_adv);
                 });
             }
             mfma_group(now);
@@ -824,16 +858,24 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         read_frag(f0, 0, 0);
         // the loop is unrolled PF times so that the register set of every slab is a compile-time choice
         int t = 0;
+        if constexpr (LATE_START) {
+            if (PF < nkf) {
+                static_for<PF>([&](auto i_tag) {
+                    slab_body(decltype(i_tag)::value, i_tag, std::true_type{}, std::integral_constant<bool, decltype(i_tag)::value == 0>{});
+                });
+                t = PF;
+            }
+        }
         for (; t + PF < nkf; t += PF)
-            static_for<PF>([&](auto i_tag) { slab_body(t + decltype(i_tag)::value, i_tag, std::true_type{}); });
+            static_for<PF>([&](auto i_tag) { slab_body(t + decltype(i_tag)::value, i_tag, std::true_type{}, std::false_type{}); });
         const int rest = nkf - t;                  // 1 .. PF slabs left; the last one requests nothing
         static_for<PF>([&](auto i_tag) {
             constexpr int i = decltype(i_tag)::value;
             if constexpr (i + 1 < PF) {
-                if (i + 1 < rest) slab_body(t + i, i_tag, std::true_type{});
-                else if (i + 1 == rest) slab_body(t + i, i_tag, std::false_type{});
+                if (i + 1 < rest) slab_body(t + i, i_tag, std::true_type{}, std::false_type{});
+                else if (i + 1 == rest) slab_body(t + i, i_tag, std::false_type{}, std::false_type{});
             } else {
-                if (PF == 1 || i + 1 == rest) slab_body(t + i, i_tag, std::false_type{});
+                if (PF == 1 || i + 1 == rest) slab_body(t + i, i_tag, std::false_type{}, std::false_type{});
             }
         });
     }
