@@ -550,23 +550,20 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
     [[maybe_unused]] v4f ta[A_ITERS], tb[B_ITERS];
     if (nkf > 0) {
         const int last = nkf - 1;
-        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  They are requested
-        // ahead of slabs 0 .. PF, pass through LDS buffer 1 with everything at or beyond column kleft zeroed in
-        // both operands, and are multiplied while slab 0 is still on its way, so that the ragged part costs one
-        // barrier instead of a load latency of its own at the end.  Every slot is one 16-byte load.  With buffer
-        // addressing (IN_PLACE) the slots stand where those of a slab stand (columns 0 .. BK - 1 all exist: K >= kleft + BK
-        // here); per-lane pointers with clamped edges are moved back instead so that each load lies inside the
-        // operand (columns at or beyond kleft re-read column 0, rows re-read row 0).
-        // (So are the tiles of 16 blocks per wave: with their register file full, the plainer form made the
-        // register allocator spill.)
-        constexpr bool IN_PLACE = BUF && MB * NB < 16;
+        // A ragged K: the K % BK odd columns come first, the whole slabs after them.  Their loads are
+        // requested ahead of slabs 0 .. PF, they pass through LDS buffer 1 and are multiplied while
+        // slab 0 is still on its way, so that the ragged part costs one barrier instead of a load
+        // latency of its own at the end.  Every slot is one 16-byte load from a position that lies inside
+        // the operand (columns at or beyond kleft re-read column 0, rows re-read row 0; K >= kleft + BK
+        // here, so the 16 bytes never reach past column K); what lies at or beyond kleft is zeroed in
+        // both operands before it reaches LDS.
         if (kleft > 0) {
             static_for<A_ITERS>([&](auto r_tag) {
                 constexpr int r = decltype(r_tag)::value;
                 const int f = tid + r * NTHR;
                 // k index of the slot's first element, and how far back (in elements) the load moves
                 const int k0 = A_KMAJOR ? (f % A_F4_ROW) * 4 : f / A_F4_ROW;
-                const int64_t back = (IN_PLACE || k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
+                const int64_t back = (k0 < kleft) ? 0 : (A_KMAJOR ? (int64_t)k0 : (int64_t)k0 * p.lda);
                 v4f v;
                 if constexpr (RANGED) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4), range_bytes(org_a, end_a));
                 else if constexpr (BUF) v = buffer_load4(org_a, va[r] - (unsigned)(back * 4));
@@ -581,7 +578,7 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
                 const int f = tid + r * NTHR;
                 const int k0 = B_KMAJOR ? (f % B_F4_ROW) * 4 : f / B_F4_ROW;
                 const int64_t kstride = (T::BMODE == B_NT) ? 1 : (T::BMODE == B_NN ? p.ldb : (int64_t)kPanel);
-                const int64_t back = (IN_PLACE || k0 < kleft) ? 0 : (int64_t)k0 * kstride;
+                const int64_t back = (k0 < kleft) ? 0 : (int64_t)k0 * kstride;
                 v4f v;
                 if constexpr (RANGED && T::BMODE != B_NN) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4), range_bytes(org_b, end_b));
                 else if constexpr (BUF) v = buffer_load4(org_b, vb[r] - (unsigned)(back * 4));
