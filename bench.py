@@ -29,13 +29,13 @@ HBM_GBS = 8000.0
 # workload, traffic is reported as null.
 TRAFFIC = {
     "sources_sha256": "fd0658082a43217e05eefdfdd08332d51329f4d41fa72779082ae7d0acc1fe34",
-    "square4096": {"variant": "t256x256x16/nn/a16", "fetch_kib": 196746.1, "write_kib": 65536.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "square1024": {"variant": "t64x64x64/nn/a16", "fetch_kib": 12401.0, "write_kib": 4096.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "ragged": {"variant": "t64x64x64/nn/a4/strip6", "fetch_kib": 14123.4, "write_kib": 4098.4, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "transb2048": {"variant": "t128x128x16/nt/a16", "fetch_kib": 49241.0, "write_kib": 16384.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135243.4, "write_kib": 1024.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
-    "wide8192": {"variant": "t32x32x64k4/nt/a16", "fetch_kib": 135274.3, "write_kib": 1024.0, "copy_fetch_kib": 32818.0, "copy_write_kib": 65536.0},
+    "square4096": {"variant": "t128x128x16/nn/a16", "fetch_kib": 394737.6, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "square1024": {"variant": "t64x64x64/nn/a16", "fetch_kib": 12401.0, "write_kib": 4096.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "ragged": {"variant": "t64x64x64/nn/a4/strip6", "fetch_kib": 14123.7, "write_kib": 4098.4, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "transb2048": {"variant": "t128x128x16/nt/a16", "fetch_kib": 49241.0, "write_kib": 16384.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "batched64": {"variant": None, "fetch_kib": 65569.5, "write_kib": 65536.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "skinny8192": {"variant": "t32x32x64k4/nn/a16", "fetch_kib": 135279.8, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
+    "wide8192": {"variant": "t32x32x64k4/nt/a16", "fetch_kib": 135283.2, "write_kib": 1024.0, "copy_fetch_kib": 32817.7, "copy_write_kib": 65536.0},
 }
 COPY_KIB = 65536.0
 # What FETCH_SIZE / WRITE_SIZE see: requests of the eight L2 caches to the fabric.  Whether the 256 MB memory-side
@@ -612,6 +612,9 @@ def main() -> int:
     ap.add_argument("--mode", default="plain", choices=["plain", "packed", "pack_only"],
                     help="what a step is: gemm_f32 (plain), gemm_f32_packed on B packed beforehand, or pack_b alone "
                          "(the last two for workloads whose B gets packed, e.g. transb2048)")
+    ap.add_argument("--force-tile", type=int, default=-1,
+                    help="for counter passes of a tile the dispatcher would not pick: tile id 0..12 through the test hook "
+                         "(the line then says so in config.forced_tile, and carries no traffic figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only --workload")
     ap.add_argument("--ladder", action="store_true",
@@ -748,10 +751,15 @@ def main() -> int:
             "forms": forms}))
         return 0
 
+    if args.force_tile >= 0:
+        binding.set_test_hooks(force_tile=args.force_tile)
     main_run = Runner(args.workload, "packed" if args.mode == "pack_only" else args.mode)
     main_run.mode = args.mode
     w = main_run.w
     wall_ms, ev_ms = main_run.time(args.steps, args.warmup)
+    ran_variant = binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"])    # (with the hook still set)
+    if args.force_tile >= 0:
+        binding.set_test_hooks()
     check = vector_check(main_run) if args.mode != "pack_only" else {"kind": "pack_b: bit-exact against the oracle in the tests", "ok": True}
     gflops = flops_of(w) / (wall_ms * 1e-3) / 1e9
     achieved_tflops = flops_of(w) / (ev_ms * 1e-3) / 1e12
@@ -822,10 +830,11 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "mode": args.mode, "M": w["M"], "N": w["N"], "K": w["K"], "batch": w["batch"],
                    "transB": w["transB"], "dist": w["dist"], "seed": w["seed"],
-                   "variant": binding.variant_name(w["M"], w["N"], w["K"], transB=w["transB"]),
-                   "settle_ms": int(SETTLE_S * 1e3)},
+                   "variant": ran_variant,
+                   "settle_ms": int(SETTLE_S * 1e3), **({"forced_tile": args.force_tile} if args.force_tile >= 0 else {})},
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4), "traffic": traffic_bytes(args.workload),
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS, 4),
+                     "traffic": traffic_bytes(args.workload) if args.force_tile < 0 else None,
                      "traffic_kind": TRAFFIC_KIND,
                      # context, not a bound: the clock a kernel of matrix instructions only sustains (the product's own
                      # clock settles elsewhere, its waves also wait, so no ceiling is derived from it)

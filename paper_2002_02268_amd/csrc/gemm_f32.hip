@@ -392,6 +392,12 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             // a matrix shorter than the tile cannot move its edge tiles inside: every tile then runs
             // the masked loads, which cost about a quarter more
             if (M < sh.bm || N < sh.bn) cost *= 1.25;
+            // Measured on ten large shapes: while both operands fit the 256 MB memory-side cache with room to spare,
+            // several rounds of 128 x 128 tiles, two workgroups to a compute unit, overlap their epilogues and
+            // the drain of C with each other's slab loops and come out 0.4-1.8 % ahead of rounds of the 256-wide
+            // tiles (4096^3: 903 against 912 us, 4096 x 4096 x 1024: 233 against 237, 6144^3: 3059 against 3069);
+            // at 8192^3 (512 MB of operands) the large tile is 1 % ahead again (7191 against 7266 us).
+            if (sh.bm * sh.bn >= 256 * 128 && 4.0 * (double)batch * ((double)M * K + (double)K * N) <= 320.0e6) cost *= 1.012;
             // both operands cross the memory interface at least once, at 5.2 TB/s at best: what
             // bounds products with one short dimension
             // (a workgroup keeps about 40 KB in flight, which at the memory latency is 22 GB/s: fewer

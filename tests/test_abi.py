@@ -49,7 +49,8 @@ def test_host_only_queries():
     assert lib.gemm_f32(4, 4, 4, None, 4, None, 4, None, 4, 0) == -2
     assert lib.gemm_f32(0, 4, 4, None, 4, None, 4, None, 4, 0) == 0
     assert lib.gemm_f32_batched(0, 4, 4, 4, None, 4, 16, None, 4, 16, None, 4, 16, 0) == 0
-    assert binding.variant_name(4096, 4096, 4096).startswith("t256")
+    assert binding.variant_name(4096, 4096, 4096).startswith("t128x128")
+    assert binding.variant_name(8192, 8192, 8192).startswith("t256x256")     # operands beyond the memory-side cache
     assert "/a4" in binding.variant_name(1000, 1030, 999)
 
 
@@ -88,14 +89,16 @@ def test_traffic_figures_are_dropped_when_the_kernel_sources_change():
     try:
         bench.TRAFFIC["sources_sha256"] = current
         t = bench.traffic_bytes("square4096")
-        assert t is not None and 4 * 3 * 4096 * 4096 <= t < 4 * 4 * 3 * 4096 * 4096   # between 1x and 4x the compulsory bytes
+        # between 1x and 6x the compulsory bytes (128 x 128 tiles: each of the eight L2 caches asks for its rows of A
+        # and columns of B about six times over)
+        assert t is not None and 4 * 3 * 4096 * 4096 <= t < 6 * 4 * 3 * 4096 * 4096
         bench.TRAFFIC["sources_sha256"] = "0" * 64
         assert bench.traffic_bytes("square4096") is None
         # ... and only while the dispatch still runs the variant they were taken on
         bench.TRAFFIC["sources_sha256"] = current
         variant = bench.TRAFFIC["square4096"]["variant"]
         assert variant == bench.workload_variant("square4096")
-        bench.TRAFFIC["square4096"]["variant"] = "t128x128x16/nn/a16"
+        bench.TRAFFIC["square4096"]["variant"] = "t256x256x16/nn/a16"
         assert bench.traffic_bytes("square4096") is None
         bench.TRAFFIC["square4096"]["variant"] = variant
     finally:
@@ -106,7 +109,7 @@ def test_dispatch_choices_for_the_benchmark_workloads():
     """The tile and split the cost model takes for the workloads the benchmark times (a host computation;
     pinned so that a change of the model's constants shows up here and not only as a slower benchmark)."""
     from paper_2002_02268_amd import synth
-    want = {"square4096": "t256x256x16/nn/a16", "square1024": "t64x64x64/nn/a16", "transb2048": "t128x128x16/nt/a16",
+    want = {"square4096": "t128x128x16/nn/a16", "square1024": "t64x64x64/nn/a16", "transb2048": "t128x128x16/nt/a16",
             "ragged": "t64x64x64/nn/a4/strip6", "skinny8192": "t32x32x64k4/nn/a16",
             "wide8192": "t32x32x64k4/nt/a16"}
     for name, variant in want.items():
@@ -201,7 +204,7 @@ def test_test_hooks_validate_and_reset():
     binding.set_test_hooks(force_tile=None, force_split=4)
     assert binding.variant_name(512, 512, 4096).endswith("splitk4")
     binding.set_test_hooks()
-    assert binding.variant_name(4096, 4096, 4096).startswith("t256x256x16")
+    assert binding.variant_name(4096, 4096, 4096).startswith("t128x128x16")
     bad = binding.HookSettings(force_tile=13)
     import ctypes
     assert lib.gemm_f32_set_test_hooks(ctypes.byref(bad)) == -1
@@ -210,7 +213,7 @@ def test_test_hooks_validate_and_reset():
     import os
     os.environ["GEMMF32_FORCE_TILE"] = "3"
     try:
-        assert binding.variant_name(4096, 4096, 4096).startswith("t256x256x16")
+        assert binding.variant_name(4096, 4096, 4096).startswith("t128x128x16")
     finally:
         os.environ.pop("GEMMF32_FORCE_TILE")
     assert lib.gemm_f32_noalloc_scratch_bytes() == 32 << 20

@@ -298,12 +298,22 @@ def test_workload_square4096_full_oracle():
     """Every element of the 4096 x 4096 output against the fp64 triple loop (about 22 s of oracle time),
     launched as the benchmark launches it; the tolerance is the one stated over the whole output."""
     A, B = workload_refs.operands("square4096")
-    assert binding.variant_name(4096, 4096, 4096) == "t256x256x16/nn/a16"
+    assert binding.variant_name(4096, 4096, 4096) == "t128x128x16/nn/a16"
     dC = torch.full((4096, 4096), float("nan"), device="cuda")
     binding.gemm_f32(dev(A), dev(B), dC)
     C = dC.cpu().numpy()
     check_close(C, workload_refs.reference("square4096"), 4096)
     _vector_check(A, B, C, False, 4096, seed=2)
+    # and the same output through the 256 x 256 tile, one tile per compute unit (what products whose operands
+    # no longer fit the memory-side cache take)
+    binding.set_test_hooks(force_tile=0)
+    try:
+        assert binding.variant_name(4096, 4096, 4096) == "t256x256x16/nn/a16"
+        dC.fill_(float("nan"))
+        binding.gemm_f32(dev(A), dev(B), dC)
+        check_close(dC.cpu().numpy(), workload_refs.reference("square4096"), 4096)
+    finally:
+        binding.set_test_hooks()
 
 
 @pytest.mark.parametrize("name", ["skinny8192", "wide8192"])
