@@ -1136,12 +1136,13 @@ template <class T> struct QuadOf<T, true> { typedef Tile<32, 32, 64, 1, 1, T::BM
 // beyond the range reads as zero, dword by dword, without a branch or a select).  With B stored N x K a lane
 // reads its columns straight from memory (16 bytes along k, as for A); with B stored K x N the workgroup brings
 // the columns of a chunk into LDS once for its four waves, two lanes per row of B (one per row for S <= 4).
-// The strip is spread over as many workgroups as there are compute units (R = 1 up to 1024 rows).
+// The strip is spread over as many workgroups as there are compute units (R = 1 up to 512 rows).  Its waves run
+// at the default priority: raised, they went ahead of the tiles' own set-up on the same SIMDs and delayed the tiles'
+// first requests (ragged workload 20.1 us against 19.6).
 constexpr int kStripMax = 8;
 template <int BMODE, int R, bool WIDE>
 __device__ __forceinline__ void strip_rows(const KArgs &p, float *lds, const int wg)
 {
-    __builtin_amdgcn_s_setprio(3);                 // its few instructions go first where they can
     for (int i = 0; i < p.strip_wait; ++i) __builtin_amdgcn_s_sleep(16);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
