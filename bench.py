@@ -334,7 +334,8 @@ def variant_with_tile(binding, M, N, K, tB, tile):
 
 
 AUDIT_FIXED = [(1024, 1024, 1024, False), (1000, 1030, 999, False), (2048, 2048, 2048, True), (4096, 4096, 4096, False),
-               (1100, 1100, 1100, False), (1536, 1536, 1536, False), (640, 640, 2048, False), (8192, 32, 8192, False)]
+               (1100, 1100, 1100, False), (1536, 1536, 1536, False), (640, 640, 2048, False), (8192, 32, 8192, False),
+               (6144, 6144, 6144, False), (2048, 11008, 4096, True)]
 NUM_TILES = 13
 
 
@@ -631,7 +632,7 @@ def main() -> int:
                     help="time every workload in 20 windows of at least 50 ms (median and best), the latency of one "
                          "square1024 launch, and the batched workload with operands streamed from HBM; one JSON object")
     ap.add_argument("--audit", action="store_true",
-                    help="guard of the cost model: on about 34 shapes, the dispatch's choice against every tile forced in "
+                    help="guard of the cost model: on about 36 shapes, the dispatch's choice against every tile forced in "
                          "turn; one JSON object; exit status 3 if a choice is more than 10 %% and 1 us behind the best tile")
     ap.add_argument("--timeline", action="store_true",
                     help="per-phase breakdown of product launches from the measurement build of the library "

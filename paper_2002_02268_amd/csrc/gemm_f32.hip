@@ -124,10 +124,13 @@ struct Choice { int tile; int split; int strip; };   // strip: last columns of C
 struct VariantModel { int id; double single, multi, overhead_single, overhead_multi; };
 const VariantModel kCandidates[] = {
     {T256, 0.975, 0.976, 63, 53},      {T256x128, 0.956, 0.962, 71, 27},  {T128x256, 0.957, 0.965, 72, 26},
-    {T128, 0.967, 0.976, 103, 40},     {T128x64, 0.958, 0.973, 159, 69},  {T64x128, 0.950, 0.972, 153, 64},
+    {T128, 0.967, 0.976, 103, 40},     {T64x128, 0.950, 0.972, 153, 64},  {T128x64, 0.958, 0.973, 159, 69},
     {TB64, 0.947, 0.963, 259, 110},    {T64, 0.904, 0.954, 213, 90},
     {T128x32, 0.898, 0.933, 223, 294}, {T32x128, 0.895, 0.797, 223, 110},
     {TQ32, 0.715, 0.837, 510, 241},    {TQ64x32, 0.874, 0.900, 429, 188}, {TQ32x64, 0.857, 0.919, 440, 245}};
+// (Of the two orientations of the 128 x 64 tile the one with the longer rows of B comes first and so wins a tie:
+// measured, it is 1-2 % ahead on outputs of five hundred tiles or more, 4352 x 4352 x 4096 1049 against 1068 us,
+// 6144^3 3162 against 3224, and level with the other below that.)
 const VariantModel &variant_model(int tile)
 {
     for (const auto &c : kCandidates)
@@ -146,7 +149,7 @@ double tile_us(const VariantModel &v, int bm, int bn, double k, bool multi)
 // of whole tiles, the second pass already charged.
 // quad: instead, every tail tile is cut into its 32 x 32 blocks (`pieces` of them), each computed by a
 // whole workgroup whose waves share the slabs along k: a quarter of a tile's time per block, and no
-// second pass.  Better than K ranges when K is short (the second pass costs a fixed 10 us).
+// second pass.  Better than K ranges when K is short (the second pass costs its launch whatever K is).
 // Test hooks (gemm_f32_set_test_hooks): process-wide, all off in production.  The environment is never read.
 struct Hooks {
     bool no_tail_split, no_quad, no_kshare, no_thin, force_thin;
@@ -209,10 +212,14 @@ TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t t
     }
     double range_benefit = 0.0;
     if (S > 1 && t.tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
-        // measured: the pieces and the second pass add 10 us and a quarter of a piece's own time (the
-        // pieces, too, start where whole tiles ended early)
+        // measured on launches of 30 us to 3 ms: the second pass adds its launch, 6 us, and the partial products
+        // written and read back at 5 TB/s; the pieces add 0.7 of a piece's own time (they start where whole tiles
+        // ended early), 0.85 for the tile that has a compute unit to itself, whose pieces can only follow the
+        // last whole tile (2048 x 11008 x 4096: 88 tail tiles of 256 x 256 in two pieces each add 441 us to the
+        // 938 us of the whole round, a piece's own time being 459 us)
         const double t_piece = tile_us(vm, bm, bn, (double)units_per_piece * bk, true);
-        range_benefit = t_full - (10.0 + 0.25 * t_piece);
+        const double second_pass = 6.0 + (double)(S + 1) * (double)t.tail * bm * bn * 4.0 / 5.0e6;
+        range_benefit = t_full - (second_pass + (bm * bn >= 256 * 256 ? 0.85 : 0.7) * t_piece);
     }
     if (quad_benefit > 0.0 && quad_benefit >= range_benefit) {
         t.pieces = subs;

@@ -60,20 +60,23 @@ def test_noalloc_matches_gemm_f32_and_the_oracle_on_calls_in_a_row():
 
 def test_noalloc_refuses_a_product_whose_split_needs_more_than_the_array():
     lib = binding.lib()
-    binding.set_test_hooks()
-    lib.gemm_f32_set_stream(None)
-    M = N = 4352
-    K = 4096
-    assert "tail33x7" in binding.variant_name(M, N, K)        # 33 * 7 tiles of 256 x 256 floats: 57.75 MiB
-    dA = torch.zeros((M, K), device="cuda")
-    dB = torch.zeros((K, N), device="cuda")
-    dC = torch.full((M, N), 7.0, device="cuda")
-    rc = lib.gemm_f32_noalloc(M, N, K, dA.data_ptr(), K, dB.data_ptr(), N, dC.data_ptr(), N, 0)
-    assert rc == -6
-    assert "scratch" in lib.gemm_f32_strerror(rc).decode()
-    torch.cuda.synchronize()
-    assert torch.equal(dC, torch.full((M, N), 7.0, device="cuda")), "something was launched"
-    # argument errors are the same as gemm_f32's
-    assert lib.gemm_f32_noalloc(8, 8, 8, dA.data_ptr(), 7, dB.data_ptr(), 8, dC.data_ptr(), 8, 0) == -1
-    assert lib.gemm_f32_noalloc(8, 8, 8, None, 8, dB.data_ptr(), 8, dC.data_ptr(), 8, 0) == -2
-    assert lib.gemm_f32_noalloc(0, 8, 8, None, 8, None, 8, None, 8, 0) == 0
+    binding.set_test_hooks(force_tile=0)                       # the 256 x 256 tile, whatever the cost model prefers
+    try:
+        lib.gemm_f32_set_stream(None)
+        M = N = 4352
+        K = 4096
+        assert "tail33x7" in binding.variant_name(M, N, K)        # 33 * 7 tiles of 256 x 256 floats: 57.75 MiB
+        dA = torch.zeros((M, K), device="cuda")
+        dB = torch.zeros((K, N), device="cuda")
+        dC = torch.full((M, N), 7.0, device="cuda")
+        rc = lib.gemm_f32_noalloc(M, N, K, dA.data_ptr(), K, dB.data_ptr(), N, dC.data_ptr(), N, 0)
+        assert rc == -6
+        assert "scratch" in lib.gemm_f32_strerror(rc).decode()
+        torch.cuda.synchronize()
+        assert torch.equal(dC, torch.full((M, N), 7.0, device="cuda")), "something was launched"
+        # argument errors are the same as gemm_f32's
+        assert lib.gemm_f32_noalloc(8, 8, 8, dA.data_ptr(), 7, dB.data_ptr(), 8, dC.data_ptr(), 8, 0) == -1
+        assert lib.gemm_f32_noalloc(8, 8, 8, None, 8, dB.data_ptr(), 8, dC.data_ptr(), 8, 0) == -2
+        assert lib.gemm_f32_noalloc(0, 8, 8, None, 8, None, 8, None, 8, 0) == 0
+    finally:
+        binding.set_test_hooks()
