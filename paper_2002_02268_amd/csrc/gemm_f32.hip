@@ -206,20 +206,24 @@ TailSplit plan_tail_split(const Hooks &hooks, int tile, int64_t batch, int64_t t
     const int64_t subs = (int64_t)(bm / 32) * (bn / 32);
     // (only tiles whose waves each own a block have the block kernel: the kernel header's QuadOf)
     if (subs > 1 && bm * bn <= 128 * 64 && bm % 32 == 0 && bn % 32 == 0 && kShapes[tile].waves_k == 1 && !hooks.no_quad) {
-        const double t_block = 5.0 + 0.0018 * (double)K;
-        // (whole rounds of blocks: with 272 blocks some compute unit gets two, and the round takes twice as long)
-        quad_benefit = t_full - (double)cdiv(t.tail * subs, 256) * t_block;
+        // (whole rounds of blocks: with 272 blocks some compute unit gets two.  The first round fills in behind the
+        // whole tiles; every further one costs the blocks' own time, 4 ns per column of K: 512 x 6144 x 4096 in
+        // 64 x 128 tiles, 1024 blocks, 72 us)
+        const double block_rounds = (double)cdiv(t.tail * subs, 256);
+        quad_benefit = t_full - (5.0 * block_rounds + (0.0018 + 0.004 * (block_rounds - 1.0)) * (double)K);
     }
     double range_benefit = 0.0;
     if (S > 1 && t.tail * S * bm * bn * 4 <= kMaxWorkspaceBytes) {
         // measured on launches of 30 us to 3 ms: the second pass adds its launch, 6 us, and the partial products
-        // written and read back at 5 TB/s; the pieces add 0.7 of a piece's own time (they start where whole tiles
-        // ended early), 0.85 for the tile that has a compute unit to itself, whose pieces can only follow the
-        // last whole tile (2048 x 11008 x 4096: 88 tail tiles of 256 x 256 in two pieces each add 441 us to the
-        // 938 us of the whole round, a piece's own time being 459 us)
+        // written and read back at 5 TB/s.  The pieces follow the whole tiles, which end within a window of about
+        // 20 us where two workgroups share a compute unit (5 us for the tile that has one to itself), and what
+        // a piece takes beyond that window is added to the launch (128 x 128 tiles, K = 4096: 16 tail tiles in 8
+        // pieces add 7 us of a piece's 30, 65 in 3 add 57 of 77, 128 in 2 add 102 of 114; 2048 x 11008 x 4096:
+        // 88 tail tiles of 256 x 256 in two pieces add 450 us to the 920 us of the whole round, a piece taking 459)
         const double t_piece = tile_us(vm, bm, bn, (double)units_per_piece * bk, true);
         const double second_pass = 6.0 + (double)(S + 1) * (double)t.tail * bm * bn * 4.0 / 5.0e6;
-        range_benefit = t_full - (second_pass + (bm * bn >= 256 * 256 ? 0.85 : 0.7) * t_piece);
+        const double added = std::max(0.25 * t_piece, t_piece - (bm * bn >= 256 * 256 ? 5.0 : 20.0));
+        range_benefit = t_full - (second_pass + added);
     }
     if (quad_benefit > 0.0 && quad_benefit >= range_benefit) {
         t.pieces = subs;
@@ -399,6 +403,10 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             // a matrix shorter than the tile cannot move its edge tiles inside: every tile then runs
             // the masked loads, which cost about a quarter more
             if (M < sh.bm || N < sh.bn) cost *= 1.25;
+            // Measured: the 64 x 64 tiles sustain the `multi` rate while only some compute units hold two of them
+            // (256 x 5120 x 5120, 320 tiles: 99 us, the best tile); with two on every compute unit they fall 4 %
+            // behind it (512 x 4096 x 11008, 512 tiles: 320 us against 308 for 64 x 128 tiles; 4096^3: 979 us).
+            if ((c.id == TB64 || c.id == T64) && wgs > 320) cost *= 1.0 + 0.04 * std::min(1.0, (double)(wgs - 320) / 192.0);
             // Measured on ten large shapes: while both operands fit the 256 MB memory-side cache with room to spare,
             // several rounds of 128 x 128 tiles, two workgroups to a compute unit, overlap their epilogues and
             // the drain of C with each other's slab loops and come out 0.4-1.8 % ahead of rounds of the 256-wide
@@ -413,7 +421,7 @@ Choice evaluate_candidates(const Hooks &hooks, int forced_tile, int forced_split
             const double hbm_us = 4.0 * (double)batch * ((double)M * K + (double)K * N) / bytes_per_us;
             // (between candidates that are all bound by the memory interface, the one with less matrix work
             // and fewer fixed costs is still the faster: a small share of the compute cost breaks the tie)
-            cost = std::max(cost, hbm_us) + 0.02 * cost;
+            cost = std::max(cost, hbm_us + 0.02 * cost);
             if (S > 1) cost += 7.5 + (double)(S + 1) * M * N * 4.0 / 5.0e6;   // second pass: launch + traffic at 5 TB/s
             // the strip runs beside the tiles, most of it while they wait for their first slab, which it delays
             // (measured against the same product without the last columns: 1.3 us at K = 1000), so it pays where
