@@ -339,7 +339,22 @@ AUDIT_FIXED = [(1024, 1024, 1024, False), (1000, 1030, 999, False), (2048, 2048,
 NUM_TILES = 13
 
 
-def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.0):
+def audit_large_shapes():
+    """The shapes of `--audit --audit-set large`: squares around whole rounds of tiles, and M in 256..8192 against
+    transformer-like N x K with B stored N x K (at most 0.5 TFLOP each, so that the set runs in a few minutes)."""
+    shapes = [(n, n, k, False) for n, k in ((4352, 4096), (4224, 4096), (2176, 2048), (4608, 4096), (3072, 3072), (5120, 5120),
+                                            (3000, 3000), (2560, 2560), (3584, 3584), (6144, 6144), (1280, 1280), (1408, 1408),
+                                            (1792, 1792), (2304, 2304), (2816, 2816), (3328, 3328))]
+    for N, K in ((4096, 4096), (11008, 4096), (4096, 11008), (14336, 4096), (4096, 14336), (12288, 4096), (5120, 5120),
+                 (13824, 5120), (5120, 13824), (8192, 8192), (28672, 8192), (8192, 28672), (6144, 4096), (1024, 4096),
+                 (4096, 1024)):
+        for M in (256, 512, 1024, 2048, 4096, 8192):
+            if 2.0 * M * N * K <= 5e11:
+                shapes.append((M, N, K, True))
+    return shapes
+
+
+def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.0, fixed=None):
     """Guard of the dispatch's cost model: for the fixed shapes above and seeded random ones (M, N log-uniform in
     32..4096, K in 64..8192, either layout of B) the time of the dispatch's own choice against every tile forced
     in turn (each with the split the model picks for it).  A shape fails when the choice takes more than
@@ -347,8 +362,9 @@ def audit(torch, binding, random_shapes=26, seed=11, tolerance=1.10, slack_us=1.
     import math
     import random
     rng = random.Random(seed)
-    shapes = list(AUDIT_FIXED)
-    while len(shapes) < len(AUDIT_FIXED) + random_shapes:
+    shapes = list(AUDIT_FIXED if fixed is None else fixed)
+    n_fixed = len(shapes)
+    while len(shapes) < n_fixed + random_shapes:
         M, N, K = (int(round(math.exp(rng.uniform(math.log(a), math.log(b))))) for a, b in ((32, 4096), (32, 4096), (64, 8192)))
         if 2.0 * M * N * K <= 4e10:
             shapes.append((M, N, K, rng.random() < 0.5))
@@ -634,6 +650,9 @@ def main() -> int:
     ap.add_argument("--audit", action="store_true",
                     help="guard of the cost model: on about 36 shapes, the dispatch's choice against every tile forced in "
                          "turn; one JSON object; exit status 3 if a choice is more than 10 %% and 1 us behind the best tile")
+    ap.add_argument("--audit-set", default="default", choices=["default", "large"],
+                    help="with --audit: the default shapes, or 89 large ones (squares around whole rounds of tiles, "
+                         "transformer-like products with B stored N x K)")
     ap.add_argument("--timeline", action="store_true",
                     help="per-phase breakdown of product launches from the measurement build of the library "
                          "(libgemmf32_timeline.so, built with -DGEMMF32_TIMELINE; built here if missing); one JSON object")
@@ -686,7 +705,9 @@ def main() -> int:
         return 0
 
     if args.audit:
-        res = audit(torch, binding)
+        res = (audit(torch, binding, random_shapes=0, fixed=audit_large_shapes()) if args.audit_set == "large"
+               else audit(torch, binding))
+        res["set"] = args.audit_set
         print(json.dumps(res))
         return 3 if res["failures"] else 0
 
