@@ -924,7 +924,12 @@ __device__ __forceinline__ void gemm_tile(const KArgs &p, float *lds, const int 
         } else {
             typedef unsigned u4 __attribute__((ext_vector_type(4)));
             if constexpr (ADD_OLD) o += beta * __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(c_rsrc, (int)off, row_bytes, 0));
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, o), c_rsrc, (int)off, row_bytes, 0);
+            // A 16-byte store takes the row offset in its vector offset.  With the row offset in the scalar
+            // offset the compiler leaves no wait state between the store and the next write of its four data
+            // registers (that form is documented as needing none; with a constant scalar offset it inserts them),
+            // and the lanes read last then stored the next row's value in their fourth dword: seen with
+            // 128 x 256 tiles, two workgroups to a compute unit, in results that changed from run to run.
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, o), c_rsrc, (int)off + row_bytes, 0, 0);
         }
     };
     if constexpr (T::WGK > 1) {

@@ -699,6 +699,31 @@ def test_strip_rows_per_wave_and_pause(rows, transB):
         binding.set_test_hooks()
 
 
+@pytest.mark.parametrize("tile,split", [("t128x256", 3), ("t128x256", 6), ("t256", 3), ("t256x128", 3)])
+def test_wide_tiles_two_to_a_compute_unit_stores_exact(tile, split):
+    """Tiles 256 columns wide store 16 bytes per lane and row.  With more workgroups than compute units, two of
+    them share one and their epilogues run against each other's loads: the stores then have to be complete before
+    their data registers are written again (the 128 x 256 tile once stored the next row's value in the fourth dword
+    of some lanes, differently from run to run).  Integer operands, K split so that every tile goes through the
+    workspace, N not a multiple of the tile: exact, on three launches in a row."""
+    M, N, K = 2798, 1582, 889
+    try:
+        binding.set_test_hooks(force_tile=TILES[tile], force_split=split)
+        name = binding.variant_name(M, N, K)
+        print(f"{tile} split={split} {name}", flush=True)
+        assert f"splitk{split}" in name, name
+        A = synth.small_ints((M, K), 760, synth.TENSOR_A)
+        B = synth.small_ints((K, N), 760, synth.TENSOR_B)
+        ref = oracle.gemm_f32(A, B, nthreads=NTHREADS)
+        dA, dB = dev(A), dev(B)
+        for launch in range(3):
+            dC = torch.full((M, N), float("nan"), device="cuda")
+            binding.gemm_f32(dA, dB, dC)
+            assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref), f"launch {launch}"
+    finally:
+        binding.set_test_hooks()
+
+
 def test_strip_uniform_operands_scalings_and_switch():
     """The ragged workload's own shape takes the strip (6 columns behind 16 whole tile columns): within
     tolerance on U(-1,1) operands, the same bits on every launch, alpha and beta applied, and the same product
