@@ -6,7 +6,8 @@ every partial sum is an integer (or a multiple of 1/2) far below 2^24, so any su
 exact and the comparison is bit for bit.  The shape classes aim at the dispatch's special cases:
 one short dimension (the 32-wide tiles and the tile whose waves share the slabs), small outputs
 with long K (K splits), tile counts a little above a multiple of 256 (split last round, with and
-without 32 x 32 blocks), and plain mid-size products with ragged edges."""
+without 32 x 32 blocks), plain mid-size products with ragged edges, and outputs of several hundred to a
+thousand tiles with a short K, where workgroups share compute units and their epilogues overlap."""
 from __future__ import annotations
 
 import os
@@ -37,12 +38,15 @@ def _draw(rng, cls):
         return r(1, 300), r(1, 300), r(2000, 20000)
     if cls == "second_round":
         return r(1000, 1300), r(1000, 1300), r(1, 700)
+    if cls == "co_resident":
+        return r(1500, 4000), r(1500, 4000), r(20, 900)
     return r(1, 1500), r(1, 1500), r(1, 900)
 
 
-@pytest.mark.parametrize("cls", ["short_m", "short_n", "long_k", "second_round", "plain"])
+@pytest.mark.parametrize("cls", ["short_m", "short_n", "long_k", "second_round", "plain", "co_resident"])
 def test_random_shapes_bit_exact(cls):
-    rng = np.random.default_rng({"short_m": 11, "short_n": 12, "long_k": 13, "second_round": 14, "plain": 15}[cls])
+    rng = np.random.default_rng({"short_m": 11, "short_n": 12, "long_k": 13, "second_round": 14, "plain": 15,
+                                 "co_resident": 16}[cls])
     tiles = [None, None, None] + list(TILES.values())
     try:
         for idx in range(CASES_PER_CLASS):
