@@ -54,6 +54,17 @@ def test_host_only_queries():
     assert "/a4" in binding.variant_name(1000, 1030, 999)
 
 
+def test_large_shapes_with_a_partly_filled_last_round_keep_their_measured_tiles():
+    """Choices the timing audit of large shapes established (the split of a last round is priced by what its pieces
+    take beyond the window in which whole tiles end; a tile alone on its compute unit gets no such window): the
+    256 x 256 tile with 88 tail tiles in two pieces took 1377 us on the first shape, the 128 x 128 tile 1245."""
+    assert binding.variant_name(2048, 11008, 4096, transB=True) == "t128x128x16/nt/a16/tail96x2"
+    assert binding.variant_name(6144, 6144, 6144) == "t128x128x16/nn/a16"
+    assert binding.variant_name(4352, 4352, 4096).startswith("t64x128x32/nn/a16")     # first of the two orientations
+    assert binding.variant_name(4224, 4224, 4096) == "t128x128x16/nn/a16/tail65x3"
+    assert binding.variant_name(512, 4096, 11008, transB=True).startswith("t64x128x32")   # not 512 co-resident 64 x 64 tiles
+
+
 def test_ladder_host_queries():
     assert binding.gemm_f32_ladder_levels() == 7
     names = [binding.gemm_f32_ladder_name(i) for i in range(7)]
